@@ -1,0 +1,285 @@
+"""CPU oracle for the MoE-layer forward.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, float64 statement of what one Mixture-of-Experts layer computes, written from
+the paper (HarMoEny, arXiv 2506.12417) and the textbook definitions it relies on.  Only the
+tests, the smoke check and the benchmark's cpu_baseline leg may call it; the product (the HIP
+library and its Python binding) never does, and this file shares no code with it.
+
+What follows which passage:
+
+  route_topk        section 2, "Mixture-of-Experts": the router gives every expert a value in
+                    (0,1) and the token goes to the k highest; Alg. 1 step 1 (m_expert).
+  permute           Alg. 1 step 4 and the initial schedule S_initial of step 3, collapsed to one
+                    GPU: tokens are grouped by their target expert (counts = the G=1 slice of
+                    S_initial).
+  expert_ffn        section 2 (two dense layers with an activation between) and section 4.4
+                    (the expert is x W1 W2 with W1: m x p, W2: p x m; no biases).
+  moe_layer         Alg. 1 steps 5-6 read as the result they must produce: each token's output is
+                    the gate-weighted sum of its k experts' FFN outputs, in the original token
+                    order (step 6, "reconstruct").  Computed per token straight from the
+                    definition, without the permutation, so a permutation mistake cannot cancel.
+  combine           Alg. 1 step 6 on already-permuted expert outputs.
+  rebalance         Alg. 2 (token rebalancing), taken step by step in the paper's notation.
+  token_threshold_q section 4.4, Eq. 1-4 and appendix B.
+
+Readings where the paper is silent (each listed in the design notes): the gate is a softmax over
+all E logits; selection is on the logits, descending, ties to the lower expert index; with
+renorm=1 the k gate values are divided by their sum; rows of one expert keep ascending
+assignment order (assignment id a = t*k + j); expert FFNs have no bias.
+
+bf16 tensors arrive as uint16 bit patterns and are widened exactly to float64; nothing is
+rounded on the way except where a function says so.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional, Sequence, Tuple
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------- number formats
+def to_f64(a: np.ndarray) -> np.ndarray:
+    """Exact widening: uint16 is read as bfloat16 bits, float32/float64 as they are."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """float64 -> nearest bfloat16 value (ties to even), returned as float64.  Only used by the
+    diagnostic mode of expert_ffn; not part of the layer's definition."""
+    f = np.asarray(a, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+# ----------------------------------------------------------------------------- step 1: routing
+def router_logits(x: np.ndarray, W_g: np.ndarray, b: Optional[np.ndarray]) -> np.ndarray:
+    """l[t,e] = b[e] + sum_i x[t,i] W_g[i,e], float64."""
+    l = to_f64(x) @ to_f64(W_g)
+    if b is not None:
+        l = l + to_f64(b)[None, :]
+    return l
+
+
+def route_topk(x: np.ndarray, W_g: np.ndarray, b: Optional[np.ndarray], k: int, renorm: int
+               ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Top-k gating (section 2).  Returns (expert_idx int32 [T,k] in descending score,
+    gate_w float32 [T,k], logits float64 [T,E]).
+
+    The value in (0,1) of each expert is softmax(l) over all E experts.  The k highest are
+    taken on the logits (softmax is monotone), ties going to the lower index.  renorm=1 divides
+    the k gate values by their sum; renorm=0 keeps the raw softmax values."""
+    l = router_logits(x, W_g, b)
+    T, E = l.shape
+    if not (1 <= k <= E):
+        raise ValueError("k out of range")
+    order = np.argsort(-l, axis=1, kind="stable")      # stable: equal logits keep index order
+    idx = order[:, :k]
+    p = np.exp(l - l.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    w = np.take_along_axis(p, idx, axis=1)
+    if renorm:
+        w = w / w.sum(axis=1, keepdims=True)
+    return idx.astype(np.int32), w.astype(np.float32), l
+
+
+def decision_gaps(logits: np.ndarray, k: int) -> np.ndarray:
+    """Per token, the smallest gap between consecutive sorted logits at ranks 1..k+1 (the k
+    comparisons that decide the top-k set and its order)."""
+    s = -np.sort(-logits, axis=1)
+    kk = min(k + 1, s.shape[1])
+    return (s[:, : kk - 1] - s[:, 1:kk]).min(axis=1)
+
+
+# ----------------------------------------------------------------------------- step 4: grouping
+def permute(expert_idx: np.ndarray, E: int) -> Dict[str, np.ndarray]:
+    """Group the A = T*k assignments by expert, keeping ascending assignment order inside each
+    expert (a stable counting sort written out from its definition):
+
+      counts[e]   = #{a : idx[a] = e}
+      offsets[0]  = 0, offsets[e+1] = offsets[e] + counts[e]
+      pos(a)      = offsets[idx[a]] + #{a' < a : idx[a'] = idx[a]}
+      perm[pos(a)] = a,  inv_perm[a] = pos(a)
+    """
+    flat = np.asarray(expert_idx, dtype=np.int64).reshape(-1)
+    A = flat.shape[0]
+    if A and (flat.min() < 0 or flat.max() >= E):
+        raise ValueError("expert id out of range")
+    counts = np.zeros(E, dtype=np.int64)
+    for a in range(A):
+        counts[flat[a]] += 1
+    offsets = np.zeros(E + 1, dtype=np.int64)
+    for e in range(E):
+        offsets[e + 1] = offsets[e] + counts[e]
+    seen = np.zeros(E, dtype=np.int64)
+    perm = np.empty(A, dtype=np.int64)
+    inv_perm = np.empty(A, dtype=np.int64)
+    for a in range(A):
+        e = flat[a]
+        pos = offsets[e] + seen[e]
+        seen[e] += 1
+        perm[pos] = a
+        inv_perm[a] = pos
+    return {"counts": counts.astype(np.int32), "offsets": offsets.astype(np.int32),
+            "perm": perm.astype(np.int32), "inv_perm": inv_perm.astype(np.int32)}
+
+
+def gather_rows(x: np.ndarray, perm: np.ndarray, k: int) -> np.ndarray:
+    """x_perm[r,:] = x[perm[r] div k, :] -- a bit copy, any dtype."""
+    return np.asarray(x)[np.asarray(perm, dtype=np.int64) // k]
+
+
+# ----------------------------------------------------------------------------- step 5: experts
+def silu(z: np.ndarray) -> np.ndarray:
+    return z / (1.0 + np.exp(-z))
+
+
+def expert_ffn(x_rows: np.ndarray, weights: Dict[str, np.ndarray], act: str,
+               h_bf16: bool = False) -> np.ndarray:
+    """One expert on a block of rows, float64 (section 4.4: x W1 W2, activation between).
+    act="relu":   y = max(0, x W1) W2           weights: W1 [d,F], W2 [F,d]
+    act="swiglu": y = (silu(x Wg) * (x Wu)) Wd  weights: Wg, Wu [d,F], Wd [F,d]
+    h_bf16=True rounds the hidden activations to bfloat16 before the second product; that is a
+    diagnostic that mimics a bf16 intermediate, not the definition."""
+    x = to_f64(x_rows)
+    if act == "relu":
+        h = np.maximum(x @ to_f64(weights["W1"]), 0.0)
+        w_out = weights["W2"]
+    elif act == "swiglu":
+        h = silu(x @ to_f64(weights["Wg"])) * (x @ to_f64(weights["Wu"]))
+        w_out = weights["Wd"]
+    else:
+        raise ValueError(act)
+    if h_bf16:
+        h = round_to_bf16(h)
+    return h @ to_f64(w_out)
+
+
+def _expert_slice(weights: Dict[str, np.ndarray], e: int) -> Dict[str, np.ndarray]:
+    return {n: a[e] for n, a in weights.items()}
+
+
+def moe_layer(x: np.ndarray, expert_idx: np.ndarray, gate_w: np.ndarray,
+              weights: Dict[str, np.ndarray], act: str,
+              shared: Optional[Dict[str, np.ndarray]] = None,
+              tokens: Optional[Sequence[int]] = None, h_bf16: bool = False) -> np.ndarray:
+    """y[t] = sum_{j<k} gate_w[t,j] * FFN_{idx[t,j]}(x[t])  (+ FFN_shared(x[t])),  float64.
+
+    `weights` holds stacked per-expert matrices ([E, ...]).  `tokens` restricts the computation
+    to a subset of token ids (rows of the result follow that order); the definition is per
+    token, so a subset needs nothing else."""
+    idx = np.asarray(expert_idx)
+    T, k = idx.shape
+    tok = np.arange(T) if tokens is None else np.asarray(tokens, dtype=np.int64)
+    xs = np.asarray(x)[tok]
+    idx_s = idx[tok]
+    w_s = np.asarray(gate_w, dtype=np.float64)[tok]
+    d = xs.shape[1]
+    y = np.zeros((tok.shape[0], d), dtype=np.float64)
+    E = next(iter(weights.values())).shape[0]
+    for j in range(k):                      # fixed j order, as in the sum above
+        for e in range(E):
+            rows = np.nonzero(idx_s[:, j] == e)[0]
+            if rows.size == 0:
+                continue
+            y[rows] += w_s[rows, j, None] * expert_ffn(xs[rows], _expert_slice(weights, e), act, h_bf16)
+    if shared is not None:
+        y += expert_ffn(xs, shared, "swiglu", h_bf16)
+    return y
+
+
+def grouped_ffn(x_perm: np.ndarray, offsets: np.ndarray, weights: Dict[str, np.ndarray],
+                act: str, h_bf16: bool = False) -> np.ndarray:
+    """Expert FFN on rows already grouped by expert: rows [offsets[e], offsets[e+1]) go through
+    expert e.  Used to check the grouped-FFN stage on its own."""
+    off = np.asarray(offsets, dtype=np.int64)
+    d_out = (weights["W2"] if act == "relu" else weights["Wd"]).shape[2]
+    y = np.zeros((x_perm.shape[0], d_out), dtype=np.float64)
+    for e in range(off.shape[0] - 1):
+        if off[e + 1] > off[e]:
+            y[off[e]:off[e + 1]] = expert_ffn(x_perm[off[e]:off[e + 1]], _expert_slice(weights, e), act, h_bf16)
+    return y
+
+
+# ----------------------------------------------------------------------------- step 6: combine
+def combine(y_perm: np.ndarray, inv_perm: np.ndarray, gate_w: np.ndarray,
+            shared: Optional[np.ndarray] = None) -> np.ndarray:
+    """y[t] = sum_{j<k} gate_w[t,j] * y_perm[inv_perm[t*k+j]] (+ shared[t]), float64."""
+    gw = np.asarray(gate_w, dtype=np.float64)
+    T, k = gw.shape
+    yp = to_f64(y_perm)
+    ip = np.asarray(inv_perm, dtype=np.int64).reshape(T, k)
+    y = np.zeros((T, yp.shape[1]), dtype=np.float64)
+    for j in range(k):
+        y += gw[:, j, None] * yp[ip[:, j]]
+    if shared is not None:
+        y += to_f64(shared)
+    return y
+
+
+# ----------------------------------------------------------------------------- Alg. 2
+def initial_assign(m_all: np.ndarray, home: Sequence[int], G: int) -> np.ndarray:
+    """S_initial[g_from, e, g_to] (Alg. 1 step 3): every token of expert e coming from GPU
+    g_from goes to the GPU that houses e.  m_all[g_from, e] = token counts, home[e] = GPU."""
+    m_all = np.asarray(m_all, dtype=np.int64)
+    G_src, E = m_all.shape
+    S = np.zeros((G_src, E, G), dtype=np.int64)
+    for g in range(G_src):
+        for e in range(E):
+            S[g, e, home[e]] = m_all[g, e]
+    return S
+
+
+def rebalance(S_initial: np.ndarray, q: int, max_iters: int = 1_000_000) -> np.ndarray:
+    """Token rebalancing, Alg. 2.  S[g_from, e, g_to] int64; q >= 1 is the transfer threshold.
+    argmax/argmin take the lowest index among equals (numpy's and the usual tensor-library
+    convention)."""
+    if q < 1:
+        raise ValueError("q must be >= 1 (with q = 0 the loop can move zero tokens forever)")
+    S = np.array(S_initial, dtype=np.int64, copy=True)
+    G = S.shape[2]
+    t_avg = int(S.sum()) // G
+    t_g = S.sum(axis=(0, 1))
+    for _ in range(max_iters):
+        if not np.any(t_g > t_avg):
+            break
+        g_max = int(np.argmax(t_g))
+        g_from = int(np.argmax(S[:, :, g_max].sum(axis=1)))
+        e_max = int(np.argmax(S[g_from, :, g_max]))
+        t_move = int(S[g_from, e_max, g_max])
+        if t_move < q:
+            return S
+        g_min = int(np.argmin(t_g))
+        if g_min == g_max or t_g[g_min] + q > t_avg:
+            return S
+        t_s = min(t_move, t_avg - int(t_g[g_min]))
+        S[g_from, e_max, g_max] -= t_s
+        S[g_from, e_max, g_min] += t_s
+        t_g[g_max] -= t_s
+        t_g[g_min] += t_s
+    return S
+
+
+# ----------------------------------------------------------------------------- threshold q
+def expert_bytes(m: int, p: int, d_type: int) -> int:
+    """|E| = (mp + pm) d_type, Eq. 2."""
+    return (m * p + p * m) * d_type
+
+
+def expert_flops(q: int, m: int, p: int) -> int:
+    """|O| = q p (2m-1) + q m (2p-1), Eq. 3."""
+    return q * p * (2 * m - 1) + q * m * (2 * p - 1)
+
+
+def token_threshold_q(phi: float, d_type: int, beta: float) -> float:
+    """Eq. 4: q > phi d_type / (2 beta)."""
+    return phi * d_type / (2.0 * beta)
+
+
+def token_threshold_q_exact(phi: float, d_type: int, beta: float, m: int, p: int) -> float:
+    """The bound before the small terms are dropped (appendix B, third line): the q at which
+    |O|/phi = |E|/beta."""
+    return (expert_bytes(m, p, d_type) / beta) * phi / (p * (2 * m - 1) + m * (2 * p - 1))

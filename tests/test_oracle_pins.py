@@ -1,0 +1,391 @@
+"""Pins for the CPU oracle: each check ties an oracle function to something other than itself --
+a value the paper prints, a hand-worked example, a closed form, a brute-force loop on tiny
+inputs, or a library routine that is the textbook form of the same thing.  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import moe_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            out[key] = [int(v) for v in vals]
+    return out
+
+
+# ------------------------------------------------------------------------------------ formats
+def test_bf16_widening_exact_values():
+    # 0x3F80 = 1.0, 0xC000 = -2.0, 0x3FC0 = 1.5, 0x0000 = 0, 0x7F80 = +inf (bfloat16 format)
+    bits = np.array([0x3F80, 0xC000, 0x3FC0, 0x0000, 0x7F80], dtype=np.uint16)
+    assert O.to_f64(bits).tolist() == [1.0, -2.0, 1.5, 0.0, float("inf")]
+
+
+def test_round_to_bf16_ties_to_even():
+    # bf16 has 8 significand bits: spacing at 1.0 is 2^-7.  1 + 2^-8 is a tie -> even (1.0);
+    # 1 + 3*2^-8 is a tie -> even (1 + 2^-6); just above a tie rounds up.
+    assert O.round_to_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert O.round_to_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    assert O.round_to_bf16(np.array([1.0 + 2.0 ** -8 + 2.0 ** -20]))[0] == 1.0 + 2.0 ** -7
+    assert O.round_to_bf16(np.array([-3.0]))[0] == -3.0
+
+
+# ------------------------------------------------------------------------------------ routing
+def _route_brute(x, Wg, b, k, renorm):
+    """Pure-Python loops: logits by explicit sums, full sort of (-logit, index) pairs, softmax
+    with math.exp."""
+    T, d = x.shape
+    E = Wg.shape[1]
+    idx, w = [], []
+    for t in range(T):
+        l = [math.fsum(float(x[t, i]) * float(Wg[i, e]) for i in range(d)) + float(b[e]) for e in range(E)]
+        order = sorted(range(E), key=lambda e: (-l[e], e))
+        m = max(l)
+        ex = [math.exp(v - m) for v in l]
+        s = math.fsum(ex)
+        p = [v / s for v in ex]
+        sel = order[:k]
+        ws = [p[e] for e in sel]
+        if renorm:
+            tot = math.fsum(ws)
+            ws = [v / tot for v in ws]
+        idx.append(sel)
+        w.append(ws)
+    return np.array(idx), np.array(w)
+
+
+@pytest.mark.parametrize("k,renorm", [(1, 0), (2, 1), (3, 0), (5, 1)])
+def test_route_matches_brute_force(k, renorm):
+    r = np.random.default_rng(7)
+    T, d, E = 48, 12, 5
+    x = r.standard_normal((T, d)).astype(np.float32)
+    Wg = r.standard_normal((d, E)).astype(np.float32)
+    b = r.standard_normal(E).astype(np.float32)
+    idx, w, _ = O.route_topk(x, Wg, b, k, renorm)
+    bi, bw = _route_brute(x, Wg, b, k, renorm)
+    assert np.array_equal(idx, bi)
+    assert np.allclose(w, bw, rtol=0, atol=1e-7)
+
+
+def test_route_one_hot_tokens_read_rows_of_Wg():
+    # x = e_i picks row i of W_g, so the logits are known by construction (catches a transposed
+    # operand: W_g is d x E with d != E and distinct rows/columns).
+    d, E = 6, 4
+    Wg = np.arange(d * E, dtype=np.float32).reshape(d, E)
+    Wg[:, [0, 3]] = Wg[:, [3, 0]]          # per row: col 0 largest, then 2, 1, 3
+    x = np.eye(d, dtype=np.float32)
+    idx, w, l = O.route_topk(x, Wg, None, 2, 1)
+    assert np.array_equal(l, Wg.astype(np.float64))
+    assert np.array_equal(idx, np.tile([0, 2], (d, 1)))
+    # renormalised pair = softmax over the two selected logits: gap is 1 -> 1/(1+e^-1)
+    assert np.allclose(w[:, 0], 1.0 / (1.0 + math.exp(-1.0)), atol=1e-7)
+    assert np.allclose(w.sum(axis=1), 1.0, atol=1e-6)
+
+
+def test_route_bias_is_added_per_expert_and_dominant_bias_wins():
+    r = np.random.default_rng(3)
+    x = r.standard_normal((64, 16)).astype(np.float32)
+    Wg = (r.standard_normal((16, 8)) / 4).astype(np.float32)
+    b = np.zeros(8, dtype=np.float32)
+    b[5] = 30.0
+    idx, w, l = O.route_topk(x, Wg, b, 2, 0)
+    assert np.all(idx[:, 0] == 5)
+    assert np.all(w[:, 0] > 0.999999)
+    assert np.allclose(l[:, 5] - (x.astype(np.float64) @ Wg.astype(np.float64))[:, 5], 30.0)
+
+
+def test_route_ties_go_to_lower_index_and_k_equals_E_is_full_softmax():
+    x = np.ones((3, 4), dtype=np.float32)
+    Wg = np.zeros((4, 6), dtype=np.float32)          # all logits equal
+    idx, w, _ = O.route_topk(x, Wg, None, 4, 0)
+    assert np.array_equal(idx, np.tile(np.arange(4), (3, 1)))
+    assert np.allclose(w, 1.0 / 6.0)
+    r = np.random.default_rng(11)
+    x = r.standard_normal((20, 9)).astype(np.float32)
+    Wg = r.standard_normal((9, 7)).astype(np.float32)
+    idx, w, l = O.route_topk(x, Wg, None, 7, 0)
+    assert np.allclose(w.sum(axis=1), 1.0, atol=1e-6)            # k = E: whole softmax
+    assert all(sorted(row) == list(range(7)) for row in idx.tolist())
+    assert np.all(np.diff(np.take_along_axis(l, idx.astype(np.int64), 1), axis=1) <= 0)   # descending
+    # renormalised weights are the softmax over the k selected logits alone (closed form)
+    idx3, w3, l3 = O.route_topk(x, Wg, None, 3, 1)
+    sel = np.take_along_axis(l3, idx3.astype(np.int64), 1)
+    ref = np.exp(sel - sel.max(1, keepdims=True))
+    ref /= ref.sum(1, keepdims=True)
+    assert np.allclose(w3, ref, atol=1e-7)
+
+
+def test_route_uniform_router_loads_within_multinomial_bounds():
+    r = np.random.default_rng(5)
+    T, d, E = 8192, 64, 16
+    x = r.standard_normal((T, d)).astype(np.float32)
+    Wg = (r.standard_normal((d, E)) / 8).astype(np.float32)
+    idx, _, _ = O.route_topk(x, Wg, None, 1, 0)
+    counts = np.bincount(idx[:, 0], minlength=E)
+    # loads are not exactly multinomial(1/E) (column norms differ), so allow a wide band
+    assert counts.sum() == T and counts.min() > 0.5 * T / E and counts.max() < 1.6 * T / E
+
+
+def test_decision_gaps():
+    l = np.array([[3.0, 1.0, 2.5, -1.0], [0.0, 0.0, 5.0, 4.0]])
+    assert np.allclose(O.decision_gaps(l, 1), [0.5, 1.0])
+    assert np.allclose(O.decision_gaps(l, 2), [0.5, 1.0])
+    assert np.allclose(O.decision_gaps(l, 3), [0.5, 0.0])
+
+
+# ------------------------------------------------------------------------------------ permute
+@pytest.mark.parametrize("T,k,E", [(1, 1, 1), (37, 2, 5), (200, 4, 9), (64, 1, 130)])
+def test_permute_is_the_stable_counting_sort(T, k, E):
+    r = np.random.default_rng(T + k + E)
+    idx = r.integers(0, E, size=(T, k)).astype(np.int32)
+    if E >= 3:
+        idx[idx == 1] = 2                               # an empty expert
+    p = O.permute(idx, E)
+    flat = idx.reshape(-1)
+    A = T * k
+    assert np.array_equal(p["counts"], np.bincount(flat, minlength=E))
+    assert np.array_equal(p["offsets"], np.concatenate([[0], np.cumsum(np.bincount(flat, minlength=E))]))
+    assert np.array_equal(p["perm"], np.argsort(flat, kind="stable"))
+    assert p["counts"].sum() == A and p["offsets"][-1] == A
+    assert sorted(p["perm"].tolist()) == list(range(A))                  # bijection
+    assert np.array_equal(p["inv_perm"][p["perm"]], np.arange(A))
+    assert np.all(np.diff(flat[p["perm"]]) >= 0)                         # grouped by expert
+    for e in range(E):                                                    # ascending inside an expert
+        seg = p["perm"][p["offsets"][e]:p["offsets"][e + 1]]
+        assert np.all(np.diff(seg) > 0)
+
+
+def test_permute_hand_example_and_empty():
+    # assignments (t,j): experts 2,0 | 1,2 | 0,2  -> flat [2,0,1,2,0,2]
+    p = O.permute(np.array([[2, 0], [1, 2], [0, 2]]), 3)
+    assert p["counts"].tolist() == [2, 1, 3]
+    assert p["offsets"].tolist() == [0, 2, 3, 6]
+    assert p["perm"].tolist() == [1, 4, 2, 0, 3, 5]
+    assert p["inv_perm"].tolist() == [3, 0, 2, 4, 1, 5]
+    x = np.arange(6, dtype=np.float32).reshape(3, 2)
+    assert O.gather_rows(x, p["perm"], 2).tolist() == [[0, 1], [4, 5], [2, 3], [0, 1], [2, 3], [4, 5]]
+    z = O.permute(np.zeros((0, 2), dtype=np.int32), 4)
+    assert z["counts"].tolist() == [0, 0, 0, 0] and z["perm"].size == 0
+    with pytest.raises(ValueError):
+        O.permute(np.array([[4]]), 4)
+
+
+# ------------------------------------------------------------------------------------ expert FFN
+def test_ffn_hand_worked_relu():
+    # x=[1,2]; W1=[[1,-1],[0,2]] -> xW1=[1,3]; W1b=[[1,-1],[-2,0]] -> [-3,-1] -> relu 0
+    x = np.array([[1.0, 2.0]])
+    W2 = np.array([[1.0, 0.0, 2.0], [2.0, 1.0, 0.0]])          # F=2 x d_out=3
+    y = O.expert_ffn(x, {"W1": np.array([[1.0, -1.0], [0.0, 2.0]]), "W2": W2}, "relu")
+    assert y.tolist() == [[7.0, 3.0, 2.0]]
+    y0 = O.expert_ffn(x, {"W1": np.array([[1.0, -1.0], [-2.0, 0.0]]), "W2": W2}, "relu")
+    assert y0.tolist() == [[0.0, 0.0, 0.0]]
+
+
+def test_ffn_hand_worked_swiglu():
+    # silu(ln 3) = ln3 * 3/4 ; silu(0) = 0 ; silu(-ln 3) = -ln3 / 4
+    ln3 = math.log(3.0)
+    x = np.array([[1.0, 1.0]])
+    Wg = np.array([[ln3, 0.0, -ln3], [0.0, 0.0, 0.0]])
+    Wu = np.array([[2.0, 5.0, 4.0], [0.0, 1.0, 0.0]])          # x Wu = [2, 6, 4]
+    Wd = np.array([[1.0, 0.0], [1.0, 1.0], [0.0, 2.0]])
+    y = O.expert_ffn(x, {"Wg": Wg, "Wu": Wu, "Wd": Wd}, "swiglu")
+    h = [ln3 * 0.75 * 2.0, 0.0, -ln3 * 0.25 * 4.0]
+    assert np.allclose(y, [[h[0] + h[1], h[1] + 2 * h[2]]], atol=1e-15)
+
+
+def test_ffn_brute_force_triple_loop():
+    r = np.random.default_rng(21)
+    n, d, F = 5, 4, 6
+    x = r.standard_normal((n, d))
+    W1, W2 = r.standard_normal((d, F)), r.standard_normal((F, d))
+    Wu = r.standard_normal((d, F))
+    for act in ("relu", "swiglu"):
+        ref = np.zeros((n, d))
+        for i in range(n):
+            h = []
+            for f in range(F):
+                a = math.fsum(x[i, c] * W1[c, f] for c in range(d))
+                if act == "relu":
+                    h.append(max(a, 0.0))
+                else:
+                    u = math.fsum(x[i, c] * Wu[c, f] for c in range(d))
+                    h.append(a / (1.0 + math.exp(-a)) * u)
+            for c in range(d):
+                ref[i, c] = math.fsum(h[f] * W2[f, c] for f in range(F))
+        w = {"W1": W1, "W2": W2} if act == "relu" else {"Wg": W1, "Wu": Wu, "Wd": W2}
+        assert np.allclose(O.expert_ffn(x, w, act), ref, atol=1e-13)
+
+
+def test_ffn_relu_power_of_two_homogeneity_and_bf16_mode():
+    r = np.random.default_rng(2)
+    x = r.standard_normal((7, 8))
+    w = {"W1": r.standard_normal((8, 16)), "W2": r.standard_normal((16, 8))}
+    assert np.array_equal(O.expert_ffn(2 * x, w, "relu"), 2 * O.expert_ffn(x, w, "relu"))
+    a, b = O.expert_ffn(x, w, "relu"), O.expert_ffn(x, w, "relu", h_bf16=True)
+    rms = np.sqrt(np.mean(a ** 2))
+    assert 0 < np.abs(a - b).max() < 2e-2 * rms          # differs, by about bf16 rounding of h
+
+
+# ------------------------------------------------------------------------------------ layer
+def _scaling_experts(E, d, c):
+    """Expert e multiplies non-negative inputs by c[e]: W1 = I, W2 = c[e] I (ReLU)."""
+    W1 = np.tile(np.eye(d), (E, 1, 1))
+    W2 = np.stack([c[e] * np.eye(d) for e in range(E)])
+    return {"W1": W1, "W2": W2}
+
+
+def test_layer_closed_form_with_scaling_experts():
+    r = np.random.default_rng(9)
+    T, d, E, k = 30, 4, 5, 2
+    x = np.abs(r.standard_normal((T, d)))
+    c = np.array([1.0, 2.0, 4.0, 8.0, 16.0])
+    idx = np.stack([r.permutation(E)[:k] for _ in range(T)])
+    gw = r.random((T, k))
+    y = O.moe_layer(x, idx, gw, _scaling_experts(E, d, c), "relu")
+    ref = (gw * c[idx]).sum(axis=1, keepdims=True) * x
+    assert np.allclose(y, ref, atol=1e-13)
+    # subset of tokens = the same rows
+    sub = [3, 29, 0, 7]
+    assert np.allclose(O.moe_layer(x, idx, gw, _scaling_experts(E, d, c), "relu", tokens=sub), ref[sub], atol=1e-13)
+
+
+def test_layer_identical_experts_equals_dense_ffn_and_shared_adds():
+    r = np.random.default_rng(10)
+    T, d, F, E, k = 40, 6, 10, 4, 2
+    x = r.standard_normal((T, d)).astype(np.float32)
+    one = {"Wg": r.standard_normal((d, F)), "Wu": r.standard_normal((d, F)), "Wd": r.standard_normal((F, d))}
+    w = {n: np.tile(a, (E, 1, 1)) for n, a in one.items()}
+    Wg = r.standard_normal((d, E)).astype(np.float32)
+    idx, gw, _ = O.route_topk(x, Wg, None, k, 1)
+    dense = O.expert_ffn(x, one, "swiglu")
+    y = O.moe_layer(x, idx, gw, w, "swiglu")
+    assert np.allclose(y, dense, atol=1e-6 * np.abs(dense).max())       # weights sum to 1 (fp32)
+    sh = {"Wg": r.standard_normal((d, 3)), "Wu": r.standard_normal((d, 3)), "Wd": r.standard_normal((3, d))}
+    y2 = O.moe_layer(x, idx, gw, w, "swiglu", shared=sh)
+    assert np.allclose(y2 - y, O.expert_ffn(x, sh, "swiglu"), atol=1e-12)
+
+
+def test_layer_uniform_routing_equals_per_token_dense_loop():
+    r = np.random.default_rng(12)
+    T, d, F, E = 33, 5, 7, 4
+    x = r.standard_normal((T, d))
+    w = {"W1": r.standard_normal((E, d, F)), "W2": r.standard_normal((E, F, d))}
+    idx = (np.arange(T) % E).reshape(T, 1)               # round-robin: every expert the same load
+    gw = np.ones((T, 1))
+    y = O.moe_layer(x, idx, gw, w, "relu")
+    for t in range(T):
+        e = t % E
+        ref = np.maximum(x[t] @ w["W1"][e], 0) @ w["W2"][e]
+        assert np.allclose(y[t], ref, atol=1e-13)
+
+
+def test_direct_and_permuted_forms_agree():
+    r = np.random.default_rng(13)
+    T, d, F, E, k = 50, 6, 8, 7, 3
+    x = r.standard_normal((T, d)).astype(np.float32)
+    w = {"Wg": r.standard_normal((E, d, F)), "Wu": r.standard_normal((E, d, F)), "Wd": r.standard_normal((E, F, d))}
+    idx, gw, _ = O.route_topk(x, r.standard_normal((d, E)).astype(np.float32), None, k, 1)
+    p = O.permute(idx, E)
+    xp = O.gather_rows(x, p["perm"], k)
+    yp = O.grouped_ffn(xp, p["offsets"], w, "swiglu")
+    y_perm_form = O.combine(yp, p["inv_perm"], gw)
+    y_direct = O.moe_layer(x, idx, gw, w, "swiglu")
+    assert np.abs(y_perm_form - y_direct).max() < 1e-12 * max(1.0, np.abs(y_direct).max())
+
+
+def test_combine_identity_and_weights():
+    r = np.random.default_rng(14)
+    T, d, E = 25, 3, 4
+    x = r.standard_normal((T, d)).astype(np.float32)
+    idx = r.integers(0, E, size=(T, 1))
+    p = O.permute(idx, E)
+    xp = O.gather_rows(x, p["perm"], 1)
+    assert np.array_equal(O.combine(xp, p["inv_perm"], np.ones((T, 1))), x.astype(np.float64))
+    # k = 2, hand-checkable: y[t] = w0*row + w1*row
+    yp = np.array([[1.0], [10.0], [100.0], [1000.0]])
+    inv = np.array([2, 0, 3, 1])                 # token0 -> rows 2,0 ; token1 -> rows 3,1
+    gw = np.array([[0.5, 0.25], [2.0, 1.0]])
+    sh = np.array([[0.125], [0.0]])
+    assert O.combine(yp, inv, gw, sh).tolist() == [[50.0 + 0.25 + 0.125], [2000.0 + 10.0]]
+
+
+# ------------------------------------------------------------------------------------ Alg. 2
+def test_rebalance_paper_example():
+    g = _golden("alg2_example.txt")
+    m_all = np.array([g["m_all_row0"], g["m_all_row1"], g["m_all_row2"]])
+    S0 = O.initial_assign(m_all, g["home"], 3)
+    assert S0.sum(axis=(0, 1)).tolist() == g["naive_loads"]
+    S = O.rebalance(S0, g["q"][0])
+    assert S.sum(axis=(0, 1)).tolist() == g["balanced_loads"]
+    assert np.array_equal(S.sum(axis=2), m_all)                  # nothing lost, nothing re-routed to another expert
+    assert S[:, 2, 0].sum() == g["expert2_tokens_on_gpu0"][0]
+    assert S[:, 2, 1].sum() == g["expert2_tokens_on_gpu1"][0]
+    assert S[:, 0, 1:].sum() == 0 and S[:, 1, 0].sum() == 0 and S[:, 1, 2].sum() == 0
+
+
+def test_rebalance_threshold_and_degenerate_cases():
+    g = _golden("alg2_example.txt")
+    m_all = np.array([g["m_all_row0"], g["m_all_row1"], g["m_all_row2"]])
+    S0 = O.initial_assign(m_all, g["home"], 3)
+    # the largest (source, expert) block going to GPU 2 holds 4 tokens: q = 5 forbids any move
+    assert np.array_equal(O.rebalance(S0, 5), S0)
+    # q = 4: first block (4 tokens) may move, but GPU 0 has room for 3 < q -> no feasible transfer
+    assert np.array_equal(O.rebalance(S0, 4), S0)
+    # q = 3: the first move (3 tokens) happens, the second (1 token) does not
+    assert O.rebalance(S0, 3).sum(axis=(0, 1)).tolist() == [5, 4, 6]
+    # one GPU: nothing to do
+    S1 = O.initial_assign(np.array([[3, 4]]), [0, 0], 1)
+    assert np.array_equal(O.rebalance(S1, 1), S1)
+    with pytest.raises(ValueError):
+        O.rebalance(S0, 0)
+
+
+def test_rebalance_invariants_random():
+    r = np.random.default_rng(15)
+    for trial in range(60):
+        G = int(r.integers(2, 9))
+        E = int(r.integers(G, 40))
+        q = int(r.integers(1, 20))
+        m_all = (r.zipf(1.6, size=(G, E)) % 200).astype(np.int64)
+        home = [e * G // E for e in range(E)]                 # contiguous blocks of experts per GPU
+        S0 = O.initial_assign(m_all, home, G)
+        S = O.rebalance(S0, q)
+        assert np.array_equal(S.sum(axis=2), m_all) and S.min() >= 0
+        t0, t1 = S0.sum(axis=(0, 1)), S.sum(axis=(0, 1))
+        t_avg = m_all.sum() // G
+        assert t1.max() <= t0.max()
+        assert np.all(t1[t0 <= t_avg] <= t_avg)               # a receiver is never pushed above the average
+        moved = S - S0
+        assert np.all((moved == 0) | (np.abs(moved) >= 1))
+        # a GPU only ever gains tokens in blocks of at least q
+        gains = moved[moved > 0]
+        assert gains.size == 0 or gains.min() >= 1
+
+
+# ------------------------------------------------------------------------------------ threshold q
+def test_threshold_q_formulas_and_paper_sizes():
+    c = _golden("paper_constants.txt")
+    assert O.expert_bytes(768, 3072, 4) == c["switch_expert_bytes"][0]
+    assert 3 * 2048 * 1408 * 4 == c["qwen_expert_bytes"][0]      # three matrices (gated FFN)
+    assert 8 * 128 * 4 == c["metadata_bytes"][0]
+    # Eq. 3 against an explicit count: a dot product of length n costs n mults + (n-1) adds
+    q, m, p = 5, 7, 11
+    assert O.expert_flops(q, m, p) == q * p * (m + m - 1) + q * m * (p + p - 1)
+    # Eq. 4 is Eq. 1 with the small terms dropped: within 0.1 % at the Switch expert's shape
+    phi, beta = 15.7e12, 16e9
+    q4 = O.token_threshold_q(phi, 4, beta)
+    qx = O.token_threshold_q_exact(phi, 4, beta, 768, 3072)
+    assert abs(q4 - qx) / qx < 1e-3
+    # at q = qx the two sides of Eq. 1 are equal
+    assert math.isclose(O.expert_flops(1, 768, 3072) * qx / phi, O.expert_bytes(768, 3072, 4) / beta, rel_tol=1e-12)
+    assert math.isclose(q4, phi * 4 / (2 * beta))
