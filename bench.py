@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""MoE-layer forward benchmark on one MI355X.
+
+A step is one pass of the whole hot path -- route -> permute -> plan -> grouped FFN (+ shared
+expert) -> combine -- over one batch of seeded synthetic input already resident in HBM.
+Default workload: c2 (Switch-style layer, bf16, T=16384, d=768, F=3072, E=128, top-1,
+first-choice loads ~ Zipf(1.0)).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def ffn_flops(wl, A):
+    per_row = (6 if wl.act == "swiglu" else 4) * wl.d * wl.F
+    f = A * per_row
+    if wl.shared_F:
+        f += wl.T * 6 * wl.d * wl.shared_F
+    return f
+
+
+def g1_algorithmic(wl, A, active):
+    """Algorithmic work of the first grouped GEMM (H = act(x_perm W_in)) of the routed experts:
+    FLOPs = 2 * A * d * F' (F' = F, or 2F with gate and up); bytes = W_in of every expert that
+    has rows, once + x_perm once + H written once."""
+    s = 2 if wl.dtype == "bf16" else 4
+    Fp = 2 * wl.F if wl.act == "swiglu" else wl.F
+    flops = 2.0 * A * wl.d * Fp
+    byts = active * wl.d * Fp * s + A * wl.d * s + A * wl.F * s
+    return flops, byts
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-uniform", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import moe_workloads as W
+    from paper_2506_12417_amd import binding as B
+    from paper_2506_12417_amd.layer import MoELayer, to_device
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    wl = W.WORKLOADS[args.workload]
+    t0 = time.time()
+    inp = W.make_inputs(wl)
+    t_gen = time.time() - t0
+    names = ("W1", "W2") if wl.act == "relu" else ("Wg", "Wu", "Wd")
+    layer = MoELayer(wl.T, wl.d, wl.F, wl.E, wl.k, wl.act, wl.dtype, wl.renorm, shared_F=wl.shared_F)
+    layer.load_router(inp["W_g"], inp["b"])
+    layer.load_experts({n: inp[n] for n in names})
+    if wl.shared_F:
+        layer.load_shared({"Wg": inp["sWg"], "Wu": inp["sWu"], "Wd": inp["sWd"]})
+    x = to_device(inp["x"], layer.device)
+    torch.cuda.synchronize()
+    print("[bench] %s: inputs drawn in %.1fs, weights packed on device" % (wl.name, t_gen), file=sys.stderr, flush=True)
+
+    def timed(steps, warmup, marks_on=True):
+        for _ in range(warmup):
+            layer.forward(x)
+        torch.cuda.synchronize()
+        marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)] if marks_on else None
+        start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        start.record()
+        for i in range(steps):
+            layer.forward(x, marks=marks[i] if marks_on else None)
+        end.record()
+        torch.cuda.synchronize()
+        ms = start.elapsed_time(end) / steps
+        g1 = g2 = None
+        if marks_on:
+            g1 = sum(m[0].elapsed_time(m[1]) for m in marks) / steps
+            g2 = sum(m[1].elapsed_time(m[2]) for m in marks) / steps
+        return ms, g1, g2
+
+    ms, g1_ms, g2_ms = timed(args.steps, args.warmup)
+    counts = layer.counts.cpu().numpy()
+    A = wl.T * wl.k
+    active = int((counts > 0).sum())
+    tokens_per_s = wl.T / (ms * 1e-3)
+    flops = ffn_flops(wl, A)
+    g1_flops, g1_bytes = g1_algorithmic(wl, A, active)
+    g1_tflops = g1_flops / (g1_ms * 1e-3) / 1e12
+    g1_gbs = g1_bytes / (g1_ms * 1e-3) / 1e9
+    ffn_tflops = ffn_flops(wl.scaled(shared_F=0), A) / ((g1_ms + g2_ms) * 1e-3) / 1e12
+    # the binding roof of the first grouped GEMM: weights stream from HBM when the experts hold
+    # few rows each (c2), the matrix cores bind when rows per expert are many (c3, c4)
+    t_hbm, t_mfma = g1_bytes / (HBM_PEAK_GBS * 1e9), g1_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_mfma:
+        roofline = {"kernel": "gemm_bf16_kernel<G1>", "bound": "hbm", "achieved": round(g1_gbs, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(g1_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                    "mfma_frac": round(g1_tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
+    else:
+        roofline = {"kernel": "gemm_bf16_kernel<G1>", "bound": "mfma", "achieved": round(g1_tflops, 1),
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(g1_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "traffic": None, "hbm_frac": round(g1_gbs / HBM_PEAK_GBS, 4)}
+    roofline["avg_launch_ms"] = round(g1_ms, 4)
+    roofline["g2_avg_launch_ms"] = round(g2_ms, 4)
+
+    out = {
+        "metric": "MoE-layer tokens/sec on 1 MI355X under Zipf skew; grouped-FFN % bf16 MFMA peak",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": "%s: T=%d d=%d F=%d E=%d top-%d %s%s, skew=%s" % (
+            wl.name, wl.T, wl.d, wl.F, wl.E, wl.k, wl.act, (" + shared F=%d" % wl.shared_F) if wl.shared_F else "",
+            wl.skew), "seed": wl.seed(), "n_bins": layer.n_bins, "q_tokens": layer.q_tokens,
+            "active_experts": active, "max_expert_rows": int(counts.max()), "min_expert_rows": int(counts.min())},
+        "ffn_tflops": round(ffn_tflops, 1), "ffn_mfma_frac": round(ffn_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "layer_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+        "roofline": roofline,
+    }
+
+    if args.workload == "c2" and not args.no_uniform:
+        layer.load_router(inp["W_g"], np.zeros(wl.E, dtype=np.float32))     # same data, router bias 0
+        ms_u, _, _ = timed(args.steps, max(3, args.warmup // 2), marks_on=False)
+        out["uniform_tokens_per_s"] = round(wl.T / (ms_u * 1e-3), 1)
+        out["skew_over_uniform"] = round(ms_u / ms, 4)
+        layer.load_router(inp["W_g"], inp["b"])
+
+    if not args.no_cpu_baseline:
+        from oracle import moe_oracle as O       # the CPU oracle, timed as it stands
+        ew = {n: inp[n] for n in names}
+        sh = {"Wg": inp["sWg"], "Wu": inp["sWu"], "Wd": inp["sWd"]} if wl.shared_F else None
+        # bounded sample: whole workload when it takes seconds (c2), else a seeded token subset
+        n_tok = wl.T if args.workload == "c2" else 1024
+        tok = None if n_tok == wl.T else np.sort(np.random.default_rng(1).choice(wl.T, n_tok, replace=False))
+        passes, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and passes < 5:
+            t1 = time.time()
+            idx_o, w_o, _ = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
+            O.permute(idx_o, wl.E)
+            O.moe_layer(inp["x"], idx_o, w_o, ew, wl.act, shared=sh, tokens=tok)
+            t_cpu += time.time() - t1
+            passes += 1
+        try:
+            cores = len(os.sched_getaffinity(0))
+        except AttributeError:
+            cores = os.cpu_count()
+        cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+        out["cpu_baseline"] = {"value": round(n_tok * passes / t_cpu, 1), "unit": "tokens/s", "cores": cores,
+                               "kind": "oracle",
+                               "sample": "%d of %d tokens (routing over all tokens), %d passes, %.1f s" % (n_tok, wl.T, passes, t_cpu)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

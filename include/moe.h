@@ -1,0 +1,249 @@
+/*
+ * libmoe -- one Mixture-of-Experts layer forward on one AMD MI355X (gfx950), as a C ABI.
+ *
+ * The layer is the one of HarMoEny (arXiv 2506.12417), Alg. 1, on a single GPU:
+ *
+ *   moe_route_topk         step 1  token routing (top-k gating, section 2)
+ *   moe_permute            step 4  tokens grouped by their expert (one-GPU form of the scatter)
+ *   moe_plan_tiles         step 3  load-aware schedule: Alg. 2 run over the GPU's XCDs
+ *   moe_grouped_ffn        step 5  expert FFNs (section 2 / section 4.4: x W1 W2)
+ *   moe_unpermute_combine  step 6  original order restored, expert outputs weighted and summed
+ *   moe_prefetch_experts   step 5  asynchronous expert fetching by overwrite (section 4.3)
+ *
+ * Conventions
+ *   - Every pointer is DEVICE memory unless its comment says host.  The caller owns every
+ *     buffer; the library allocates nothing on the device (the prefetch engine owns a stream
+ *     and events only).
+ *   - Every call only ENQUEUES work on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  No call synchronises with the host or reads device data on the host.
+ *   - Every function returns a moe_status.  Arguments are checked before anything is
+ *     enqueued; on an error nothing has been launched and no buffer has been touched.
+ *     moe_last_error() gives the text of the calling thread's last error.
+ *   - Matrices are row-major and contiguous.  T tokens, d = d_model, F = d_ff, E experts,
+ *     k experts per token, A = T*k assignments, assignment id a = t*k + j.
+ *   - dtype is the type of activations and weights (MOE_F32 or MOE_BF16); accumulation is
+ *     always fp32 or wider, gate weights and layer outputs are fp32.
+ */
+#ifndef MOE_H
+#define MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* exported from libmoe.so (the library is built with hidden visibility by default) */
+#define MOE_API __attribute__((visibility("default")))
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_ARG = -1,          /* null pointer, size or range */
+    MOE_ERR_UNSUPPORTED = -2,  /* dtype, activation, alignment or a size beyond a stated limit */
+    MOE_ERR_WORKSPACE = -3,    /* workspace smaller than moe_workspace_bytes() */
+    MOE_ERR_CAPACITY = -4,     /* tile table or expert slots too small */
+    MOE_ERR_HIP = -5           /* the HIP runtime reported an error */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+typedef enum { MOE_RELU = 0, MOE_SWIGLU = 1 } moe_act;
+
+/* Limits (MOE_ERR_UNSUPPORTED beyond them). */
+#define MOE_MAX_EXPERTS 256
+#define MOE_MAX_TOPK 8
+#define MOE_MAX_BINS 32
+
+/* ------------------------------------------------------------------------------------------
+ * Step 1, token routing (Alg. 1 line "m_expert <- router(x)"; section 2: the router gives each
+ * expert a value in (0,1), the token goes to the k highest, outputs are weighted by them).
+ *
+ *   logits[t,e] = bias[e] + sum_i x[t,i] * w_gate[i,e]
+ *   value       = softmax over all E logits
+ *   expert_idx[t,0..k) = the k experts with the largest logits, in descending order; equal
+ *                 logits go to the lower expert index
+ *   gate_w[t,j] = value of expert_idx[t,j]; renorm != 0 divides the k values by their sum
+ *
+ * The top-k decision is taken as if the logits were computed in float64: the kernel works in
+ * fp32 with a rigorous error bound and recomputes in fp64 every token whose decision gaps are
+ * inside that bound.
+ *
+ *   x       [T,d]  dtype dt        w_gate [d,E] dtype dt       bias [E] fp32, may be NULL
+ *   expert_idx [T,k] int32 out     gate_w [T,k] fp32 out
+ *   logits_out [T,E] fp32 out, may be NULL (diagnostic)
+ * Requires 1 <= k <= min(E, MOE_MAX_TOPK), E <= MOE_MAX_EXPERTS, d % 8 == 0.  T = 0 is a no-op.
+ */
+MOE_API int moe_route_topk(const void* x, const void* w_gate, const float* bias,
+                   int T, int d, int E, int k, int renorm, moe_dtype dt,
+                   int32_t* expert_idx, float* gate_w, float* logits_out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Step 4 on one GPU (Alg. 1 "scatter tokens"; counts[] is the one-GPU slice of the initial
+ * schedule S_initial of step 3): a stable counting sort of the A assignments by expert.
+ *
+ *   counts[e]  = number of assignments with expert e        offsets = exclusive scan, [E+1]
+ *   pos(a)     = offsets[idx[a]] + #{a' < a : idx[a'] = idx[a]}
+ *   perm[pos(a)] = a      inv_perm[a] = pos(a)      x_perm[pos(a),:] = x[a div k,:] (bit copy)
+ *
+ *   x [T,d] dt (may be NULL together with x_perm: indices only)
+ *   expert_idx [T,k] int32, every entry in [0,E) (entries outside are not detected)
+ *   ws / ws_bytes: scratch of at least moe_workspace_bytes(MOE_OP_PERMUTE, ...)
+ */
+MOE_API int moe_permute(const void* x, const int32_t* expert_idx, int T, int d, int E, int k, moe_dtype dt,
+                int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
+                void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Step 3 on one GPU: the load-aware token schedule (section 4.2, Alg. 2) with the GPU's
+ * n_bins XCDs in the role of the paper's GPUs.  S[e,g] = rows of expert e processed by bin g.
+ *
+ * policy
+ *   MOE_PLAN_BALANCED  experts are first placed whole, heaviest first, each on the least
+ *                      loaded bin; then Alg. 2's loop moves rows of the largest block of the
+ *                      most loaded bin to the least loaded one while that helps.  A block of n
+ *                      rows of one expert in one bin weighs max(n, q_tokens): below q_tokens
+ *                      rows an expert's time is the fetch of its weights, not its arithmetic
+ *                      (section 4.4, Eq. 1).  Moves are whole multiples of tile_m rows unless a
+ *                      whole block moves.
+ *   MOE_PLAN_HARMOENY  Alg. 2 as printed: expert e starts on bin e*n_bins/E (contiguous
+ *                      blocks of experts), loads are row counts, any number of rows may move,
+ *                      a move needs at least q_tokens rows.
+ *   MOE_PLAN_STATIC    the starting placement of MOE_PLAN_HARMOENY, no rebalancing.
+ *   MOE_PLAN_EVEN_SPLIT every expert's rows are divided evenly over all bins (section 5.3.2).
+ *
+ * Output: a table of tiles, bin after bin.  A tile is at most tile_m consecutive rows of one
+ * expert; the tiles cover rows [0,A) exactly once.  Inside a bin the blocks are ordered by
+ * falling row count (then expert id), a block's tiles by rising row_begin.
+ *
+ *   counts [E], offsets [E+1] int32 (device, e.g. from moe_permute)
+ *   tiles  [tile_capacity] out;  tile_capacity >= moe_plan_capacity(A, E, tile_m, n_bins)
+ *   plan_hdr [MOE_PLAN_HDR_INTS] int32 out:
+ *       [0] n_tiles  [1] n_bins  [2] number of Alg. 2 moves made  [3] t_avg
+ *       [4 .. 4+n_bins]  bin_start (n_bins+1 entries; bin g owns tiles [bin_start[g], bin_start[g+1]))
+ *       [4+MOE_MAX_BINS+1 .. +n_bins)  load of each bin after rebalancing (in the policy's unit)
+ *   sched  [E*n_bins] int32 out, may be NULL: the schedule S, row-major [E, n_bins]
+ * Requires 1 <= E <= MOE_MAX_EXPERTS, 1 <= n_bins <= MOE_MAX_BINS, tile_m >= 1, q_tokens >= 1.
+ */
+typedef struct { int32_t expert, row_begin, row_count, bin; } moe_tile;
+
+enum { MOE_PLAN_BALANCED = 0, MOE_PLAN_HARMOENY = 1, MOE_PLAN_STATIC = 2, MOE_PLAN_EVEN_SPLIT = 3 };
+#define MOE_PLAN_HDR_INTS (4 + 2 * (MOE_MAX_BINS + 1))
+
+MOE_API int moe_plan_capacity(int A, int E, int tile_m, int n_bins);
+
+MOE_API int moe_plan_tiles(const int32_t* counts, const int32_t* offsets, int E, int A,
+                   int tile_m, int n_bins, int q_tokens, int policy,
+                   moe_tile* tiles, int tile_capacity, int32_t* plan_hdr, int32_t* sched,
+                   void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Weight layout of the FFN kernels.  The paper writes an expert as x W1 W2 with W1: d x F and
+ * W2: F x d (section 4.4).  The kernels read every weight matrix "output-major": row n holds
+ * the d (or F) input coefficients of output feature n, i.e. the transpose, so that the
+ * contraction index is contiguous for both operands.  moe_pack_weights makes that layout once,
+ * outside the hot path.
+ *
+ *   w_a [n, K, N] dt : n matrices in the paper's orientation (K inputs, N outputs)
+ *   w_b [n, K, N] dt or NULL.  If given (SwiGLU: w_a = W_gate, w_b = W_up) the output has 2N
+ *        rows per matrix, in blocks of 32 rows: block 2j holds outputs [32j, 32j+32) of w_a,
+ *        block 2j+1 the same outputs of w_b.  Requires N % 32 == 0.
+ *   out  [n, N or 2N, K] dt
+ */
+MOE_API int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int N, moe_dtype dt,
+                     void* out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Step 5, expert processing (Alg. 1 "experts(S, x')"; section 2: two dense layers with an
+ * activation between; section 4.4: no biases).  For every row r of expert e
+ * (offsets[e] <= r < offsets[e+1]):
+ *
+ *   MOE_RELU    y_perm[r] = max(0, x_perm[r] W1_e) W2_e
+ *   MOE_SWIGLU  y_perm[r] = (silu(x_perm[r] Wgate_e) * (x_perm[r] Wup_e)) Wdown_e,  silu(z) = z/(1+exp(-z))
+ *
+ * The work is taken from the tile table of moe_plan_tiles: each XCD runs the tiles of its bin.
+ *
+ *   x_perm [A,d] dt
+ *   w_in  : device array of E device pointers; w_in[e] = packed [F,d] (ReLU) or [2F,d] (SwiGLU,
+ *           gate/up interleaved by moe_pack_weights)
+ *   w_out : device array of E device pointers; w_out[e] = packed [d,F]
+ *   tiles, plan_hdr : from moe_plan_tiles with the same E and A; tile_m must be one of the
+ *           kernel's tile heights (moe_ffn_tile_m)
+ *   h_scratch [A,F] dt : hidden activations (written, then read)
+ *   y_perm    [A,d] fp32 out
+ * Requires d % 64 == 0 and F % 64 == 0 for MOE_BF16 (d % 4, F % 4 for MOE_F32); MOE_BF16
+ * accumulates in fp32 and rounds the hidden activations to bf16 once.
+ */
+MOE_API int moe_ffn_tile_m(moe_dtype dt);
+
+MOE_API int moe_grouped_ffn(const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,
+                    const void* const* w_in, const void* const* w_out,
+                    const moe_tile* tiles, const int32_t* plan_hdr, int tile_m,
+                    void* h_scratch, float* y_perm, void* stream);
+
+/* One of the two grouped GEMMs of moe_grouped_ffn on its own (same kernels, same arguments):
+ * phase 1 computes the hidden activations H = act(x_perm W_in) into h_scratch (w_out and y_perm
+ * may be NULL), phase 2 computes y_perm = H W_out from h_scratch (x_perm and w_in may be NULL).
+ * moe_grouped_ffn is phase 1 followed by phase 2 on the same stream.  Lets a caller time, or
+ * interleave other work between, the two products of section 4.4's x W1 W2. */
+MOE_API int moe_grouped_ffn_phase(int phase, const void* x_perm, int A, int d, int F, int E, moe_act act,
+                                  moe_dtype dt, const void* const* w_in, const void* const* w_out,
+                                  const moe_tile* tiles, const int32_t* plan_hdr, int tile_m,
+                                  void* h_scratch, float* y_perm, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Step 6 (Alg. 1 "reconstruct"; section 2: the experts' outputs are weighted by the router's
+ * values and combined):
+ *
+ *   y[t] = sum_{j<k} gate_w[t,j] * y_perm[inv_perm[t*k+j]]  (+ shared[t]),  j ascending, fp32
+ *
+ *   y_perm [A,d] fp32   inv_perm [A] int32   gate_w [T,k] fp32 (NULL = all ones)
+ *   shared [T,d] fp32 or NULL (output of an always-on shared expert)      y [T,d] fp32 out
+ */
+MOE_API int moe_unpermute_combine(const float* y_perm, const int32_t* inv_perm, const float* gate_w,
+                          const float* shared, int T, int d, int k, float* y, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Asynchronous expert fetching (section 4.3): experts whose weights live in pinned host
+ * memory are copied into device slots on a stream of the engine's own while the caller's
+ * stream computes; a slot whose expert has finished is overwritten by the next expert
+ * (nothing is written back).  The engine owns one stream and two events per slot.
+ *
+ *   moe_prefetch_create   n_slots >= 1 slots of slot_bytes each, laid out back to back from
+ *                         slot_base (device memory of the caller)
+ *   moe_prefetch_experts  enqueue the copies of n experts, in the given order.  Expert i is
+ *                         copied from host_w[i] (HOST pinned pointer, bytes_each bytes, already
+ *                         in the packed layout) into slot (first free, else the slot released
+ *                         longest ago); slot_ptrs_out[i] (HOST array) receives the slot's
+ *                         device address.  A copy into a slot in use waits for that slot's
+ *                         release.  MOE_ERR_CAPACITY if a slot is needed and none was released.
+ *   moe_prefetch_wait     make `stream` wait until expert_id's copy has landed (before its FFN)
+ *   moe_prefetch_release  declare that work enqueued so far on `stream` is the last use of
+ *                         expert_id's slot (after its FFN); the slot may then be overwritten
+ *   moe_prefetch_destroy  waits for the engine's stream, frees stream and events
+ */
+typedef struct moe_prefetch moe_prefetch;
+
+MOE_API int moe_prefetch_create(moe_prefetch** h, int n_slots, size_t slot_bytes, void* slot_base);
+MOE_API int moe_prefetch_experts(moe_prefetch* h, const int32_t* expert_ids /*host*/, int n,
+                         const void* const* host_w /*host array of pinned host pointers*/,
+                         size_t bytes_each, const void** slot_ptrs_out /*host*/);
+MOE_API int moe_prefetch_wait(moe_prefetch* h, int expert_id, void* stream);
+MOE_API int moe_prefetch_release(moe_prefetch* h, int expert_id, void* stream);
+MOE_API int moe_prefetch_destroy(moe_prefetch* h);
+
+/* Token threshold q of section 4.4, Eq. 4: the row count above which running an expert takes
+ * longer than fetching its weights, q = phi * d_type / (2 * beta), rounded up.
+ *   phi: arithmetic rate in FLOP/s   d_type: bytes per weight   beta: fetch rate in bytes/s */
+MOE_API int moe_token_threshold(double phi, int d_type, double beta);
+
+/* Scratch sizes.  op selects the call. */
+enum { MOE_OP_PERMUTE = 1 };
+MOE_API size_t moe_workspace_bytes(int op, int T, int d, int F, int E, int k, moe_dtype dt);
+
+MOE_API const char* moe_last_error(void);
+MOE_API const char* moe_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H */

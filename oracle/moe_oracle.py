@@ -283,3 +283,133 @@ def token_threshold_q_exact(phi: float, d_type: int, beta: float, m: int, p: int
     """The bound before the small terms are dropped (appendix B, third line): the q at which
     |O|/phi = |E|/beta."""
     return (expert_bytes(m, p, d_type) / beta) * phi / (p * (2 * m - 1) + m * (2 * p - 1))
+
+
+# ----------------------------------------------------------------------------- one-GPU schedule
+# The library runs Alg. 2 with the GPU's XCDs ("bins") in the role of the paper's GPUs and one
+# source (G_src = 1), so S is [E, n_bins].  Two of its policies are the paper's own
+# (schedule_harmoeny, schedule_static, schedule_even_split); schedule_balanced is this build's
+# extension of Alg. 2 and is DEFINED by the function below (no paper counterpart to pin it to
+# beyond: it reduces to Alg. 2 when weights are row counts, and the invariants in the tests).
+
+def contiguous_home(E: int, G: int):
+    """Experts in contiguous blocks per GPU (Fig. 2 of the paper: experts 1,2 on GPU 0, ...)."""
+    return [(e * G) // E for e in range(E)]
+
+
+def schedule_static(counts, G: int) -> np.ndarray:
+    counts = np.asarray(counts, dtype=np.int64)
+    return initial_assign(counts[None, :], contiguous_home(len(counts), G), G)[0]
+
+
+def schedule_harmoeny(counts, G: int, q: int) -> np.ndarray:
+    """Alg. 2 as printed, one source GPU, experts starting in contiguous blocks."""
+    counts = np.asarray(counts, dtype=np.int64)
+    S0 = initial_assign(counts[None, :], contiguous_home(len(counts), G), G)
+    return rebalance(S0, q)[0]
+
+
+def schedule_even_split(counts, G: int) -> np.ndarray:
+    """Even Split (section 5.3.2): a tokens of an expert over G GPUs -> a/G each; the remainder
+    of the integer division goes one token each to the lowest-numbered GPUs (the paper's a/4
+    example leaves the remainder open)."""
+    counts = np.asarray(counts, dtype=np.int64)
+    S = np.zeros((len(counts), G), dtype=np.int64)
+    for e, a in enumerate(counts):
+        for g in range(G):
+            S[e, g] = a // G + (1 if g < a % G else 0)
+    return S
+
+
+def block_weight(n: int, q: int) -> int:
+    """Weight of n rows of one expert on one bin, in row equivalents: below q rows the time is
+    the fetch of the expert's weights, which by Eq. 1 equals the arithmetic of q rows."""
+    return 0 if n <= 0 else max(int(n), int(q))
+
+
+def schedule_balanced(counts, G: int, q: int, tile_m: int, by_cost: bool = True) -> np.ndarray:
+    """This build's default schedule.
+    1. initialAssign: experts in order of falling weight (equal weights: rising id), each whole
+       onto the bin with the least weight so far (lowest bin among equals).
+    2. Alg. 2's loop on bin weights t_g = sum_e block_weight(S[e,g]); t_avg = floor(sum t_g / G).
+       Differences from the printed loop: weights instead of row counts; when only part of a
+       block moves, at least q rows stay behind and the part is rounded down to whole tiles of
+       tile_m rows (stop if fewer than q rows would move).
+    by_cost=False makes the weight the row count and the granule one row: then step 2 IS Alg. 2."""
+    counts = np.asarray(counts, dtype=np.int64)
+    E = len(counts)
+    w = (lambda n: block_weight(n, q)) if by_cost else (lambda n: int(n))
+    gran = tile_m if by_cost else 1
+    S = np.zeros((E, G), dtype=np.int64)
+    order = sorted(range(E), key=lambda e: (-w(counts[e]), e))
+    t_g = np.zeros(G, dtype=np.int64)
+    for e in order:
+        if w(counts[e]) == 0:
+            break
+        g = int(np.argmin(t_g))
+        S[e, g] = counts[e]
+        t_g[g] += w(counts[e])
+    t_avg = int(t_g.sum()) // G
+    for _ in range(E * G + 16):
+        if not np.any(t_g > t_avg):
+            break
+        g_max = int(np.argmax(t_g))
+        e_max = int(np.argmax(S[:, g_max]))
+        t_move = int(S[e_max, g_max])
+        if t_move < q:
+            break
+        g_min = int(np.argmin(t_g))
+        if g_min == g_max or t_g[g_min] + q > t_avg:
+            break
+        t_s = min(t_move, t_avg - int(t_g[g_min]))
+        if by_cost and t_s < t_move:
+            if t_move - t_s < q:
+                t_s = t_move - q
+            t_s = (t_s // gran) * gran
+            if t_s < q or t_s <= 0:
+                break
+        n_from, n_to = int(S[e_max, g_max]), int(S[e_max, g_min])
+        t_g[g_max] -= w(n_from) - w(n_from - t_s)
+        t_g[g_min] += w(n_to + t_s) - w(n_to)
+        S[e_max, g_max] = n_from - t_s
+        S[e_max, g_min] = n_to + t_s
+    return S
+
+
+def tiles_from_schedule(S: np.ndarray, offsets, tile_m: int):
+    """The tile table a schedule S [E, n_bins] stands for: bin after bin; inside a bin the
+    blocks by falling row count (then expert id); a block's rows are the expert's rows after
+    those of lower-numbered bins, cut into tiles of at most tile_m rows.
+    Returns (tiles [n,4] int32 = expert,row_begin,row_count,bin ; bin_start [G+1])."""
+    S = np.asarray(S, dtype=np.int64)
+    E, G = S.shape
+    before = np.concatenate([np.zeros((E, 1), dtype=np.int64), np.cumsum(S, axis=1)[:, :-1]], axis=1)
+    tiles, bin_start = [], [0]
+    for g in range(G):
+        blocks = sorted((e for e in range(E) if S[e, g] > 0), key=lambda e: (-S[e, g], e))
+        for e in blocks:
+            row, left = int(offsets[e] + before[e, g]), int(S[e, g])
+            while left > 0:
+                rc = min(tile_m, left)
+                tiles.append((e, row, rc, g))
+                row += rc
+                left -= rc
+        bin_start.append(len(tiles))
+    return np.array(tiles, dtype=np.int32).reshape(-1, 4), np.array(bin_start, dtype=np.int32)
+
+
+def validate_tiles(tiles: np.ndarray, bin_start: np.ndarray, counts, offsets, tile_m: int, G: int) -> None:
+    """Raises AssertionError unless the table is a valid plan: bins contiguous and in order,
+    every row of [0,A) in exactly one tile, no tile across an expert boundary or above tile_m."""
+    counts = np.asarray(counts, dtype=np.int64)
+    offsets = np.asarray(offsets, dtype=np.int64)
+    A = int(offsets[-1])
+    assert len(bin_start) == G + 1 and bin_start[0] == 0 and bin_start[-1] == len(tiles)
+    assert np.all(np.diff(bin_start) >= 0)
+    covered = np.zeros(A, dtype=np.int64)
+    for g in range(G):
+        for e, rb, rc, b in tiles[bin_start[g]:bin_start[g + 1]]:
+            assert b == g and 0 < rc <= tile_m
+            assert offsets[e] <= rb and rb + rc <= offsets[e + 1]
+            covered[rb:rb + rc] += 1
+    assert np.all(covered == 1)

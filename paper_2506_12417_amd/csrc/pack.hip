@@ -1,0 +1,48 @@
+// moe_pack_weights: the paper's W (K inputs x N outputs, section 4.4) rewritten output-major
+// (N x K, contraction index contiguous), optionally with a second matrix interleaved in blocks
+// of 32 output rows (SwiGLU gate / up).  A 32x32 LDS transpose; done once, outside the hot path.
+#include "common.h"
+
+namespace {
+template <typename T>
+__global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ wa, const T* __restrict__ wb, int K, int N,
+                                                   T* __restrict__ out) {
+    __shared__ T tile[32][33];
+    const int m = blockIdx.z / (wb ? 2 : 1), which = wb ? blockIdx.z % 2 : 0;
+    const T* src = (which ? wb : wa) + (size_t)m * K * N;
+    const int n0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+    for (int r = ty; r < 32; r += 8)
+        if (k0 + r < K && n0 + tx < N) tile[r][tx] = src[(size_t)(k0 + r) * N + n0 + tx];
+    __syncthreads();
+    const int n_rows = wb ? 2 * N : N;
+    T* dst = out + (size_t)m * n_rows * K;
+    for (int r = ty; r < 32; r += 8) {
+        const int n = n0 + r;
+        if (n < N && k0 + tx < K) {
+            const int prow = wb ? (n / 32) * 64 + which * 32 + (n % 32) : n;
+            dst[(size_t)prow * K + k0 + tx] = tile[tx][r];
+        }
+    }
+}
+}  // namespace
+
+extern "C" int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int N, moe_dtype dt, void* out,
+                                void* stream) {
+    MOE_REQUIRE(moe_dtype_ok(dt), MOE_ERR_UNSUPPORTED, "moe_pack_weights: dtype %d", (int)dt);
+    MOE_REQUIRE(n >= 0 && K >= 1 && N >= 1, MOE_ERR_ARG, "moe_pack_weights: n=%d K=%d N=%d", n, K, N);
+    MOE_REQUIRE(!w_b || N % 32 == 0, MOE_ERR_UNSUPPORTED, "moe_pack_weights: interleaving needs N %% 32 == 0 (N=%d)", N);
+    if (n == 0) return MOE_OK;
+    MOE_REQUIRE(w_a && out, MOE_ERR_ARG, "moe_pack_weights: null pointer");
+    MOE_REQUIRE((long long)n * (w_b ? 2 : 1) <= 65535, MOE_ERR_UNSUPPORTED, "moe_pack_weights: too many matrices");
+    dim3 grid((N + 31) / 32, (K + 31) / 32, n * (w_b ? 2 : 1));
+    MOE_REQUIRE(grid.y <= 65535, MOE_ERR_UNSUPPORTED, "moe_pack_weights: K too large");
+    if (dt == MOE_BF16)
+        hipLaunchKernelGGL(pack_kernel<uint16_t>, grid, dim3(256), 0, (hipStream_t)stream, (const uint16_t*)w_a,
+                           (const uint16_t*)w_b, K, N, (uint16_t*)out);
+    else
+        hipLaunchKernelGGL(pack_kernel<float>, grid, dim3(256), 0, (hipStream_t)stream, (const float*)w_a,
+                           (const float*)w_b, K, N, (float*)out);
+    MOE_CHECK_LAUNCH("moe_pack_weights");
+    return MOE_OK;
+}

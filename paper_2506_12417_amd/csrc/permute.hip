@@ -1,0 +1,160 @@
+// moe_permute: stable counting sort of the A = T*k assignments by expert, and the row gather
+// (one-GPU form of Alg. 1 step 4; counts[] is the one-GPU slice of S_initial, step 3).
+//
+// Four launches, no float atomics, no ordering left to chance:
+//   1. per-block histogram of expert ids (1024 assignments per work-group, LDS integer adds)
+//   2. one work-group: per-expert exclusive prefix over the blocks -> counts, offsets
+//   3. per-block stable rank: inside a wavefront the peers of an assignment (same expert) are
+//      found with one ballot per bit of the expert id; popcount of the lower lanes is the rank;
+//      per-64-chunk counts are prefix-summed in LDS -> perm, inv_perm
+//   4. row gather x_perm[r] = x[perm[r] / k], 16 bytes per lane, fully coalesced
+#include "common.h"
+
+namespace {
+
+constexpr int PB = 1024;   // assignments per work-group in steps 1 and 3
+constexpr int NTH = 256;
+constexpr int CHUNKS = PB / 64;
+
+__global__ __launch_bounds__(NTH) void hist_kernel(const int32_t* __restrict__ idx, int A, int E,
+                                                   int32_t* __restrict__ block_hist) {
+    __shared__ int h[MOE_MAX_EXPERTS];
+    for (int e = threadIdx.x; e < E; e += NTH) h[e] = 0;
+    __syncthreads();
+    const int base = blockIdx.x * PB;
+    for (int i = threadIdx.x; i < PB; i += NTH) {
+        int a = base + i;
+        if (a < A) {
+            int e = idx[a];
+            if ((unsigned)e < (unsigned)E) atomicAdd(&h[e], 1);
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += NTH) block_hist[(size_t)blockIdx.x * E + e] = h[e];
+}
+
+// One work-group.  block_hist[b][e] becomes the number of assignments of expert e in blocks < b.
+__global__ __launch_bounds__(NTH) void scan_kernel(int32_t* __restrict__ block_hist, int nb, int E,
+                                                   int32_t* __restrict__ counts, int32_t* __restrict__ offsets) {
+    __shared__ int tot[MOE_MAX_EXPERTS];
+    for (int e = threadIdx.x; e < E; e += NTH) {
+        int run = 0;
+        for (int b = 0; b < nb; ++b) {
+            int v = block_hist[(size_t)b * E + e];
+            block_hist[(size_t)b * E + e] = run;
+            run += v;
+        }
+        tot[e] = run;
+        counts[e] = run;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) { offsets[e] = run; run += tot[e]; }
+        offsets[E] = run;
+    }
+}
+
+__global__ __launch_bounds__(NTH) void rank_kernel(const int32_t* __restrict__ idx, int A, int E, int nbits,
+                                                   const int32_t* __restrict__ block_hist,
+                                                   const int32_t* __restrict__ offsets,
+                                                   int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
+    extern __shared__ int chunk_hist[];   // [CHUNKS][E]
+    for (int i = threadIdx.x; i < CHUNKS * E; i += NTH) chunk_hist[i] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int base = blockIdx.x * PB;
+    int my_e[CHUNKS / 4], my_rank[CHUNKS / 4];
+#pragma unroll
+    for (int ci = 0; ci < CHUNKS / 4; ++ci) {
+        const int c = ci * 4 + wave;
+        const int a = base + c * 64 + lane;
+        int e = -1;
+        if (a < A) {
+            e = idx[a];
+            if ((unsigned)e >= (unsigned)E) e = -1;
+        }
+        unsigned long long peers = __ballot(e >= 0);
+        for (int b = 0; b < nbits; ++b) {
+            unsigned long long m = __ballot((e >> b) & 1);
+            peers &= ((e >> b) & 1) ? m : ~m;
+        }
+        const unsigned long long below = peers & ((1ull << lane) - 1ull);
+        my_e[ci] = e;
+        my_rank[ci] = __popcll(below);
+        if (e >= 0 && below == 0) chunk_hist[c * E + e] = __popcll(peers);   // lowest peer lane
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += NTH) {
+        int run = offsets[e] + block_hist[(size_t)blockIdx.x * E + e];
+        for (int c = 0; c < CHUNKS; ++c) {
+            int v = chunk_hist[c * E + e];
+            chunk_hist[c * E + e] = run;
+            run += v;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ci = 0; ci < CHUNKS / 4; ++ci) {
+        const int c = ci * 4 + wave;
+        const int a = base + c * 64 + lane;
+        if (my_e[ci] >= 0) {
+            int pos = chunk_hist[c * E + my_e[ci]] + my_rank[ci];
+            perm[pos] = a;
+            inv_perm[a] = pos;
+        }
+    }
+}
+
+// x_perm row r <- x row perm[r] / k, in 16-byte pieces (vpr pieces per row)
+__global__ __launch_bounds__(NTH) void gather_rows_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ perm,
+                                                          int A, int k, int vpr, uint4* __restrict__ x_perm) {
+    const size_t total = (size_t)A * vpr;
+    for (size_t i = (size_t)blockIdx.x * NTH + threadIdx.x; i < total; i += (size_t)gridDim.x * NTH) {
+        int r = (int)(i / vpr), v = (int)(i - (size_t)r * vpr);
+        int t = perm[r] / k;
+        x_perm[i] = x[(size_t)t * vpr + v];
+    }
+}
+
+}  // namespace
+
+extern "C" int moe_permute(const void* x, const int32_t* expert_idx, int T, int d, int E, int k, moe_dtype dt,
+                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
+                           void* ws, size_t ws_bytes, void* stream) {
+    MOE_REQUIRE(moe_dtype_ok(dt), MOE_ERR_UNSUPPORTED, "moe_permute: dtype %d", (int)dt);
+    MOE_REQUIRE(T >= 0 && E >= 1 && k >= 1 && d >= 1, MOE_ERR_ARG, "moe_permute: T=%d d=%d E=%d k=%d", T, d, E, k);
+    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "moe_permute: E=%d > %d", E, MOE_MAX_EXPERTS);
+    MOE_REQUIRE((long long)T * k < (1ll << 30), MOE_ERR_UNSUPPORTED, "moe_permute: T*k too large");
+    MOE_REQUIRE((x == nullptr) == (x_perm == nullptr), MOE_ERR_ARG, "moe_permute: x and x_perm must both be given or both be null");
+    MOE_REQUIRE(((size_t)d * moe_elem_size(dt)) % 16 == 0, MOE_ERR_UNSUPPORTED, "moe_permute: row of %d elements is not a multiple of 16 bytes", d);
+    MOE_REQUIRE(counts && offsets && ws, MOE_ERR_ARG, "moe_permute: null pointer");
+    MOE_REQUIRE(ws_bytes >= moe_workspace_bytes(MOE_OP_PERMUTE, T, d, 0, E, k, dt), MOE_ERR_WORKSPACE,
+                "moe_permute: workspace %zu < %zu bytes", ws_bytes, moe_workspace_bytes(MOE_OP_PERMUTE, T, d, 0, E, k, dt));
+    const int A = T * k;
+    MOE_REQUIRE(A == 0 || (expert_idx && perm && inv_perm), MOE_ERR_ARG, "moe_permute: null pointer");
+    hipStream_t st = (hipStream_t)stream;
+    int32_t* block_hist = (int32_t*)ws;
+    const int nb = A == 0 ? 1 : (A + PB - 1) / PB;
+    int nbits = 0;
+    while ((1 << nbits) < E) ++nbits;
+
+    hipLaunchKernelGGL(hist_kernel, dim3(nb), dim3(NTH), 0, st, expert_idx, A, E, block_hist);
+    MOE_CHECK_LAUNCH("moe_permute/hist");
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(NTH), 0, st, block_hist, nb, E, counts, offsets);
+    MOE_CHECK_LAUNCH("moe_permute/scan");
+    if (A == 0) return MOE_OK;
+    hipLaunchKernelGGL(rank_kernel, dim3(nb), dim3(NTH), sizeof(int) * CHUNKS * E, st, expert_idx, A, E, nbits,
+                       block_hist, offsets, perm, inv_perm);
+    MOE_CHECK_LAUNCH("moe_permute/rank");
+    if (x) {
+        const int vpr = (int)((size_t)d * moe_elem_size(dt) / 16);
+        size_t total = (size_t)A * vpr;
+        size_t blocks = (total + NTH - 1) / NTH;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)blocks), dim3(NTH), 0, st, (const uint4*)x, perm, A, k,
+                           vpr, (uint4*)x_perm);
+        MOE_CHECK_LAUNCH("moe_permute/gather");
+    }
+    return MOE_OK;
+}

@@ -1,0 +1,175 @@
+"""One MoE layer forward as a chain of libmoe calls (Alg. 1 on one GPU).
+
+This class owns device buffers (torch tensors used as memory) and marshals arguments; every step
+of the path -- routing, grouping, scheduling, the expert FFNs, the combine, weight packing --
+runs in the library's kernels.  Nothing here touches a tensor's values."""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+XCDS = 8   # accelerator complex dies of an MI355X; work-groups are dealt to them round-robin
+
+
+def to_device(a: np.ndarray, device) -> torch.Tensor:
+    """numpy -> device tensor; uint16 arrays are bfloat16 bit patterns."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def default_q_tokens(dt: int) -> int:
+    """Eq. 4 with one XCD as the unit: phi = its share of the matrix (bf16) or vector (fp32)
+    peak, beta = its share of the HBM bandwidth, d_type = bytes per weight."""
+    if dt == B.MOE_BF16:
+        return B.moe_token_threshold(2.5e15 / XCDS, 2, 8.0e12 / XCDS)
+    return B.moe_token_threshold(157.3e12 / XCDS, 4, 8.0e12 / XCDS)
+
+
+class ExpertGroup:
+    """Packed weights of a set of experts on the device, plus the pointer tables the FFN reads."""
+
+    def __init__(self, E: int, d: int, F: int, act: int, dt: int, device):
+        self.E, self.d, self.F, self.act, self.dt = E, d, F, act, dt
+        tdt = torch.bfloat16 if dt == B.MOE_BF16 else torch.float32
+        self.rows_in = 2 * F if act == B.MOE_SWIGLU else F
+        self.w_in = torch.empty((E, self.rows_in, d), dtype=tdt, device=device)
+        self.w_out = torch.empty((E, d, F), dtype=tdt, device=device)
+        self.refresh_pointers()
+
+    def refresh_pointers(self, in_ptrs=None, out_ptrs=None):
+        es = self.w_in.element_size()
+        ip = in_ptrs if in_ptrs is not None else [self.w_in.data_ptr() + e * self.rows_in * self.d * es for e in range(self.E)]
+        op = out_ptrs if out_ptrs is not None else [self.w_out.data_ptr() + e * self.d * self.F * es for e in range(self.E)]
+        self.in_ptrs = torch.tensor(ip, dtype=torch.int64).to(self.w_in.device)
+        self.out_ptrs = torch.tensor(op, dtype=torch.int64).to(self.w_in.device)
+
+    def load_expert(self, e: int, w: Dict[str, np.ndarray], stream=None):
+        """w: one expert's matrices in the paper's orientation (W1/W2 or Wg/Wu/Wd)."""
+        dev = self.w_in.device
+        if self.act == B.MOE_SWIGLU:
+            a, b2, o = to_device(w["Wg"], dev), to_device(w["Wu"], dev), to_device(w["Wd"], dev)
+            B.moe_pack_weights(a, b2, 1, self.d, self.F, self.dt, self.w_in[e], stream)
+        else:
+            a, o = to_device(w["W1"], dev), to_device(w["W2"], dev)
+            B.moe_pack_weights(a, None, 1, self.d, self.F, self.dt, self.w_in[e], stream)
+        B.moe_pack_weights(o, None, 1, self.F, self.d, self.dt, self.w_out[e], stream)
+        torch.cuda.synchronize(dev)   # the staging tensors above may be freed now
+
+
+class MoELayer:
+    def __init__(self, T: int, d: int, F: int, E: int, k: int, act: str, dtype: str, renorm: int,
+                 shared_F: int = 0, n_bins: int = XCDS, q_tokens: Optional[int] = None,
+                 policy: int = B.MOE_PLAN_BALANCED, device="cuda:0"):
+        self.T, self.d, self.F, self.E, self.k, self.renorm = T, d, F, E, k, renorm
+        self.A = T * k
+        self.act = B.MOE_SWIGLU if act == "swiglu" else B.MOE_RELU
+        self.dt = B.MOE_BF16 if dtype == "bf16" else B.MOE_F32
+        self.tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.n_bins, self.policy = n_bins, policy
+        self.q_tokens = q_tokens if q_tokens is not None else default_q_tokens(self.dt)
+        self.tile_m = B.moe_ffn_tile_m(self.dt)
+        self.device = torch.device(device)
+        dev, A = self.device, self.A
+        i32, f32 = torch.int32, torch.float32
+        self.W_g = None
+        self.bias = None
+        self.experts = ExpertGroup(E, d, F, self.act, self.dt, dev)
+        self.expert_idx = torch.empty((T, k), dtype=i32, device=dev)
+        self.gate_w = torch.empty((T, k), dtype=f32, device=dev)
+        self.counts = torch.empty(E, dtype=i32, device=dev)
+        self.offsets = torch.empty(E + 1, dtype=i32, device=dev)
+        self.perm = torch.empty(A, dtype=i32, device=dev)
+        self.inv_perm = torch.empty(A, dtype=i32, device=dev)
+        self.x_perm = torch.empty((A, d), dtype=self.tdt, device=dev)
+        self.ws_bytes = B.moe_workspace_bytes(B.MOE_OP_PERMUTE, T, d, F, E, k, self.dt)
+        self.ws = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=dev)
+        self.tile_capacity = B.moe_plan_capacity(A, E, self.tile_m, n_bins)
+        self.tiles = torch.empty((self.tile_capacity, 4), dtype=i32, device=dev)
+        self.plan_hdr = torch.empty(B.MOE_PLAN_HDR_INTS, dtype=i32, device=dev)
+        self.sched = torch.empty((E, n_bins), dtype=i32, device=dev)
+        self.h = torch.empty((A, F), dtype=self.tdt, device=dev)
+        self.y_perm = torch.empty((A, d), dtype=f32, device=dev)
+        self.y = torch.empty((T, d), dtype=f32, device=dev)
+        self.shared_F = shared_F
+        if shared_F:
+            # the always-on shared expert is one more group: E = 1, every token, rows in place
+            self.shared = ExpertGroup(1, d, shared_F, B.MOE_SWIGLU, self.dt, dev)
+            self.s_counts = torch.tensor([T], dtype=i32).to(dev)
+            self.s_offsets = torch.tensor([0, T], dtype=i32).to(dev)
+            self.s_capacity = B.moe_plan_capacity(T, 1, self.tile_m, n_bins)
+            self.s_tiles = torch.empty((self.s_capacity, 4), dtype=i32, device=dev)
+            self.s_hdr = torch.empty(B.MOE_PLAN_HDR_INTS, dtype=i32, device=dev)
+            self.s_h = torch.empty((T, shared_F), dtype=self.tdt, device=dev)
+            self.s_y = torch.empty((T, d), dtype=f32, device=dev)
+            B.moe_plan_tiles(self.s_counts, self.s_offsets, 1, T, self.tile_m, n_bins, self.q_tokens,
+                             B.MOE_PLAN_BALANCED, self.s_tiles, self.s_capacity, self.s_hdr, None)
+
+    # ------------------------------------------------------------------ parameters
+    def load_router(self, W_g: np.ndarray, b: Optional[np.ndarray]):
+        self.W_g = to_device(W_g, self.device)
+        self.bias = None if b is None else to_device(np.asarray(b, dtype=np.float32), self.device)
+
+    def load_experts(self, weights: Dict[str, np.ndarray]):
+        """weights: stacked [E, ...] arrays in the paper's orientation."""
+        for e in range(self.E):
+            self.experts.load_expert(e, {n: a[e] for n, a in weights.items() if not n.startswith("s")})
+
+    def load_shared(self, w: Dict[str, np.ndarray]):
+        self.shared.load_expert(0, w)
+
+    # ------------------------------------------------------------------ the path, step by step
+    def route(self, x, logits_out=None, stream=None):
+        B.moe_route_topk(x, self.W_g, self.bias, self.T, self.d, self.E, self.k, self.renorm, self.dt,
+                         self.expert_idx, self.gate_w, logits_out, stream)
+
+    def permute(self, x, stream=None):
+        B.moe_permute(x, self.expert_idx, self.T, self.d, self.E, self.k, self.dt, self.counts, self.offsets,
+                      self.perm, self.inv_perm, self.x_perm, self.ws, self.ws_bytes, stream)
+
+    def plan(self, stream=None):
+        B.moe_plan_tiles(self.counts, self.offsets, self.E, self.A, self.tile_m, self.n_bins, self.q_tokens,
+                         self.policy, self.tiles, self.tile_capacity, self.plan_hdr, self.sched, stream)
+
+    def ffn(self, stream=None):
+        g = self.experts
+        B.moe_grouped_ffn(self.x_perm, self.A, self.d, self.F, self.E, self.act, self.dt, g.in_ptrs, g.out_ptrs,
+                          self.tiles, self.plan_hdr, self.tile_m, self.h, self.y_perm, stream)
+
+    def ffn_phase(self, phase: int, stream=None):
+        g = self.experts
+        B.moe_grouped_ffn_phase(phase, self.x_perm, self.A, self.d, self.F, self.E, self.act, self.dt, g.in_ptrs,
+                                g.out_ptrs, self.tiles, self.plan_hdr, self.tile_m, self.h, self.y_perm, stream)
+
+    def shared_ffn(self, x, stream=None):
+        g = self.shared
+        B.moe_grouped_ffn(x, self.T, self.d, self.shared_F, 1, B.MOE_SWIGLU, self.dt, g.in_ptrs, g.out_ptrs,
+                          self.s_tiles, self.s_hdr, self.tile_m, self.s_h, self.s_y, stream)
+
+    def combine(self, use_gate: bool = True, stream=None):
+        B.moe_unpermute_combine(self.y_perm, self.inv_perm, self.gate_w if use_gate else None,
+                                self.s_y if self.shared_F else None, self.T, self.d, self.k, self.y, stream)
+
+    def forward(self, x: torch.Tensor, stream=None, marks=None) -> torch.Tensor:
+        """Enqueues the whole layer on the current (or given) stream; returns the output buffer.
+        marks: optional list of 3 torch.cuda.Event recorded before / between / after the two
+        grouped GEMMs (for per-kernel timing)."""
+        self.route(x, None, stream)
+        self.permute(x, stream)
+        self.plan(stream)
+        if marks is None:
+            self.ffn(stream)
+        else:
+            marks[0].record()
+            self.ffn_phase(1, stream)
+            marks[1].record()
+            self.ffn_phase(2, stream)
+            marks[2].record()
+        if self.shared_F:
+            self.shared_ffn(x, stream)
+        self.combine(True, stream)
+        return self.y

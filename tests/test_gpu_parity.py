@@ -1,0 +1,291 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Integer outputs (expert indices, counts, offsets, permutation, the
+schedule and its tile table, packed-weight bytes, gathered rows) must match bit for bit;
+floating-point outputs within max|err| <= 1e-4 * RMS (fp32) or 2e-2 * RMS (bf16)."""
+import numpy as np
+import pytest
+
+import moe_workloads as W
+from oracle import moe_oracle as O
+from gpu_util import TOL, expert_dict, make_layer, max_err_over_rms, shared_dict, to_numpy
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+def _note(msg):
+    print("[case] " + msg, flush=True)
+
+
+ROUTE_CASES = [
+    ("c1", {}),
+    ("c1", dict(T=1, E=2, k=2)),
+    ("c1", dict(T=67, d=72, E=5, k=5)),
+    ("c2", dict(T=1000, d=256, E=128)),
+    ("c2", dict(T=4096, d=768, E=128)),
+    ("c3", dict(T=777, d=512, E=60, shared_F=0)),
+    ("c4", dict(T=512, d=1024)),
+    ("c2", dict(T=300, d=128, E=200, k=3)),
+    ("c2u", dict(T=513, d=64, E=16, k=2, renorm=1)),
+]
+
+
+@pytest.mark.parametrize("name,over", ROUTE_CASES)
+def test_route_topk(torch_gpu, name, over):
+    torch = torch_gpu
+    wl = W.WORKLOADS[name].scaled(**over)
+    _note("route %s %s" % (name, over))
+    inp = W.make_inputs(wl, weights=False)
+    idx_o, w_o, l_o = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
+    layer = make_layer(wl, inp)
+    x = layer_x(layer, inp)
+    logits = torch.empty((wl.T, wl.E), dtype=torch.float32, device=layer.device)
+    layer.route(x, logits)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_numpy(layer.expert_idx), idx_o)
+    assert np.abs(to_numpy(layer.gate_w).astype(np.float64) - w_o).max() <= 2e-6
+    assert np.abs(to_numpy(logits) - l_o).max() <= 1e-5 * max(1.0, np.abs(l_o).max())
+
+
+def layer_x(layer, inp):
+    from paper_2506_12417_amd.layer import to_device
+    return to_device(inp["x"], layer.device)
+
+
+def test_route_near_ties_take_the_exact_path(torch_gpu):
+    # logits that differ only far below fp32 resolution of the accumulation, and exact ties:
+    # the selection must still be the float64 one (ties to the lower index).
+    torch = torch_gpu
+    T, d, E, k = 128, 64, 8, 2
+    r = np.random.default_rng(1)
+    x = r.standard_normal((T, d)).astype(np.float32)
+    Wg = r.standard_normal((d, E)).astype(np.float32) / 8
+    Wg[:, 3] = Wg[:, 6]                        # experts 3 and 6 always tie exactly
+    Wg[:, 5] = Wg[:, 1]
+    Wg[0, 5] += np.float32(2.0 ** -20)         # expert 5 = expert 1 + x0 * 2^-20: tiny, sign follows x0
+    wl = W.WORKLOADS["c1"].scaled(T=T, d=d, E=E, k=k)
+    idx_o, w_o, _ = O.route_topk(x, Wg, None, k, 1)
+    layer = make_layer(wl, {"W_g": Wg, "b": None})
+    layer.route(torch.from_numpy(x).to(layer.device))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_numpy(layer.expert_idx), idx_o)
+    assert np.abs(to_numpy(layer.gate_w) - w_o).max() <= 2e-6
+
+
+PERMUTE_CASES = [(1, 1, 1, 8), (256, 2, 8, 64), (1000, 1, 128, 32), (5000, 4, 60, 16), (3, 2, 256, 8),
+                 (4097, 1, 7, 128), (16384, 1, 128, 768)]
+
+
+@pytest.mark.parametrize("T,k,E,d", PERMUTE_CASES)
+def test_permute(torch_gpu, T, k, E, d):
+    torch = torch_gpu
+    _note("permute T=%d k=%d E=%d d=%d" % (T, k, E, d))
+    r = np.random.default_rng(T * 7 + k)
+    p = 1.0 / np.arange(1, E + 1) ** 1.2
+    idx = r.choice(E, size=(T, k), p=p / p.sum()).astype(np.int32)
+    x = W.f32_to_bf16_bits(r.standard_normal((T, d)).astype(np.float32))
+    ref = O.permute(idx, E)
+    wl = W.WORKLOADS["c2"].scaled(T=T, k=k, E=E, d=d, F=64)
+    layer = make_layer(wl, {})
+    layer.expert_idx.copy_(torch.from_numpy(idx))
+    from paper_2506_12417_amd.layer import to_device
+    layer.perm.fill_(-1)
+    layer.inv_perm.fill_(-1)
+    layer.permute(to_device(x, layer.device))
+    torch.cuda.synchronize()
+    for n in ("counts", "offsets", "perm", "inv_perm"):
+        assert np.array_equal(to_numpy(getattr(layer, n)), ref[n]), n
+    assert np.array_equal(to_numpy(layer.x_perm), O.gather_rows(x, ref["perm"], k))
+
+
+def test_permute_fp32_rows_and_empty_input(torch_gpu):
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    r = np.random.default_rng(5)
+    T, k, E, d = 130, 2, 8, 12
+    idx = r.integers(0, E, size=(T, k)).astype(np.int32)
+    x = r.standard_normal((T, d)).astype(np.float32)
+    ref = O.permute(idx, E)
+    wl = W.WORKLOADS["c1"].scaled(T=T, k=k, E=E, d=d, F=16)
+    layer = make_layer(wl, {})
+    layer.expert_idx.copy_(torch.from_numpy(idx))
+    layer.permute(torch.from_numpy(x).to(layer.device))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_numpy(layer.perm), ref["perm"])
+    assert np.array_equal(to_numpy(layer.x_perm), O.gather_rows(x, ref["perm"], k))
+    # T = 0: counts and offsets are written (all zero), nothing else is touched
+    counts = torch.full((E,), 7, dtype=torch.int32, device=layer.device)
+    offsets = torch.full((E + 1,), 7, dtype=torch.int32, device=layer.device)
+    B.moe_permute(None, None, 0, d, E, k, B.MOE_F32, counts, offsets, None, None, None, layer.ws, layer.ws_bytes)
+    torch.cuda.synchronize()
+    assert to_numpy(counts).tolist() == [0] * E and to_numpy(offsets).tolist() == [0] * (E + 1)
+
+
+def _plan_counts():
+    r = np.random.default_rng(77)
+    cases = []
+    for name in ("c2", "c2u", "c3", "c4"):
+        wl = W.WORKLOADS[name]
+        inp = W.make_inputs(wl, weights=False)
+        idx, _, _ = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
+        cases.append((name, np.bincount(idx.reshape(-1), minlength=wl.E)))
+    ids = W.routed_ids(W.WORKLOADS["c5"])
+    cases.append(("c5", np.bincount(ids, minlength=32)))
+    cases.append(("one-hot", np.array([0, 0, 4096, 0])))
+    cases.append(("single", np.array([777])))
+    cases.append(("empty", np.zeros(5, dtype=np.int64)))
+    cases.append(("tiny", np.array([1, 2, 3, 4, 5, 6, 7, 8, 9])))
+    cases.append(("rand256", (r.zipf(1.4, size=256) * 17 % 5000)))
+    return cases
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2, 3])
+def test_plan_tiles_all_policies(torch_gpu, policy):
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    dev = torch.device("cuda:0")
+    for name, counts in _plan_counts():
+        counts = np.asarray(counts, dtype=np.int64)
+        E, A = len(counts), int(counts.sum())
+        offsets = np.concatenate([[0], np.cumsum(counts)])
+        for G, q, tile_m in ((8, 313, 128), (8, 1, 64), (3, 40, 16), (1, 5, 128), (32, 100, 128)):
+            _note("plan %s policy=%d G=%d q=%d tile_m=%d" % (name, policy, G, q, tile_m))
+            if policy == B.MOE_PLAN_BALANCED:
+                S = O.schedule_balanced(counts, G, q, tile_m)
+            elif policy == B.MOE_PLAN_HARMOENY:
+                S = O.schedule_harmoeny(counts, G, q)
+            elif policy == B.MOE_PLAN_STATIC:
+                S = O.schedule_static(counts, G)
+            else:
+                S = O.schedule_even_split(counts, G)
+            tiles_o, bin_start_o = O.tiles_from_schedule(S, offsets, tile_m)
+            cap = B.moe_plan_capacity(A, E, tile_m, G)
+            assert len(tiles_o) <= cap
+            c_d = torch.from_numpy(counts.astype(np.int32)).to(dev)
+            o_d = torch.from_numpy(offsets.astype(np.int32)).to(dev)
+            tiles = torch.full((cap, 4), -1, dtype=torch.int32, device=dev)
+            hdr = torch.full((B.MOE_PLAN_HDR_INTS,), -1, dtype=torch.int32, device=dev)
+            sched = torch.full((E, G), -1, dtype=torch.int32, device=dev)
+            B.moe_plan_tiles(c_d, o_d, E, A, tile_m, G, q, policy, tiles, cap, hdr, sched)
+            torch.cuda.synchronize()
+            hdr_h, tiles_h = to_numpy(hdr), to_numpy(tiles)
+            assert np.array_equal(to_numpy(sched), S)
+            n = int(hdr_h[0])
+            assert n == len(tiles_o) and hdr_h[1] == G
+            assert np.array_equal(hdr_h[4:4 + G + 1], bin_start_o)
+            assert np.array_equal(tiles_h[:n], tiles_o)
+            O.validate_tiles(tiles_h[:n], hdr_h[4:4 + G + 1], counts, offsets, tile_m, G)
+
+
+PACK_CASES = [("f32", 1, 64, 128, False), ("bf16", 3, 768, 3072 // 4, False), ("bf16", 2, 96, 160, True),
+              ("f32", 2, 40, 64, True), ("bf16", 1, 50, 70, False)]
+
+
+@pytest.mark.parametrize("dtype,n,K,N,inter", PACK_CASES)
+def test_pack_weights(torch_gpu, dtype, n, K, N, inter):
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    from paper_2506_12417_amd.layer import to_device
+    dev = torch.device("cuda:0")
+    r = np.random.default_rng(K + N)
+    mk = (lambda: W.f32_to_bf16_bits(r.standard_normal((n, K, N)).astype(np.float32))) if dtype == "bf16" \
+        else (lambda: r.standard_normal((n, K, N)).astype(np.float32))
+    a = mk()
+    b = mk() if inter else None
+    dt = B.MOE_BF16 if dtype == "bf16" else B.MOE_F32
+    rows = 2 * N if inter else N
+    out = torch.zeros((n, rows, K), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device=dev)
+    B.moe_pack_weights(to_device(a, dev), None if b is None else to_device(b, dev), n, K, N, dt, out)
+    torch.cuda.synchronize()
+    at = np.transpose(a, (0, 2, 1))                      # output-major: row = output feature
+    if inter:
+        bt = np.transpose(b, (0, 2, 1))
+        ref = np.empty((n, rows, K), dtype=a.dtype)
+        for j in range(N // 32):
+            ref[:, 64 * j:64 * j + 32] = at[:, 32 * j:32 * j + 32]
+            ref[:, 64 * j + 32:64 * j + 64] = bt[:, 32 * j:32 * j + 32]
+    else:
+        ref = at
+    assert np.array_equal(to_numpy(out), ref)
+
+
+def _stage_check(torch, wl, inp, tol_scale=1.0):
+    """Runs route -> permute -> plan -> ffn -> combine on the GPU and checks every stage."""
+    layer = make_layer(wl, inp)
+    x = layer_x(layer, inp)
+    y = layer.forward(x)
+    torch.cuda.synchronize()
+    idx_o, w_o, _ = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
+    assert np.array_equal(to_numpy(layer.expert_idx), idx_o)
+    p = O.permute(idx_o, wl.E)
+    for n in ("counts", "offsets", "perm", "inv_perm"):
+        assert np.array_equal(to_numpy(getattr(layer, n)), p[n]), n
+    xp = O.gather_rows(inp["x"], p["perm"], wl.k)
+    assert np.array_equal(to_numpy(layer.x_perm), xp)
+    hdr = to_numpy(layer.plan_hdr)
+    O.validate_tiles(to_numpy(layer.tiles)[:hdr[0]], hdr[4:4 + layer.n_bins + 1], p["counts"], p["offsets"],
+                     layer.tile_m, layer.n_bins)
+    assert np.array_equal(to_numpy(layer.sched), O.schedule_balanced(p["counts"], layer.n_bins, layer.q_tokens, layer.tile_m))
+    ew = expert_dict(wl, inp)
+    yp_o = O.grouped_ffn(xp, p["offsets"], ew, wl.act)
+    tol = TOL[wl.dtype] * tol_scale
+    e_ffn = max_err_over_rms(to_numpy(layer.y_perm), yp_o)
+    y_o = O.moe_layer(inp["x"], idx_o, w_o, ew, wl.act, shared=shared_dict(wl, inp))
+    e_y = max_err_over_rms(to_numpy(y), y_o)
+    print("   ffn err/rms %.3e   layer err/rms %.3e   (tol %.1e)" % (e_ffn, e_y, tol), flush=True)
+    assert e_ffn <= tol and e_y <= tol
+    if wl.dtype == "bf16":
+        # against the oracle with bf16 hidden activations only the rounding decisions that fall
+        # differently (fp32 vs fp64 pre-activations) are left: a handful of one-ulp flips of h
+        yp_m = O.grouped_ffn(xp, p["offsets"], ew, wl.act, h_bf16=True)
+        e_m = max_err_over_rms(to_numpy(layer.y_perm), yp_m)
+        print("   ffn err/rms vs bf16-hidden oracle %.3e" % e_m, flush=True)
+        assert e_m <= 5e-3
+    return layer
+
+
+LAYER_CASES = [
+    ("c1", {}),
+    ("c1", dict(T=77, d=24, F=40, E=3, k=1)),
+    ("c1", dict(T=300, d=64, F=96, E=8, k=2, act="swiglu")),
+    ("c2", dict(T=1500, d=128, F=256, E=16)),
+    ("c2", dict(T=2048, d=768, F=3072, E=8)),
+    ("c3", dict(T=700, d=256, F=192, E=12, shared_F=320)),
+    ("c4", dict(T=900, d=512, F=1024, E=4)),
+]
+
+
+@pytest.mark.parametrize("name,over", LAYER_CASES)
+def test_layer_stage_by_stage(torch_gpu, name, over):
+    wl = W.WORKLOADS[name].scaled(**over)
+    _note("layer %s %s" % (name, over))
+    inp = W.make_inputs(wl)
+    _stage_check(torch_gpu, wl, inp)
+
+
+def test_combine_identity_and_error_paths(torch_gpu):
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    dev = torch.device("cuda:0")
+    r = np.random.default_rng(3)
+    T, d, E = 500, 32, 6
+    x = r.standard_normal((T, d)).astype(np.float32)
+    idx = r.integers(0, E, size=(T, 1)).astype(np.int32)
+    p = O.permute(idx, E)
+    xp = torch.from_numpy(O.gather_rows(x, p["perm"], 1)).to(dev)
+    y = torch.empty((T, d), dtype=torch.float32, device=dev)
+    B.moe_unpermute_combine(xp, torch.from_numpy(p["inv_perm"]).to(dev), None, None, T, d, 1, y)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_numpy(y), x)          # unpermute(permute(x)) = x, bit for bit
+    with pytest.raises(B.MoeError) as e:
+        B.moe_unpermute_combine(xp, None, None, None, T, d, 1, y)
+    assert e.value.status == B.MOE_ERR_ARG
+    with pytest.raises(B.MoeError) as e:
+        B.moe_unpermute_combine(xp, xp, None, None, T, 30, 1, y)
+    assert e.value.status == B.MOE_ERR_UNSUPPORTED

@@ -389,3 +389,65 @@ def test_threshold_q_formulas_and_paper_sizes():
     # at q = qx the two sides of Eq. 1 are equal
     assert math.isclose(O.expert_flops(1, 768, 3072) * qx / phi, O.expert_bytes(768, 3072, 4) / beta, rel_tol=1e-12)
     assert math.isclose(q4, phi * 4 / (2 * beta))
+
+
+# ------------------------------------------------------------------------------------ one-GPU schedule
+def test_schedule_without_weights_is_alg2():
+    # by_cost=False: weights are row counts and one row is the granule, so the loop must be
+    # Alg. 2 itself.  Start both from the same placement by making it unambiguous: one expert
+    # per bin and strictly falling counts (heaviest-first placement = contiguous homes).
+    r = np.random.default_rng(31)
+    for G in (2, 3, 5, 8):
+        counts = np.sort(r.integers(1, 500, size=G))[::-1] * 2 + np.arange(G, 0, -1)
+        for q in (1, 7, 64):
+            a = O.schedule_balanced(counts, G, q, tile_m=1, by_cost=False)
+            b = O.schedule_harmoeny(counts, G, q)
+            assert np.array_equal(a, b), (G, q)
+    # the paper's example again, through the one-source interface: loads 2,4,9 -> 5,5,5
+    assert O.schedule_harmoeny([2, 4, 9], 3, 1).sum(axis=0).tolist() == [5, 5, 5]
+
+
+def test_schedule_policies_invariants():
+    r = np.random.default_rng(32)
+    for trial in range(40):
+        E = int(r.integers(1, 70))
+        G = int(r.integers(1, 9))
+        q = int(r.integers(1, 400))
+        tile_m = int(r.choice([16, 64, 128]))
+        counts = (r.zipf(1.3, size=E) * 13 % 3000).astype(np.int64)
+        counts[r.random(E) < 0.2] = 0
+        offsets = np.concatenate([[0], np.cumsum(counts)])
+        for S in (O.schedule_balanced(counts, G, q, tile_m), O.schedule_harmoeny(counts, G, q),
+                  O.schedule_static(counts, G), O.schedule_even_split(counts, G)):
+            assert S.shape == (E, G) and S.min() >= 0
+            assert np.array_equal(S.sum(axis=1), counts)                       # every row scheduled once
+            tiles, bin_start = O.tiles_from_schedule(S, offsets, tile_m)
+            O.validate_tiles(tiles, bin_start, counts, offsets, tile_m, G)
+            assert len(tiles) <= -(-int(counts.sum()) // tile_m) + E * G
+        Sb = O.schedule_balanced(counts, G, q, tile_m)
+        # a split block keeps at least q rows in every part
+        for e in range(E):
+            parts = Sb[e][Sb[e] > 0]
+            assert len(parts) <= 1 or parts.min() >= min(q, counts[e])
+        Se = O.schedule_even_split(counts, G)
+        assert np.all(Se.max(axis=1) - Se.min(axis=1) <= 1)
+
+
+def test_schedule_balanced_splits_hot_expert_and_balances():
+    # one expert with half of all rows, 8 bins: its rows must be spread, bin weights near equal
+    counts = np.array([8192, 2600, 1500, 1100, 900, 800, 700, 592])
+    q, tile_m, G = 313, 128, 8
+    S = O.schedule_balanced(counts, G, q, tile_m)
+    assert (S[0] > 0).sum() >= 4
+    w = np.array([[O.block_weight(n, q) for n in row] for row in S]).sum(axis=0)
+    assert w.max() <= w.sum() // G + q + tile_m          # the loop stops when no bin has room for q more rows
+    assert np.all(np.sort(S[0][S[0] > 0])[:-1] % tile_m == 0)   # moved parts are whole tiles
+    # uniform small experts: nothing to split, experts dealt evenly
+    S = O.schedule_balanced(np.full(128, 128), 8, 313, 128)
+    assert np.all((S > 0).sum(axis=1) == 1) and np.all((S > 0).sum(axis=0) == 16)
+    # all rows on one expert: spread over all bins in whole tiles
+    S = O.schedule_balanced(np.array([4096, 0, 0, 0]), 8, 313, 128)
+    assert (S[0] > 0).sum() == 8 and S[0].sum() == 4096
+    # static placement never splits; contiguous homes
+    assert O.contiguous_home(6, 3) == [0, 0, 1, 1, 2, 2]
+    assert O.block_weight(0, 5) == 0 and O.block_weight(3, 5) == 5 and O.block_weight(9, 5) == 9
