@@ -52,7 +52,7 @@ typedef enum { MOE_RELU = 0, MOE_SWIGLU = 1 } moe_act;
 /* Limits (MOE_ERR_UNSUPPORTED beyond them). */
 #define MOE_MAX_EXPERTS 256
 #define MOE_MAX_TOPK 8
-#define MOE_MAX_BINS 32
+#define MOE_MAX_BINS 16
 
 /* ------------------------------------------------------------------------------------------
  * Step 1, token routing (Alg. 1 line "m_expert <- router(x)"; section 2: the router gives each
@@ -122,7 +122,8 @@ MOE_API int moe_permute(const void* x, const int32_t* expert_idx, int T, int d, 
  *       [4 .. 4+n_bins]  bin_start (n_bins+1 entries; bin g owns tiles [bin_start[g], bin_start[g+1]))
  *       [4+MOE_MAX_BINS+1 .. +n_bins)  load of each bin after rebalancing (in the policy's unit)
  *   sched  [E*n_bins] int32 out, may be NULL: the schedule S, row-major [E, n_bins]
- * Requires 1 <= E <= MOE_MAX_EXPERTS, 1 <= n_bins <= MOE_MAX_BINS, tile_m >= 1, q_tokens >= 1.
+ * Requires 1 <= E <= MOE_MAX_EXPERTS, 1 <= n_bins <= MOE_MAX_BINS, tile_m >= 1, q_tokens >= 1,
+ * A + E*q_tokens < 2^26.
  */
 typedef struct { int32_t expert, row_begin, row_count, bin; } moe_tile;
 

@@ -38,6 +38,7 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.f + __expf(-z))
 // =============================================================================== bf16 / MFMA
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte load/store
 
 constexpr int BM = 128, BN = 128, BK = 64, PITCH = BK + 8;   // PITCH in bf16 elements (144 B)
 constexpr int STAGE_ELEMS = (BM + BN) * PITCH;
@@ -77,11 +78,11 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
             a_src[i] = a_mat + (size_t)(tile.row_begin + ar) * K + ld_kv;
             b_src[i] = wmat + (size_t)br * K + ld_kv;
         }
-        uint4 a_reg[4], b_reg[4];
+        u32x4 a_reg[4], b_reg[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            a_reg[i] = *(const uint4*)(a_src[i]);
-            b_reg[i] = *(const uint4*)(b_src[i]);
+            a_reg[i] = *(const u32x4*)(a_src[i]);
+            b_reg[i] = *(const u32x4*)(b_src[i]);
         }
         f32x16 acc[2][2];
 #pragma unroll
@@ -94,22 +95,22 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
         __syncthreads();   // the previous item's last reads of stage 0 are done
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            *(uint4*)(lds + (ld_row + 32 * i) * PITCH + ld_kv) = a_reg[i];
-            *(uint4*)(lds + (BM + ld_row + 32 * i) * PITCH + ld_kv) = b_reg[i];
+            *(u32x4*)(lds + (ld_row + 32 * i) * PITCH + ld_kv) = a_reg[i];
+            *(u32x4*)(lds + (BM + ld_row + 32 * i) * PITCH + ld_kv) = b_reg[i];
         }
         __syncthreads();
 
-        const bool m_on[2] = {wm * 64 < rc, wm * 64 + 32 < rc};
+        const bool m_on0 = wm * 64 < rc, m_on1 = wm * 64 + 32 < rc;
         for (int kt = 0; kt < KT; ++kt) {
             const uint16_t* st = lds + (kt & 1) * STAGE_ELEMS;
             if (kt + 1 < KT) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    a_reg[i] = *(const uint4*)(a_src[i] + (size_t)(kt + 1) * BK);
-                    b_reg[i] = *(const uint4*)(b_src[i] + (size_t)(kt + 1) * BK);
+                    a_reg[i] = *(const u32x4*)(a_src[i] + (size_t)(kt + 1) * BK);
+                    b_reg[i] = *(const u32x4*)(b_src[i] + (size_t)(kt + 1) * BK);
                 }
             }
-            if (m_on[0]) {
+            if (m_on0) {
 #pragma unroll
                 for (int ks = 0; ks < BK / 16; ++ks) {
                     bf16x8 af[2], bf[2];
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
                         bf[ni] = *(const bf16x8*)(st + (BM + wn * 64 + ni * 32 + l32) * PITCH + ks * 16 + lhi * 8);
 #pragma unroll
                     for (int mi = 0; mi < 2; ++mi) {
-                        if (mi == 0 || m_on[1]) {
+                        if (mi == 0 || m_on1) {
 #pragma unroll
                             for (int ni = 0; ni < 2; ++ni)
                                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
@@ -133,8 +134,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
                 uint16_t* dst = lds + ((kt + 1) & 1) * STAGE_ELEMS;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    *(uint4*)(dst + (ld_row + 32 * i) * PITCH + ld_kv) = a_reg[i];
-                    *(uint4*)(dst + (BM + ld_row + 32 * i) * PITCH + ld_kv) = b_reg[i];
+                    *(u32x4*)(dst + (ld_row + 32 * i) * PITCH + ld_kv) = a_reg[i];
+                    *(u32x4*)(dst + (BM + ld_row + 32 * i) * PITCH + ld_kv) = b_reg[i];
                 }
             }
             __syncthreads();

@@ -15,13 +15,46 @@ constexpr int NTH = 256;   // >= MOE_MAX_EXPERTS: one thread per expert
 __device__ __forceinline__ int weight_of(int n, int q, bool by_cost) {
     return by_cost ? (n > 0 ? (n > q ? n : q) : 0) : n;
 }
-// larger value wins, equal values go to the lower index
-__device__ __forceinline__ void wave_argbest(int& v, int& i) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        int ov = __shfl_xor(v, off), oi = __shfl_xor(i, off);
-        if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
-    }
+
+// Wave-wide unsigned min / max at ALU speed: four DPP steps reduce each row of 16 lanes
+// (pairs, quads, half rows, rows), then the four row results are combined through SGPRs.
+__device__ __forceinline__ unsigned wave_min_u32(unsigned v) {
+    unsigned t;
+    t = __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xf, 0xf, false); v = t < v ? t : v;    // quad_perm [1,0,3,2]
+    t = __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xf, 0xf, false); v = t < v ? t : v;    // quad_perm [2,3,0,1]
+    t = __builtin_amdgcn_update_dpp(v, v, 0x141, 0xf, 0xf, false); v = t < v ? t : v;   // row_half_mirror
+    t = __builtin_amdgcn_update_dpp(v, v, 0x140, 0xf, 0xf, false); v = t < v ? t : v;   // row_mirror
+    unsigned a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    unsigned c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    a = a < b ? a : b;
+    c = c < d ? c : d;
+    return a < c ? a : c;
+}
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v) { return ~wave_min_u32(~v); }
+
+// Loads are kept below 2^26 so that (load << 5 | bin) fits 32 bits (bins < 32): one reduction gives both the
+// extreme load and, among equal loads, the lowest bin.
+constexpr int BIN_BITS = 5;
+__device__ __forceinline__ void argmin_bin(int tg, int lane, int G, int& g, int& v) {
+    unsigned key = lane < G ? (((unsigned)tg << BIN_BITS) | (unsigned)lane) : 0xffffffffu;
+    key = wave_min_u32(key);
+    g = (int)(key & ((1u << BIN_BITS) - 1u));
+    v = (int)(key >> BIN_BITS);
+}
+__device__ __forceinline__ void argmax_bin(int tg, int lane, int G, int& g, int& v) {
+    unsigned key = lane < G ? (((unsigned)tg << BIN_BITS) | (unsigned)(MOE_MAX_BINS - 1 - lane)) : 0u;
+    key = wave_max_u32(key);
+    g = MOE_MAX_BINS - 1 - (int)(key & ((1u << BIN_BITS) - 1u));
+    v = (int)(key >> BIN_BITS);
+}
+
+__device__ __forceinline__ unsigned wave_sum_u32(unsigned v) {
+    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false);
+    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false);
+    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xf, 0xf, false);
+    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xf, 0xf, false);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
 }
 
 __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ counts,
@@ -31,8 +64,10 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
                                                    int32_t* __restrict__ sched) {
     __shared__ int cnt[MOE_MAX_EXPERTS], cost[MOE_MAX_EXPERTS], order[MOE_MAX_EXPERTS];
     __shared__ int S_[MOE_MAX_EXPERTS * MOE_MAX_BINS];
-    __shared__ unsigned short NT_[MOE_MAX_EXPERTS * MOE_MAX_BINS];
-    __shared__ int load[MOE_MAX_BINS];
+    // non-empty (expert, bin) blocks, one segment per bin: rows and expert id
+    __shared__ int blk_n[MOE_MAX_EXPERTS * MOE_MAX_BINS];
+    __shared__ unsigned char blk_e[MOE_MAX_EXPERTS * MOE_MAX_BINS];
+    __shared__ int load[MOE_MAX_BINS], bin_blocks[MOE_MAX_BINS + 1], bin_cursor[MOE_MAX_BINS], bin_tiles[MOE_MAX_BINS + 1];
     __shared__ int s_tavg, s_moves;
     volatile int* S = S_;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -40,6 +75,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     (void)A;
 
     for (int i = tid; i < E * G; i += NTH) S_[i] = 0;
+    if (tid < G) { load[tid] = 0; bin_blocks[tid] = 0; bin_cursor[tid] = 0; bin_tiles[tid] = 0; }
     if (tid < E) {
         int c = counts[tid];
         cnt[tid] = c;
@@ -51,130 +87,175 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     // ---- initial placement (the paper's initialAssign)
     if (policy == MOE_PLAN_BALANCED) {
         if (tid < E) {   // experts by falling weight, equal weights by rising id
-            int c = cost[tid], r = 0;
+            const int c = cost[tid];
+            int r = 0;
+#pragma unroll 8
             for (int e2 = 0; e2 < E; ++e2) {
-                int c2 = cost[e2];
+                const int c2 = cost[e2];
                 r += (c2 > c || (c2 == c && e2 < tid)) ? 1 : 0;
             }
             order[r] = tid;
         }
         __syncthreads();
-        if (tid < 64) {  // each expert whole, on the least loaded bin so far
-            int tg = 0;
-            for (int r = 0; r < E; ++r) {
-                int e = order[r], c = cost[e];
-                if (c == 0) break;
-                int v = lane < G ? -tg : INT_MIN, g = lane;
-                wave_argbest(v, g);
-                if (lane == 0) S[e * G + g] = cnt[e];
-                if (lane == g) tg += c;
+        if (tid < 64) {  // each expert whole, on the least loaded bin so far; the list lives in registers
+            constexpr int NJ = MOE_MAX_EXPERTS / 64;
+            int ord[NJ], cst[NJ], cn[NJ];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const int r = lane + 64 * j;
+                ord[j] = r < E ? order[r] : 0;
+                cst[j] = r < E ? cost[ord[j]] : 0;
+                cn[j] = r < E ? cnt[ord[j]] : 0;
             }
+            int tg = 0;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const int n = E - 64 * j < 64 ? E - 64 * j : 64;
+                for (int r = 0; r < n; ++r) {
+                    const int c = __builtin_amdgcn_readlane(cst[j], r);
+                    if (c == 0) break;
+                    const int e = __builtin_amdgcn_readlane(ord[j], r), rows = __builtin_amdgcn_readlane(cn[j], r);
+                    int g, v;
+                    argmin_bin(tg, lane, G, g, v);
+                    if (lane == 0) S[e * G + g] = rows;
+                    if (lane == g) tg += c;
+                }
+            }
+            if (lane < G) load[lane] = tg;
         }
     } else if (policy == MOE_PLAN_EVEN_SPLIT) {
         if (tid < E) {
-            int c = cnt[tid];
-            for (int g = 0; g < G; ++g) S[tid * G + g] = c / G + (g < c % G ? 1 : 0);
+            const int c = cnt[tid];
+            for (int g = 0; g < G; ++g) {
+                const int n = c / G + (g < c % G ? 1 : 0);
+                S[tid * G + g] = n;
+                atomicAdd(&load[g], n);
+            }
         }
     } else {             // contiguous blocks of experts per bin
-        if (tid < E) S[tid * G + (int)(((long long)tid * G) / E)] = cnt[tid];
-    }
-    __syncthreads();
-    if (tid < G) {
-        int s = 0;
-        for (int e = 0; e < E; ++e) s += weight_of(S[e * G + tid], q, by_cost);
-        load[tid] = s;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        long long tot = 0;
-        for (int g = 0; g < G; ++g) tot += load[g];
-        s_tavg = (int)(tot / G);
+        if (tid < E) {
+            const int g = (int)(((long long)tid * G) / E);
+            S[tid * G + g] = cnt[tid];
+            atomicAdd(&load[g], cnt[tid]);
+        }
     }
     __syncthreads();
 
     // ---- Alg. 2: move rows of the largest block of the most loaded bin to the least loaded bin
-    if ((policy == MOE_PLAN_BALANCED || policy == MOE_PLAN_HARMOENY) && tid < 64) {
-        const int t_avg = s_tavg;
-        const int gran = by_cost ? tile_m : 1;
+    if (tid < 64) {
         int tg = lane < G ? load[lane] : 0;
+        const int t_avg = (int)(wave_sum_u32((unsigned)tg) / (unsigned)G);
         int moves = 0;
-        const int max_iters = E * G + 16;
-        for (int it = 0; it < max_iters; ++it) {
-            if (__ballot(lane < G && tg > t_avg) == 0ull) break;
-            int v = lane < G ? tg : INT_MIN, g_max = lane;
-            wave_argbest(v, g_max);
-            int t_move = -1, e_max = INT_MAX;
-            for (int e = lane; e < E; e += 64) {
-                int s = S[e * G + g_max];
-                if (s > t_move) { t_move = s; e_max = e; }
+        if (policy == MOE_PLAN_BALANCED || policy == MOE_PLAN_HARMOENY) {
+            const int gran = by_cost ? tile_m : 1;
+            const int max_iters = E * G + 16;
+            for (int it = 0; it < max_iters; ++it) {
+                int g_max, t_max;
+                argmax_bin(tg, lane, G, g_max, t_max);
+                if (t_max <= t_avg) break;                       // no bin above the average
+                int best = -1;
+                for (int e = lane; e < E; e += 64) {
+                    const int sv = S[e * G + g_max];
+                    best = sv > best ? sv : best;
+                }
+                const int t_move = (int)wave_max_u32((unsigned)(best + 1)) - 1;
+                unsigned first = 0xffffffffu;                    // lowest expert holding t_move rows
+                for (int e = lane; e < E; e += 64)
+                    if (S[e * G + g_max] == t_move) { first = (unsigned)e; break; }
+                const int e_max = (int)wave_min_u32(first);
+                if (t_move < q) break;
+                int g_min, t_min;
+                argmin_bin(tg, lane, G, g_min, t_min);
+                if (g_min == g_max || t_min + q > t_avg) break;
+                int t_s = t_move < t_avg - t_min ? t_move : t_avg - t_min;
+                if (by_cost && t_s < t_move) {
+                    // a split leaves at least q rows behind and moves whole tiles
+                    if (t_move - t_s < q) t_s = t_move - q;
+                    t_s = t_s / gran * gran;
+                    if (t_s < q || t_s <= 0) break;
+                }
+                const int n_from = S[e_max * G + g_max], n_to = S[e_max * G + g_min];
+                const int d_from = weight_of(n_from, q, by_cost) - weight_of(n_from - t_s, q, by_cost);
+                const int d_to = weight_of(n_to + t_s, q, by_cost) - weight_of(n_to, q, by_cost);
+                if (lane == 0) {
+                    S[e_max * G + g_max] = n_from - t_s;
+                    S[e_max * G + g_min] = n_to + t_s;
+                }
+                if (lane == g_max) tg -= d_from;
+                if (lane == g_min) tg += d_to;
+                ++moves;
             }
-            wave_argbest(t_move, e_max);
-            if (t_move < q) break;
-            int nv = lane < G ? -tg : INT_MIN, g_min = lane;
-            wave_argbest(nv, g_min);
-            const int t_min = -nv;
-            if (g_min == g_max || t_min + q > t_avg) break;
-            int t_s = t_move < t_avg - t_min ? t_move : t_avg - t_min;
-            if (by_cost && t_s < t_move) {
-                // a split leaves at least q rows behind and moves whole tiles
-                if (t_move - t_s < q) t_s = t_move - q;
-                t_s = t_s / gran * gran;
-                if (t_s < q || t_s <= 0) break;
-            }
-            const int n_from = S[e_max * G + g_max], n_to = S[e_max * G + g_min];
-            const int d_from = weight_of(n_from, q, by_cost) - weight_of(n_from - t_s, q, by_cost);
-            const int d_to = weight_of(n_to + t_s, q, by_cost) - weight_of(n_to, q, by_cost);
-            if (lane == 0) {
-                S[e_max * G + g_max] = n_from - t_s;
-                S[e_max * G + g_min] = n_to + t_s;
-            }
-            if (lane == g_max) tg -= d_from;
-            if (lane == g_min) tg += d_to;
-            ++moves;
         }
         if (lane < G) load[lane] = tg;
-        if (lane == 0) s_moves = moves;
+        if (lane == 0) { s_moves = moves; s_tavg = t_avg; }
     }
     __syncthreads();
 
-    // ---- tiles, bin after bin; inside a bin blocks by falling row count, then expert id
-    const int e = tid;
-    if (e < E)
-        for (int g = 0; g < G; ++g) NT_[e * G + g] = (unsigned short)((S[e * G + g] + tile_m - 1) / tile_m > 65535 ? 65535 : (S[e * G + g] + tile_m - 1) / tile_m);
+    // ---- the non-empty blocks of every bin, gathered into per-bin segments (any order)
+    for (int p = tid; p < E * G; p += NTH) {
+        const int n = S_[p];
+        if (sched) sched[p] = n;
+        if (n > 0) atomicAdd(&bin_blocks[p % G], 1);
+    }
     __syncthreads();
-    if (e < E) {
-        int row = offsets[e], bin_start = 0;
-        for (int g = 0; g < G; ++g) {
-            const int n = S[e * G + g];
-            int before = 0, total = 0;
-            for (int e2 = 0; e2 < E; ++e2) {
-                int n2 = S[e2 * G + g], t2 = NT_[e2 * G + g];
-                total += t2;
-                before += (n2 > n || (n2 == n && e2 < e)) ? t2 : 0;
-            }
-            if (e == 0) hdr[4 + g] = bin_start;
-            const int nt = (n + tile_m - 1) / tile_m;
-            for (int i = 0; i < nt; ++i) {
-                int at = bin_start + before + i;
-                if (at < capacity) {
-                    moe_tile t;
-                    t.expert = e;
-                    t.row_begin = row + i * tile_m;
-                    t.row_count = (n - i * tile_m) < tile_m ? (n - i * tile_m) : tile_m;
-                    t.bin = g;
-                    tiles[at] = t;
-                }
-            }
-            if (sched) sched[e * G + g] = n;
-            row += n;
-            bin_start += total;
+    if (tid == 0) {
+        int run = 0;
+        for (int g = 0; g < G; ++g) { const int c = bin_blocks[g]; bin_blocks[g] = run; run += c; }
+        bin_blocks[G] = run;
+    }
+    __syncthreads();
+    for (int p = tid; p < E * G; p += NTH) {
+        const int n = S_[p];
+        if (n > 0) {
+            const int g = p % G;
+            const int at = bin_blocks[g] + atomicAdd(&bin_cursor[g], 1);
+            blk_n[at] = n;
+            blk_e[at] = (unsigned char)(p / G);
+            atomicAdd(&bin_tiles[g], (n + tile_m - 1) / tile_m);
         }
-        if (e == 0) {
-            hdr[4 + G] = bin_start < capacity ? bin_start : capacity;
-            hdr[0] = bin_start < capacity ? bin_start : capacity;
-            hdr[1] = G;
-            hdr[2] = s_moves;
-            hdr[3] = s_tavg;
+    }
+    __syncthreads();
+
+    // ---- tiles: inside a bin the blocks by falling row count, then expert id; one block per thread
+    const int n_blocks = bin_blocks[G];
+    if (tid == 0) {
+        int run = 0;
+        for (int g = 0; g < G; ++g) {
+            const int t = bin_tiles[g];
+            bin_tiles[g] = run;
+            hdr[4 + g] = run < capacity ? run : capacity;
+            run += t;
+        }
+        bin_tiles[G] = run;
+        hdr[4 + G] = run < capacity ? run : capacity;
+        hdr[0] = run < capacity ? run : capacity;
+        hdr[1] = G;
+        hdr[2] = s_moves;
+        hdr[3] = s_tavg;
+    }
+    __syncthreads();
+    for (int b = tid; b < n_blocks; b += NTH) {
+        int g = 0;
+        while (b >= bin_blocks[g + 1]) ++g;
+        const int n = blk_n[b], e = blk_e[b];
+        int before = 0;
+        for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o) {
+            const int n2 = blk_n[o], e2 = blk_e[o];
+            if (n2 > n || (n2 == n && e2 < e)) before += (n2 + tile_m - 1) / tile_m;
+        }
+        int row = offsets[e];
+        for (int g2 = 0; g2 < g; ++g2) row += S_[e * G + g2];
+        const int nt = (n + tile_m - 1) / tile_m;
+        for (int i = 0; i < nt; ++i) {
+            const int at = bin_tiles[g] + before + i;
+            if (at < capacity) {
+                moe_tile t;
+                t.expert = e;
+                t.row_begin = row + i * tile_m;
+                t.row_count = (n - i * tile_m) < tile_m ? (n - i * tile_m) : tile_m;
+                t.bin = g;
+                tiles[at] = t;
+            }
         }
     }
     if (tid < G) hdr[4 + MOE_MAX_BINS + 1 + tid] = load[tid];
@@ -192,6 +273,8 @@ extern "C" int moe_plan_tiles(const int32_t* counts, const int32_t* offsets, int
                               int q_tokens, int policy, moe_tile* tiles, int tile_capacity, int32_t* plan_hdr,
                               int32_t* sched, void* stream) {
     MOE_REQUIRE(E >= 1 && A >= 0, MOE_ERR_ARG, "moe_plan_tiles: E=%d A=%d", E, A);
+    MOE_REQUIRE((long long)A + (long long)E * q_tokens < (1ll << 26), MOE_ERR_UNSUPPORTED,
+                "moe_plan_tiles: A + E*q_tokens = %lld is not below 2^26", (long long)A + (long long)E * q_tokens);
     MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "moe_plan_tiles: E=%d > %d", E, MOE_MAX_EXPERTS);
     MOE_REQUIRE(n_bins >= 1 && n_bins <= MOE_MAX_BINS, MOE_ERR_ARG, "moe_plan_tiles: n_bins=%d outside [1,%d]", n_bins, MOE_MAX_BINS);
     MOE_REQUIRE(tile_m >= 1 && q_tokens >= 1, MOE_ERR_ARG, "moe_plan_tiles: tile_m=%d q_tokens=%d must be >= 1", tile_m, q_tokens);

@@ -1,4 +1,6 @@
 // moe_route_topk: router logits, softmax, top-k selection (Alg. 1 step 1; section 2).
+// This file: argument checks, and the fp32-input kernel (plain FMAs); bf16 inputs go to the MFMA
+// kernel in route_mfma.hip, which follows the same scheme.
 //
 // One work-group takes 64 tokens.  The logits x.W_g are accumulated with fp32 FMAs in chunks of
 // 32 terms; every chunk's partial sum is then added into an fp64 accumulator, so the only
@@ -274,6 +276,10 @@ int dispatch_route(const void* x, const void* wg, const float* bias, int T, int 
 
 }  // namespace
 
+// bf16 inputs: the MFMA kernel of route_mfma.hip
+int moe_route_bf16_mfma(const void* x, const void* wg, const float* bias, int T, int d, int E, int k, int renorm,
+                        int32_t* idx, float* w, float* logits, hipStream_t st);
+
 extern "C" int moe_route_topk(const void* x, const void* w_gate, const float* bias, int T, int d, int E, int k,
                               int renorm, moe_dtype dt, int32_t* expert_idx, float* gate_w, float* logits_out,
                               void* stream) {
@@ -287,6 +293,6 @@ extern "C" int moe_route_topk(const void* x, const void* w_gate, const float* bi
     MOE_REQUIRE(x && w_gate && expert_idx && gate_w, MOE_ERR_ARG, "moe_route_topk: null pointer");
     hipStream_t st = (hipStream_t)stream;
     if (dt == MOE_BF16)
-        return dispatch_route<uint16_t>(x, w_gate, bias, T, d, E, k, renorm, expert_idx, gate_w, logits_out, st);
+        return moe_route_bf16_mfma(x, w_gate, bias, T, d, E, k, renorm, expert_idx, gate_w, logits_out, st);
     return dispatch_route<float>(x, w_gate, bias, T, d, E, k, renorm, expert_idx, gate_w, logits_out, st);
 }

@@ -154,7 +154,7 @@ def test_plan_tiles_all_policies(torch_gpu, policy):
         counts = np.asarray(counts, dtype=np.int64)
         E, A = len(counts), int(counts.sum())
         offsets = np.concatenate([[0], np.cumsum(counts)])
-        for G, q, tile_m in ((8, 313, 128), (8, 1, 64), (3, 40, 16), (1, 5, 128), (32, 100, 128)):
+        for G, q, tile_m in ((8, 313, 128), (8, 1, 64), (3, 40, 16), (1, 5, 128), (16, 100, 128)):
             _note("plan %s policy=%d G=%d q=%d tile_m=%d" % (name, policy, G, q, tile_m))
             if policy == B.MOE_PLAN_BALANCED:
                 S = O.schedule_balanced(counts, G, q, tile_m)
