@@ -167,14 +167,17 @@ MOE_API int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int
  *   w_in  : device array of E device pointers; w_in[e] = packed [F,d] (ReLU) or [2F,d] (SwiGLU,
  *           gate/up interleaved by moe_pack_weights)
  *   w_out : device array of E device pointers; w_out[e] = packed [d,F]
- *   tiles, plan_hdr : from moe_plan_tiles with the same E and A; tile_m must be one of the
- *           kernel's tile heights (moe_ffn_tile_m)
+ *   tiles, plan_hdr : from moe_plan_tiles with the same E and A; tile_m as given to the plan:
+ *           moe_ffn_tile_m(dt), or for bf16 128 or 256 (moe_ffn_pick_tile_m)
  *   h_scratch [A,F] dt : hidden activations (written, then read)
  *   y_perm    [A,d] fp32 out
  * Requires d % 64 == 0 and F % 64 == 0 for MOE_BF16 (d % 4, F % 4 for MOE_F32); MOE_BF16
  * accumulates in fp32 and rounds the hidden activations to bf16 once.
  */
 MOE_API int moe_ffn_tile_m(moe_dtype dt);
+/* bf16 has two tile heights, 128 and 256 rows; this picks one from the mean rows per expert
+ * (256 once A/E >= 512).  Plan and FFN must be given the same value. */
+MOE_API int moe_ffn_pick_tile_m(moe_dtype dt, int A, int E);
 
 MOE_API int moe_grouped_ffn(const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,
                     const void* const* w_in, const void* const* w_out,

@@ -29,7 +29,7 @@ MOE_OP_PERMUTE = 1
 
 EXPORTS = [
     "moe_route_topk", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_pack_weights",
-    "moe_ffn_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_unpermute_combine", "moe_prefetch_create",
+    "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_unpermute_combine", "moe_prefetch_create",
     "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_destroy",
     "moe_token_threshold", "moe_workspace_bytes", "moe_last_error", "moe_version",
 ]
@@ -41,6 +41,7 @@ lib.moe_plan_capacity.argtypes = [_i, _i, _i, _i]
 lib.moe_plan_tiles.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp]
 lib.moe_pack_weights.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp]
 lib.moe_ffn_tile_m.argtypes = [_i]
+lib.moe_ffn_pick_tile_m.argtypes = [_i, _i, _i]
 lib.moe_grouped_ffn.argtypes = [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp]
 lib.moe_grouped_ffn_phase.argtypes = [_i, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp]
 lib.moe_unpermute_combine.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp]
@@ -114,6 +115,10 @@ def moe_plan_capacity(A: int, E: int, tile_m: int, n_bins: int) -> int:
 
 def moe_ffn_tile_m(dt: int) -> int:
     return int(lib.moe_ffn_tile_m(dt))
+
+
+def moe_ffn_pick_tile_m(dt: int, A: int, E: int) -> int:
+    return int(lib.moe_ffn_pick_tile_m(dt, A, E))
 
 
 def moe_route_topk(x, w_gate, bias, T, d, E, k, renorm, dt, expert_idx, gate_w, logits_out=None, stream=None):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe.so")
-SOURCES = ["common.hip", "route.hip", "route_mfma.hip", "permute.hip", "plan.hip", "ffn.hip", "combine.hip", "pack.hip", "prefetch.hip"]
+SOURCES = ["common.hip", "route.hip", "route_mfma.hip", "permute.hip", "plan.hip", "ffn.hip", "ffn_bf16.hip", "combine.hip", "pack.hip", "prefetch.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -43,3 +43,32 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
 template <typename T> __device__ __forceinline__ float load_as_f32(const T* p);
 template <> __device__ __forceinline__ float load_as_f32<float>(const float* p) { return *p; }
 template <> __device__ __forceinline__ float load_as_f32<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
+
+// Wave-wide unsigned min / max / sum at ALU speed (all 64 lanes must be active): four DPP steps
+// reduce each row of 16 lanes (pairs, quads, half rows, rows), then the four row results are
+// combined through SGPRs.  Every lane gets the result.
+__device__ __forceinline__ unsigned moe_wave_min_u32(unsigned v) {
+    unsigned t;
+    t = __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xf, 0xf, false); v = t < v ? t : v;    // quad_perm [1,0,3,2]
+    t = __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xf, 0xf, false); v = t < v ? t : v;    // quad_perm [2,3,0,1]
+    t = __builtin_amdgcn_update_dpp(v, v, 0x141, 0xf, 0xf, false); v = t < v ? t : v;   // row_half_mirror
+    t = __builtin_amdgcn_update_dpp(v, v, 0x140, 0xf, 0xf, false); v = t < v ? t : v;   // row_mirror
+    unsigned a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    unsigned c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    a = a < b ? a : b;
+    c = c < d ? c : d;
+    return a < c ? a : c;
+}
+__device__ __forceinline__ unsigned moe_wave_max_u32(unsigned v) { return ~moe_wave_min_u32(~v); }
+__device__ __forceinline__ unsigned moe_wave_sum_u32(unsigned v) {
+    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false);
+    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false);
+    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xf, 0xf, false);
+    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xf, 0xf, false);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
+}
+// max of non-negative floats (their bit patterns order like unsigned integers)
+__device__ __forceinline__ float moe_wave_max_nonneg(float v) {
+    return __uint_as_float(moe_wave_max_u32(__float_as_uint(v)));
+}

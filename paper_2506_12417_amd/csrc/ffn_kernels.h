@@ -1,0 +1,13 @@
+// Internal interface between the FFN entry points (ffn.hip) and the bf16 MFMA kernels (ffn_bf16.hip).
+#pragma once
+#include "common.h"
+
+enum { MOE_EPI_RELU = 0, MOE_EPI_SWIGLU = 1, MOE_EPI_STORE = 2 };
+
+// persistent grid: one work-group per CU (256 CUs; 32 per XCD, dealt round-robin)
+constexpr int MOE_GEMM_GRID = 256;
+
+// out = epilogue(a . w_e^T) over the tile table.  epi: RELU / SWIGLU write bf16, STORE writes fp32.
+// tile_m: 128 or 256 (the tile height the table was planned with).
+int moe_launch_gemm_bf16(int epi, int tile_m, const void* a, int K, int N, const void* const* w,
+                         const moe_tile* tiles, const int32_t* hdr, void* out, int ld_out, hipStream_t st);

@@ -16,45 +16,20 @@ __device__ __forceinline__ int weight_of(int n, int q, bool by_cost) {
     return by_cost ? (n > 0 ? (n > q ? n : q) : 0) : n;
 }
 
-// Wave-wide unsigned min / max at ALU speed: four DPP steps reduce each row of 16 lanes
-// (pairs, quads, half rows, rows), then the four row results are combined through SGPRs.
-__device__ __forceinline__ unsigned wave_min_u32(unsigned v) {
-    unsigned t;
-    t = __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xf, 0xf, false); v = t < v ? t : v;    // quad_perm [1,0,3,2]
-    t = __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xf, 0xf, false); v = t < v ? t : v;    // quad_perm [2,3,0,1]
-    t = __builtin_amdgcn_update_dpp(v, v, 0x141, 0xf, 0xf, false); v = t < v ? t : v;   // row_half_mirror
-    t = __builtin_amdgcn_update_dpp(v, v, 0x140, 0xf, 0xf, false); v = t < v ? t : v;   // row_mirror
-    unsigned a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
-    unsigned c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
-    a = a < b ? a : b;
-    c = c < d ? c : d;
-    return a < c ? a : c;
-}
-__device__ __forceinline__ unsigned wave_max_u32(unsigned v) { return ~wave_min_u32(~v); }
-
 // Loads are kept below 2^26 so that (load << 5 | bin) fits 32 bits (bins < 32): one reduction gives both the
 // extreme load and, among equal loads, the lowest bin.
 constexpr int BIN_BITS = 5;
 __device__ __forceinline__ void argmin_bin(int tg, int lane, int G, int& g, int& v) {
     unsigned key = lane < G ? (((unsigned)tg << BIN_BITS) | (unsigned)lane) : 0xffffffffu;
-    key = wave_min_u32(key);
+    key = moe_wave_min_u32(key);
     g = (int)(key & ((1u << BIN_BITS) - 1u));
     v = (int)(key >> BIN_BITS);
 }
 __device__ __forceinline__ void argmax_bin(int tg, int lane, int G, int& g, int& v) {
     unsigned key = lane < G ? (((unsigned)tg << BIN_BITS) | (unsigned)(MOE_MAX_BINS - 1 - lane)) : 0u;
-    key = wave_max_u32(key);
+    key = moe_wave_max_u32(key);
     g = MOE_MAX_BINS - 1 - (int)(key & ((1u << BIN_BITS) - 1u));
     v = (int)(key >> BIN_BITS);
-}
-
-__device__ __forceinline__ unsigned wave_sum_u32(unsigned v) {
-    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false);
-    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false);
-    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xf, 0xf, false);
-    v += (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xf, 0xf, false);
-    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
-           __builtin_amdgcn_readlane(v, 48);
 }
 
 __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ counts,
@@ -144,7 +119,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     // ---- Alg. 2: move rows of the largest block of the most loaded bin to the least loaded bin
     if (tid < 64) {
         int tg = lane < G ? load[lane] : 0;
-        const int t_avg = (int)(wave_sum_u32((unsigned)tg) / (unsigned)G);
+        const int t_avg = (int)(moe_wave_sum_u32((unsigned)tg) / (unsigned)G);
         int moves = 0;
         if (policy == MOE_PLAN_BALANCED || policy == MOE_PLAN_HARMOENY) {
             const int gran = by_cost ? tile_m : 1;
@@ -158,11 +133,11 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
                     const int sv = S[e * G + g_max];
                     best = sv > best ? sv : best;
                 }
-                const int t_move = (int)wave_max_u32((unsigned)(best + 1)) - 1;
+                const int t_move = (int)moe_wave_max_u32((unsigned)(best + 1)) - 1;
                 unsigned first = 0xffffffffu;                    // lowest expert holding t_move rows
                 for (int e = lane; e < E; e += 64)
                     if (S[e * G + g_max] == t_move) { first = (unsigned)e; break; }
-                const int e_max = (int)wave_min_u32(first);
+                const int e_max = (int)moe_wave_min_u32(first);
                 if (t_move < q) break;
                 int g_min, t_min;
                 argmin_bin(tg, lane, G, g_min, t_min);

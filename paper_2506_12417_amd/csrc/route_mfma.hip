@@ -1,9 +1,9 @@
 // moe_route_topk for bf16 inputs: the router product on the matrix cores (Alg. 1 step 1).
 //
 // One work-group takes TB tokens (64, or 32 when E > 128).  Logits x.W_g are accumulated by
-// v_mfma_f32_32x32x16_bf16 in chunks of 32 terms (bf16 x bf16 products are exact in fp32); each
+// v_mfma_f32_32x32x16_bf16 in chunks of 64 terms (bf16 x bf16 products are exact in fp32); each
 // chunk's fp32 result is added into fp64 accumulators, so only the rounding inside a chunk
-// counts: |error| <= c * |x_t| * |w_e| with c = (2*32+6) * 2^-24 (two roundings per term allowed
+// counts: |error| <= c * |x_t| * |w_e| with c = (2*64+6) * 2^-24 (two roundings per term allowed
 // for, since the accumulation order inside the instruction is not specified).  A token whose
 // deciding gaps are all wider than twice that bound keeps its fp32 selection; the others get the
 // logits of every expert that could still reach the top k recomputed in fp64 by a wavefront, so
@@ -23,8 +23,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int NTH = 256;
-constexpr int KC = 32;                 // terms per fp32 chunk (two MFMAs)
-constexpr int PK = KC + 8;             // LDS pitch of a K-row in bf16 elements (80 B: conflict-free 16 B reads)
+constexpr int KC = 64;                 // terms per fp32 chunk (four MFMAs)
+constexpr int PK = KC + 8;             // LDS pitch of a K-row in bf16 elements (144 B: conflict-free 16 B reads)
 constexpr int MAXR = MOE_MAX_TOPK + 1;
 constexpr float NEG_INF = -__builtin_huge_valf();
 
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(NTH) void route_mfma_kernel(const uint16_t* __restr
     __shared__ __attribute__((aligned(16))) uint16_t xs[TB * PK];
     __shared__ __attribute__((aligned(16))) uint16_t wsT[EP * PK];
     __shared__ float ls[TB * PL];
-    __shared__ float xn2[TB], wn2[EP];
+    __shared__ float xn2[TB], part[NTH], red_w[4], red_b[4];
     __shared__ int flag_tok[TB];
     __shared__ float flag_thr[TB], flag_max[TB], flag_den[TB];
     __shared__ int n_flag;
@@ -103,7 +103,6 @@ __global__ __launch_bounds__(NTH) void route_mfma_kernel(const uint16_t* __restr
     const int wm = wave % MT, wn0 = wave / MT;
     const int t0 = blockIdx.x * TB;
 
-    for (int i = tid; i < EP; i += NTH) wn2[i] = 0.f;
     if (tid == 0) n_flag = 0;
 
     double acc64[NJ][16];
@@ -111,53 +110,60 @@ __global__ __launch_bounds__(NTH) void route_mfma_kernel(const uint16_t* __restr
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc64[j][r] = 0.0;
-    float xsq = 0.f;
-
-    // x staging: one 16-byte piece (8 terms) of one token per thread and chunk
-    const int s_tok = tid >> 2, s_kk = (tid & 3) * 8;
-    const bool s_on = s_tok < TB;
-    const int s_t = t0 + s_tok;
-    __syncthreads();
 
     // Register staging, one chunk ahead: the loads of chunk c+1 are in flight while chunk c is
-    // multiplied.  W_g piece u of a thread is element (kk, e) = ((tid + u*NTH) / EP, (tid + u*NTH) % EP).
+    // multiplied.  x: piece p = tid + u*NTH is 8 terms of token p / 8 at k offset (p % 8) * 8.
+    // W_g: piece u is element (kk, e) = ((tid + u*NTH) / EP, tid % EP) -- always the same column,
+    // so the column's sum of squares is kept in a register.
+    constexpr int XN = TB * (KC / 8) / NTH;
     constexpr int WN = KC * EP / NTH;
-    u32x4 xv = {0u, 0u, 0u, 0u};
+    u32x4 xv[XN];
     uint16_t wv[WN];
+    float xsq[XN], wsq = 0.f;
+#pragma unroll
+    for (int u2 = 0; u2 < XN; ++u2) xsq[u2] = 0.f;
+    const int w_e = tid % EP, w_kk0 = tid / EP;
     auto load_chunk = [&](int k0) {
-        xv = (u32x4){0u, 0u, 0u, 0u};
-        if (s_on && s_t < T && k0 + s_kk < d) xv = *(const u32x4*)(x + (size_t)s_t * d + k0 + s_kk);
+#pragma unroll
+        for (int u2 = 0; u2 < XN; ++u2) {
+            const int p = tid + u2 * NTH, tok = p >> 3, kk = (p & 7) * 8;
+            xv[u2] = (u32x4){0u, 0u, 0u, 0u};
+            if (t0 + tok < T && k0 + kk < d) xv[u2] = *(const u32x4*)(x + (size_t)(t0 + tok) * d + k0 + kk);
+        }
 #pragma unroll
         for (int u2 = 0; u2 < WN; ++u2) {
-            const int i = tid + u2 * NTH, kk = i / EP, e = i % EP;
-            wv[u2] = (e < E && k0 + kk < d) ? wg[(size_t)(k0 + kk) * E + e] : (uint16_t)0;
+            const int kk = w_kk0 + u2 * (NTH / EP);
+            wv[u2] = (w_e < E && k0 + kk < d) ? wg[(size_t)(k0 + kk) * E + w_e] : (uint16_t)0;
         }
     };
-    load_chunk(0);
+    // Work-groups start at different chunks: all of them reading the same 16 KB of W_g at the same
+    // moment would queue on a few L2 channels.
+    const int n_chunks = (d + KC - 1) / KC;
+    int chunk = blockIdx.x % n_chunks;
+    load_chunk(chunk * KC);
+    __syncthreads();
 
-    for (int k0 = 0; k0 < d; k0 += KC) {
-        if (s_on) {
-            *(u32x4*)(xs + s_tok * PK + s_kk) = xv;
+    for (int c = 0; c < n_chunks; ++c) {
+#pragma unroll
+        for (int u2 = 0; u2 < XN; ++u2) {
+            const int p = tid + u2 * NTH, tok = p >> 3, kk = (p & 7) * 8;
+            *(u32x4*)(xs + tok * PK + kk) = xv[u2];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                float lo = __uint_as_float(xv[i] << 16), hi = __uint_as_float(xv[i] & 0xffff0000u);
-                xsq = fmaf(lo, lo, xsq);
-                xsq = fmaf(hi, hi, xsq);
+                float lo = __uint_as_float(xv[u2][i] << 16), hi = __uint_as_float(xv[u2][i] & 0xffff0000u);
+                xsq[u2] = fmaf(lo, lo, xsq[u2]);
+                xsq[u2] = fmaf(hi, hi, xsq[u2]);
             }
         }
 #pragma unroll
         for (int u2 = 0; u2 < WN; ++u2) {             // W_g chunk, transposed into LDS
-            const int i = tid + u2 * NTH, kk = i / EP, e = i % EP;
-            wsT[e * PK + kk] = wv[u2];
+            wsT[w_e * PK + w_kk0 + u2 * (NTH / EP)] = wv[u2];
+            const float v = bf16_to_f32(wv[u2]);
+            wsq = fmaf(v, v, wsq);
         }
         __syncthreads();
-        if (k0 + KC < d) load_chunk(k0 + KC);
-        if (tid < E) {                                   // column norms, fixed order
-            float s = wn2[tid];
-#pragma unroll 8
-            for (int kk = 0; kk < KC; ++kk) { float v = bf16_to_f32(wsT[tid * PK + kk]); s = fmaf(v, v, s); }
-            wn2[tid] = s;
-        }
+        chunk = chunk + 1 == n_chunks ? 0 : chunk + 1;
+        if (c + 1 < n_chunks) load_chunk(chunk * KC);
         f32x16 acc[NJ];
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
@@ -179,12 +185,16 @@ __global__ __launch_bounds__(NTH) void route_mfma_kernel(const uint16_t* __restr
         __syncthreads();
     }
 
-    // ---- logits to LDS (fp32), token norms
-    if (s_on) {
-        xsq += __shfl_xor(xsq, 1);
-        xsq += __shfl_xor(xsq, 2);
-        if ((tid & 3) == 0) xn2[s_tok] = xsq;
+    // ---- logits to LDS (fp32), token and column norms
+#pragma unroll
+    for (int u2 = 0; u2 < XN; ++u2) {              // the 8 threads of a token row are neighbours
+        float v = xsq[u2];
+        v += dpp_xchg<0>(v);
+        v += dpp_xchg<1>(v);
+        v += dpp_xchg<2>(v);
+        if ((tid & 7) == 0) xn2[(tid + u2 * NTH) >> 3] = v;
     }
+    part[tid] = wsq;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         const int e = (wn0 + NW * j) * 32 + l32;
@@ -201,9 +211,20 @@ __global__ __launch_bounds__(NTH) void route_mfma_kernel(const uint16_t* __restr
     }
     __syncthreads();
 
-    float wmax2 = 0.f, bmax = 0.f;
-    for (int e = 0; e < E; ++e) wmax2 = fmaxf(wmax2, wn2[e]);      // broadcast reads
-    if (bias) for (int e = 0; e < E; ++e) bmax = fmaxf(bmax, fabsf(bias[e]));
+    {   // largest column norm and largest |bias|, reduced in parallel
+        float w2 = 0.f, bm = 0.f;
+        if (tid < E) {
+#pragma unroll
+            for (int j = 0; j < NTH / EP; ++j) w2 += part[tid + j * EP];
+            if (bias) bm = fabsf(bias[tid]);
+        }
+        w2 = moe_wave_max_nonneg(w2);
+        bm = moe_wave_max_nonneg(bm);
+        if (lane == 0) { red_w[wave] = w2; red_b[wave] = bm; }
+    }
+    __syncthreads();
+    const float wmax2 = fmaxf(fmaxf(red_w[0], red_w[1]), fmaxf(red_w[2], red_w[3]));
+    const float bmax = fmaxf(fmaxf(red_b[0], red_b[1]), fmaxf(red_b[2], red_b[3]));
     const float wn_max = sqrtf(wmax2) * 1.0001f;
     const int rounds = (k + 1 < E) ? k + 1 : E;
     const float u = 5.9604645e-8f;   // 2^-24
@@ -299,10 +320,19 @@ __global__ __launch_bounds__(NTH) void route_mfma_kernel(const uint16_t* __restr
             while (mask) {
                 const int ce = e0 + (int)__builtin_ctzll(mask);
                 mask &= mask - 1;
-                double part = 0.0;
-                for (int i = lane; i < d; i += 64)
-                    part = fma((double)bf16_to_f32(xr[i]), (double)bf16_to_f32(wg[(size_t)i * E + ce]), part);
-                const double tot = wave_sum_f64(part) + (bias ? (double)bias[ce] : 0.0);
+                double psum = 0.0;
+                for (int i0 = lane; i0 < d; i0 += 64 * 8) {      // 16 loads in flight per lane
+                    float xa[8], wa[8];
+#pragma unroll
+                    for (int u2 = 0; u2 < 8; ++u2) {
+                        const int i = i0 + 64 * u2;
+                        xa[u2] = i < d ? bf16_to_f32(xr[i]) : 0.f;
+                        wa[u2] = i < d ? bf16_to_f32(wg[(size_t)i * E + ce]) : 0.f;
+                    }
+#pragma unroll
+                    for (int u2 = 0; u2 < 8; ++u2) psum = fma((double)xa[u2], (double)wa[u2], psum);
+                }
+                const double tot = wave_sum_f64(psum) + (bias ? (double)bias[ce] : 0.0);
                 if (lane == 0) { cand_v[wave][nc] = tot; cand_e[wave][nc] = ce; }
                 ++nc;
             }
@@ -362,7 +392,8 @@ int launch(const void* x, const void* wg, const float* bias, int T, int d, int E
 // bf16 path of moe_route_topk (arguments already validated by the caller)
 int moe_route_bf16_mfma(const void* x, const void* wg, const float* bias, int T, int d, int E, int k, int renorm,
                         int32_t* idx, float* w, float* logits, hipStream_t st) {
-    if (E <= 64) return launch<2, 1>(x, wg, bias, T, d, E, k, renorm, idx, w, logits, st);
-    if (E <= 128) return launch<2, 2>(x, wg, bias, T, d, E, k, renorm, idx, w, logits, st);
+    // 32 tokens per work-group: twice the work-groups, so that two or three share a CU and hide
+    // each other's load latency
+    if (E <= 128) return launch<1, 1>(x, wg, bias, T, d, E, k, renorm, idx, w, logits, st);
     return launch<1, 2>(x, wg, bias, T, d, E, k, renorm, idx, w, logits, st);
 }

@@ -64,7 +64,7 @@ class ExpertGroup:
 class MoELayer:
     def __init__(self, T: int, d: int, F: int, E: int, k: int, act: str, dtype: str, renorm: int,
                  shared_F: int = 0, n_bins: int = XCDS, q_tokens: Optional[int] = None,
-                 policy: int = B.MOE_PLAN_BALANCED, device="cuda:0"):
+                 policy: int = B.MOE_PLAN_BALANCED, tile_m: Optional[int] = None, device="cuda:0"):
         self.T, self.d, self.F, self.E, self.k, self.renorm = T, d, F, E, k, renorm
         self.A = T * k
         self.act = B.MOE_SWIGLU if act == "swiglu" else B.MOE_RELU
@@ -72,7 +72,7 @@ class MoELayer:
         self.tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.n_bins, self.policy = n_bins, policy
         self.q_tokens = q_tokens if q_tokens is not None else default_q_tokens(self.dt)
-        self.tile_m = B.moe_ffn_tile_m(self.dt)
+        self.tile_m = tile_m if tile_m is not None else B.moe_ffn_pick_tile_m(self.dt, self.A, E)
         self.device = torch.device(device)
         dev, A = self.device, self.A
         i32, f32 = torch.int32, torch.float32
@@ -101,12 +101,13 @@ class MoELayer:
             self.shared = ExpertGroup(1, d, shared_F, B.MOE_SWIGLU, self.dt, dev)
             self.s_counts = torch.tensor([T], dtype=i32).to(dev)
             self.s_offsets = torch.tensor([0, T], dtype=i32).to(dev)
-            self.s_capacity = B.moe_plan_capacity(T, 1, self.tile_m, n_bins)
+            self.s_tile_m = B.moe_ffn_pick_tile_m(self.dt, T, 1)
+            self.s_capacity = B.moe_plan_capacity(T, 1, self.s_tile_m, n_bins)
             self.s_tiles = torch.empty((self.s_capacity, 4), dtype=i32, device=dev)
             self.s_hdr = torch.empty(B.MOE_PLAN_HDR_INTS, dtype=i32, device=dev)
             self.s_h = torch.empty((T, shared_F), dtype=self.tdt, device=dev)
             self.s_y = torch.empty((T, d), dtype=f32, device=dev)
-            B.moe_plan_tiles(self.s_counts, self.s_offsets, 1, T, self.tile_m, n_bins, self.q_tokens,
+            B.moe_plan_tiles(self.s_counts, self.s_offsets, 1, T, self.s_tile_m, n_bins, self.q_tokens,
                              B.MOE_PLAN_BALANCED, self.s_tiles, self.s_capacity, self.s_hdr, None)
 
     # ------------------------------------------------------------------ parameters
@@ -148,7 +149,7 @@ class MoELayer:
     def shared_ffn(self, x, stream=None):
         g = self.shared
         B.moe_grouped_ffn(x, self.T, self.d, self.shared_F, 1, B.MOE_SWIGLU, self.dt, g.in_ptrs, g.out_ptrs,
-                          self.s_tiles, self.s_hdr, self.tile_m, self.s_h, self.s_y, stream)
+                          self.s_tiles, self.s_hdr, self.s_tile_m, self.s_h, self.s_y, stream)
 
     def combine(self, use_gate: bool = True, stream=None):
         B.moe_unpermute_combine(self.y_perm, self.inv_perm, self.gate_w if use_gate else None,
