@@ -3,25 +3,31 @@
 //
 //   out[r, n] = epilogue( sum_k a[r, k] * w_e[n, k] )      r in a tile of expert e
 //
-// Persistent launch, one work-group (4 wavefronts, 2 x 2) per CU.  Work-group b serves bin
-// b % n_bins: work-groups are dealt round-robin to the 8 XCDs, so a bin's tiles -- and with them
-// an expert's weights -- stay inside one XCD's L2.  Inside a bin the work items (tile, column
-// block) are taken column-block-major with a fixed stride.
+// Persistent launch, one work-group of 8 wavefronts (2 per SIMD) per CU.  Work-group b serves
+// bin b % n_bins: work-groups are dealt round-robin to the 8 XCDs, so a bin's tiles -- and with
+// them an expert's weights -- stay inside one XCD's L2.  Inside a bin the work items
+// (tile, column block) are taken column-block-major with a fixed stride.
 //
-// Two shapes of the same kernel:
-//   BM=128, BN=256  wavefront tile  64 x 128 (2 x 4 MFMA blocks)  -- experts with few rows
-//   BM=256, BN=256  wavefront tile 128 x 128 (4 x 4 MFMA blocks)  -- many rows per expert
-// A wavefront tile that large keeps the LDS operand traffic (one 16-byte read feeds 2 to 4
-// v_mfma_f32_32x32x16_bf16) below the LDS bandwidth.
+// A work-group's items form ONE stream of K-steps: the operand loads run RING-1 steps ahead of
+// the arithmetic and cross item boundaries, so the next item's first tiles are already on their
+// way while the current item is finished and stored.
 //
-// Operands go global -> LDS directly (global_load_lds_dwordx4: each lane fetches 16 bytes, a
-// wavefront fills 1 KB of LDS in lane order) into a ring of stages, so several K-steps of loads
-// are in flight while one is multiplied; the stage barrier is a bare s_barrier, since a fence
-// would drain the loads still in flight.  LDS layout of an operand tile: row r holds BK bf16
-// (PPR pieces of 16 bytes), piece p stored at position p ^ swz(r); the swizzle is chosen so
-// that the MFMA operand reads of 16 consecutive rows touch all 64 banks once, and it is applied
-// on the global side (which piece a lane fetches).  Inside a K-step the operand reads of the
-// next 16-wide slice are issued before the MFMAs of the current one.
+// Operands go global -> LDS directly (buffer_load_dwordx4 ... lds: each lane fetches 16 bytes, a
+// wavefront fills 1 KB of LDS in lane order).  The loads go through buffer descriptors that
+// cover exactly the rows of the tile (and of the column block): rows past the end read as zero
+// and stores past the end are dropped by the hardware's range check, so ragged tiles need no
+// clamping, and all per-load address arithmetic is scalar.
+//
+// LDS layout of an operand tile: row r holds BK bf16 (PPR pieces of 16 bytes), piece p stored
+// at position p ^ swz(r); the swizzle is chosen so that the MFMA operand reads of 16 consecutive
+// rows touch all 64 banks once, and it is applied on the global side (which piece a lane
+// fetches).
+//
+// One K-step: the fragments of its first 16-wide slice are already in registers.  Slices are
+// multiplied while the next slice's fragments are read; before the last slice the wavefronts
+// meet (the next stage has landed everywhere and the current stage has been read by everyone),
+// refill the stage just freed, and read the first fragments of the next stage, so the matrix
+// cores stay busy across the barrier.
 #include "common.h"
 #include "ffn_kernels.h"
 
@@ -30,179 +36,247 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void gbl_void_t;
 
 // s_waitcnt on vmcnt only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
 #define MOE_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+// s_waitcnt on lgkmcnt only
+#define MOE_WAIT_LGKMCNT(n) __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (((n) & 0xF) << 8))
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.f + __expf(-z)); }
 
-template <int BM, int BN, int BK, int RING>
+// raw buffer descriptor over [p, p + bytes): offsets beyond `bytes` read 0 / are not written
+// (pointer and size are wave-uniform; readfirstlane tells the compiler so)
+__device__ __forceinline__ int sgpr(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ const void* sgpr_ptr(const void* p) {
+    const uint64_t u = (uint64_t)p;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)u);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(u >> 32));
+    return (const void*)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(sgpr_ptr(p)), 0, sgpr((int)bytes), 0x00020000);
+}
+
+template <int BM_, int BN_, int BK_, int RING_, int WM_, int WN_>
 struct Cfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, RING = RING_, WM = WM_, WN = WN_;
+    static constexpr int NW = WM * WN, NTH = NW * 64;
     static constexpr int PPR = BK / 8;                    // 16-byte pieces per row
     static constexpr int ROW_BYTES = BK * 2;
     static constexpr int WRAP = 256 / ROW_BYTES;          // rows per 256 bytes (one sweep of the banks)
     static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int NA = BM * PPR / 256, NB = BN * PPR / 256;   // loads per thread and stage
-    static constexpr int WTM = BM / 2, WTN = BN / 2;      // wavefront tile
+    static constexpr int NA = A_BYTES / (NTH * 16), NB = B_BYTES / (NTH * 16);   // loads per thread and stage
+    static constexpr int LPS = NA + NB;
+    static constexpr int ROWS_PER_PASS = NTH / PPR;       // operand rows one pass of the work-group's loads covers
+    static constexpr int WTM = BM / WM, WTN = BN / WN;    // wavefront tile
     static constexpr int MI = WTM / 32, NI = WTN / 32;
+    static constexpr int KS = BK / 16;                    // 16-wide slices per K-step
     static constexpr size_t SMEM = (size_t)RING * STAGE_BYTES;
+    static_assert(NA >= 1 && NB >= 1 && A_BYTES % (NTH * 16) == 0 && B_BYTES % (NTH * 16) == 0, "tile vs threads");
+    static_assert(ROWS_PER_PASS % (WRAP * PPR) == 0 && 32 % (WRAP * PPR) == 0, "swizzle period");
+    static_assert(KS % 2 == 0, "fragment double buffer needs an even number of slices");
+    static_assert(LPS * (RING - 2 > 0 ? RING - 2 : 0) < 64 && RING <= 4, "vmcnt range");
     __device__ static __forceinline__ int swz(int r) { return (r / WRAP) & (PPR - 1); }
 };
 
-template <int EPI, int BM, int BN, int BK, int RING>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __restrict__ a_mat, int K, int N,
-                                                           const void* const* __restrict__ w_ptrs,
-                                                           const moe_tile* __restrict__ tiles,
-                                                           const int32_t* __restrict__ hdr, void* __restrict__ out,
-                                                           int ld_out) {
-    using C = Cfg<BM, BN, BK, RING>;
+// (The body is a __device__ function: it uses buffer-descriptor types that exist only on the
+// device side, and the host pass must still be able to instantiate the kernel's stub.)
+template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN>
+__device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_mat, int K, int N,
+                                               const void* const* __restrict__ w_ptrs,
+                                               const moe_tile* __restrict__ tiles, const int32_t* __restrict__ hdr,
+                                               void* __restrict__ out, int ld_out) {
+    using C = Cfg<BM, BN, BK, RING, WM, WN>;
+    constexpr int MI = C::MI, NI = C::NI, KS = C::KS;
     extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = sgpr(tid >> 6);
+    const int wm = wave / C::WN, wn = wave % C::WN;       // the two wavefronts of a SIMD (w, w+4) differ in wm
     const int l32 = lane & 31, lhi = lane >> 5;
     const int n_col_blocks = (N + BN - 1) / BN;
     const int KT = K / BK;
 
-    // the bin's work list
+    // the bin's work list and this work-group's share of it
     const int G = hdr[1];
     const int bin = blockIdx.x % G;
     const int stride = ((int)gridDim.x - bin + G - 1) / G;
+    const int first = blockIdx.x / G;
     const int bin_start = hdr[4 + bin];
     const int n_tiles = hdr[4 + bin + 1] - bin_start;
     const int n_items = n_tiles * n_col_blocks;
+    if (first >= n_items) return;
+    const int total = ((n_items - first + stride - 1) / stride) * KT;   // K-steps of this work-group
 
-    for (int item = blockIdx.x / G; item < n_items; item += stride) {
+    // ---- loader.  Piece id = i * NTH + tid of an operand tile: row id / PPR, position id % PPR;
+    // the swizzle does not depend on i, so one per-lane offset serves every load of a stage.
+    const int ld_row = tid / C::PPR;
+    // The row part of an address must sit in the per-lane offset: only that one is range-checked.
+    constexpr int NPASS = C::NA > C::NB ? C::NA : C::NB;
+    unsigned ld_voff[NPASS];
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i)
+        ld_voff[i] = (unsigned)(ld_row + i * C::ROWS_PER_PASS) * (unsigned)K * 2u +
+                     (unsigned)(((tid % C::PPR) ^ C::swz(ld_row)) << 4);
+    __amdgpu_buffer_rsrc_t l_ra, l_rb;
+    int l_item = first, l_kt = 0, l_buf = 0, issued = 0;
+    auto load_item = [&](int it) {
+        const int cb = it / n_tiles;
+        const moe_tile t = tiles[bin_start + (it - cb * n_tiles)];
+        const int rc = t.row_count < BM ? t.row_count : BM;
+        const int n0 = cb * BN;
+        const int nr = N - n0 < BN ? N - n0 : BN;
+        const uint16_t* wmat = (const uint16_t*)w_ptrs[t.expert];
+        l_ra = make_rsrc(a_mat + (size_t)t.row_begin * K, (unsigned)(rc > 0 ? rc : 0) * (unsigned)K * 2u);
+        l_rb = make_rsrc(wmat + (size_t)n0 * K, (unsigned)nr * (unsigned)K * 2u);
+    };
+    auto issue = [&]() {
+        unsigned char* st = ring + l_buf * C::STAGE_BYTES + wave * 1024;
+        const unsigned k_off = (unsigned)l_kt * (BK * 2);
+#pragma unroll
+        for (int i = 0; i < C::NA; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(l_ra, (lds_void_t*)(st + i * (C::NW * 1024)), 16, ld_voff[i],
+                                                     k_off, 0, 0);
+#pragma unroll
+        for (int i = 0; i < C::NB; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(l_rb, (lds_void_t*)(st + C::A_BYTES + i * (C::NW * 1024)), 16,
+                                                     ld_voff[i], k_off, 0, 0);
+        ++issued;
+        l_buf = l_buf + 1 == RING ? 0 : l_buf + 1;
+        if (++l_kt == KT) {
+            l_kt = 0;
+            l_item += stride;
+            if (l_item < n_items) load_item(l_item);
+        }
+    };
+
+    // ---- operand fragment reads.  Row r of a 32-row block is read by lanes r and r + 32 (the
+    // two 8-wide halves of a 16-wide slice); the swizzle depends on r % 32 only.
+    const int sw = C::swz(l32);
+    int a_rd[KS], b_rd[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const int piece = ((ks * 2 + lhi) ^ sw) << 4;
+        a_rd[ks] = (wm * C::WTM + l32) * C::ROW_BYTES + piece;
+        b_rd[ks] = C::A_BYTES + (wn * C::WTN + l32) * C::ROW_BYTES + piece;
+    }
+    bf16x8 af[2][MI], bf[2][NI];
+    auto fetch = [&](int buf, int ks, int fb) {
+        const unsigned char* st = ring + buf * C::STAGE_BYTES;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) af[fb][mi] = *(const bf16x8*)(st + a_rd[ks] + mi * 32 * C::ROW_BYTES);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) bf[fb][ni] = *(const bf16x8*)(st + b_rd[ks] + ni * 32 * C::ROW_BYTES);
+    };
+
+    // ---- prologue: every stage of the ring on its way, the first one landed and its first
+    // fragments read
+    load_item(first);
+#pragma unroll
+    for (int s = 0; s < RING; ++s)
+        if (issued < total) issue();
+    {
+        const int younger = issued - 1;
+        if (RING >= 3 && younger >= 2) MOE_WAIT_VMCNT(2 * C::LPS);
+        else if (RING >= 2 && younger >= 1) MOE_WAIT_VMCNT(C::LPS);
+        else MOE_WAIT_VMCNT(0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        fetch(0, 0, 0);
+    }
+
+    int g = 0, c_buf = 0;                                  // K-step counter of the stream, its stage
+    for (int item = first; item < n_items; item += stride) {
         const int cb = item / n_tiles;
         const moe_tile tile = tiles[bin_start + (item - cb * n_tiles)];
-        const int rc = tile.row_count;
-        if (rc <= 0) continue;
+        const int rc = sgpr(tile.row_count < BM ? tile.row_count : BM);
         const int n0 = cb * BN;
-        const uint16_t* __restrict__ wmat = (const uint16_t*)w_ptrs[tile.expert];
+        // 32-row blocks of this wavefront that hold real rows (wave-uniform)
+        int mi_on = (rc - wm * C::WTM + 31) / 32;
+        mi_on = mi_on < 0 ? 0 : (mi_on > MI ? MI : mi_on);
 
-        // loader role: piece id = i*256 + tid -> row id / PPR, position id % PPR of the operand tile
-        const uint16_t* a_src[C::NA];
-        const uint16_t* b_src[C::NB];
+        f32x16 acc[MI][NI];
 #pragma unroll
-        for (int i = 0; i < C::NA; ++i) {
-            const int id = i * 256 + tid, r = id / C::PPR, kv = (id % C::PPR) ^ C::swz(r);
-            a_src[i] = a_mat + (size_t)(tile.row_begin + (r < rc ? r : rc - 1)) * K + kv * 8;
-        }
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int i = 0; i < C::NB; ++i) {
-            const int id = i * 256 + tid, r = id / C::PPR, kv = (id % C::PPR) ^ C::swz(r);
-            b_src[i] = wmat + (size_t)(n0 + r < N ? n0 + r : N - 1) * K + kv * 8;
-        }
-        auto issue = [&](int kt) {
-            unsigned char* st = ring + (kt % RING) * C::STAGE_BYTES + wave * 1024;
-#pragma unroll
-            for (int i = 0; i < C::NA; ++i)
-                __builtin_amdgcn_global_load_lds((gbl_void_t*)(a_src[i] + (size_t)kt * BK), (lds_void_t*)(st + i * 4096), 16, 0, 0);
-#pragma unroll
-            for (int i = 0; i < C::NB; ++i)
-                __builtin_amdgcn_global_load_lds((gbl_void_t*)(b_src[i] + (size_t)kt * BK),
-                                                 (lds_void_t*)(st + C::A_BYTES + i * 4096), 16, 0, 0);
-        };
-
-        f32x16 acc[C::MI][C::NI];
-#pragma unroll
-        for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < C::NI; ++ni)
+            for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-        // operand read offsets of this lane (bytes, without the piece position)
-        int a_off[C::MI], a_swz[C::MI], b_off[C::NI], b_swz[C::NI];
+        auto mfmas = [&](int fb) {
 #pragma unroll
-        for (int mi = 0; mi < C::MI; ++mi) {
-            const int r = wm * C::WTM + mi * 32 + l32;
-            a_off[mi] = r * C::ROW_BYTES;
-            a_swz[mi] = C::swz(r);
-        }
+            for (int mi = 0; mi < MI; ++mi) {
+                if (mi < mi_on) {
 #pragma unroll
-        for (int ni = 0; ni < C::NI; ++ni) {
-            const int r = wn * C::WTN + ni * 32 + l32;
-            b_off[ni] = C::A_BYTES + r * C::ROW_BYTES;
-            b_swz[ni] = C::swz(r);
-        }
-        // 32-row blocks of this wavefront that hold real rows (wave-uniform)
-        int mi_on = (rc - wm * C::WTM + 31) / 32;
-        mi_on = mi_on < 0 ? 0 : (mi_on > C::MI ? C::MI : mi_on);
+                    for (int ni = 0; ni < NI; ++ni)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fb][mi], bf[fb][ni], acc[mi][ni], 0, 0, 0);
+                }
+            }
+        };
 
-        __syncthreads();                                       // the previous item's LDS reads are done
+        for (int kt = 0; kt < KT; ++kt, ++g) {
 #pragma unroll
-        for (int s = 0; s < RING - 1; ++s)
-            if (s < KT) issue(s);
-
-        constexpr int LPS = C::NA + C::NB;                     // loads per thread and stage
-        for (int kt = 0; kt < KT; ++kt) {
-            // stage kt has landed once only the younger stages' loads are outstanding
-            const int younger = KT - 1 - kt < RING - 2 ? KT - 1 - kt : RING - 2;
-            if (RING >= 4 && younger >= 2) MOE_WAIT_VMCNT(2 * LPS);
-            else if (RING >= 3 && younger == 1) MOE_WAIT_VMCNT(LPS);
-            else MOE_WAIT_VMCNT(0);
+            for (int ks = 0; ks < KS - 1; ++ks) {
+                fetch(c_buf, ks + 1, (ks + 1) & 1);
+                mfmas(ks & 1);
+            }
+            // Before the last slice: its fragments are in registers (every read of stage g is done),
+            // stage g+1 must have landed everywhere; then stage g's buffer is refilled.
+            const int n_buf = c_buf + 1 == RING ? 0 : c_buf + 1;
+            const bool more = g + 1 < total;
+            if (more) {
+                const int younger = issued - g - 2;            // stages after g+1 still on their way
+                if (RING >= 4 && younger >= 2) MOE_WAIT_VMCNT(2 * C::LPS);
+                else if (RING >= 3 && younger >= 1) MOE_WAIT_VMCNT(C::LPS);
+                else MOE_WAIT_VMCNT(0);
+            }
+            MOE_WAIT_LGKMCNT(0);
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            if (kt + RING - 1 < KT) issue(kt + RING - 1);      // refills the stage consumed at kt-1
-            const unsigned char* st = ring + (kt % RING) * C::STAGE_BYTES;
-            if (mi_on > 0) {
-                bf16x8 af[2][C::MI], bf[2][C::NI];
-                auto fetch = [&](int ks, int buf) {
-                    const int kv = ks * 2 + lhi;
-#pragma unroll
-                    for (int mi = 0; mi < C::MI; ++mi)
-                        if (mi < mi_on) af[buf][mi] = *(const bf16x8*)(st + a_off[mi] + ((kv ^ a_swz[mi]) << 4));
-#pragma unroll
-                    for (int ni = 0; ni < C::NI; ++ni)
-                        bf[buf][ni] = *(const bf16x8*)(st + b_off[ni] + ((kv ^ b_swz[ni]) << 4));
-                };
-                fetch(0, 0);
-#pragma unroll
-                for (int ks = 0; ks < BK / 16; ++ks) {
-                    if (ks + 1 < BK / 16) fetch(ks + 1, (ks + 1) & 1);
-#pragma unroll
-                    for (int mi = 0; mi < C::MI; ++mi) {
-                        if (mi < mi_on) {
-#pragma unroll
-                            for (int ni = 0; ni < C::NI; ++ni)
-                                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][mi], bf[ks & 1][ni],
-                                                                                     acc[mi][ni], 0, 0, 0);
-                        }
-                    }
-                }
-            }
+            if (issued < total) issue();
+            if (more) fetch(n_buf, 0, 0);
+            mfmas((KS - 1) & 1);
+            c_buf = n_buf;
         }
 
-        // ---- epilogue.  acc[mi][ni][r]: row 8*(r/4) + 4*lhi + r%4, column l32 of the 32x32 block
+        // ---- epilogue.  acc[mi][ni][r]: row 8*(r/4) + 4*lhi + r%4, column l32 of the 32x32 block.
+        // Stores go through a descriptor that ends with the tile's last row.
+        constexpr int ES = EPI == MOE_EPI_STORE ? 4 : 2;
+        const unsigned ld_bytes = (unsigned)ld_out * ES;
+        const __amdgpu_buffer_rsrc_t ro =
+            make_rsrc((const unsigned char*)out + (size_t)tile.row_begin * ld_bytes, (unsigned)(rc > 0 ? rc : 0) * ld_bytes);
+        // (the row part of a store's address is range-checked only in the per-lane offset)
+        const unsigned st_voff = (unsigned)(wm * C::WTM + 4 * lhi) * ld_bytes + (unsigned)l32 * ES;
 #pragma unroll
-        for (int mi = 0; mi < C::MI; ++mi) {
+        for (int mi = 0; mi < MI; ++mi) {
+            if (mi >= mi_on) continue;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = wm * C::WTM + mi * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-                if (row >= rc) continue;
-                const size_t grow = (size_t)(tile.row_begin + row);
+                const unsigned row_off = (unsigned)(mi * 32 + 8 * (r >> 2) + (r & 3)) * ld_bytes;
                 if (EPI == MOE_EPI_SWIGLU) {
                     // packed weight rows alternate in blocks of 32: gate, up, gate, up, ...
 #pragma unroll
-                    for (int ni = 0; ni < C::NI; ni += 2) {
+                    for (int ni = 0; ni < NI; ni += 2) {
                         const int pc = n0 + wn * C::WTN + ni * 32;          // packed column of the gate block
                         if (pc < N) {
                             const float h = silu_f(acc[mi][ni][r]) * acc[mi][ni + 1][r];
-                            ((uint16_t*)out)[grow * ld_out + pc / 2 + l32] = f32_to_bf16(h);
+                            __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(h), ro, st_voff + row_off,
+                                                                  (unsigned)(pc / 2) * 2u, 0);
                         }
                     }
                 } else {
 #pragma unroll
-                    for (int ni = 0; ni < C::NI; ++ni) {
-                        const int col = n0 + wn * C::WTN + ni * 32 + l32;
+                    for (int ni = 0; ni < NI; ++ni) {
+                        const int col = n0 + wn * C::WTN + ni * 32;
                         if (col < N) {
                             if (EPI == MOE_EPI_RELU)
-                                ((uint16_t*)out)[grow * ld_out + col] = f32_to_bf16(fmaxf(acc[mi][ni][r], 0.f));
+                                __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(fmaxf(acc[mi][ni][r], 0.f)), ro,
+                                                                      st_voff + row_off, (unsigned)col * 2u, 0);
                             else
-                                ((float*)out)[grow * ld_out + col] = acc[mi][ni][r];
+                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mi][ni][r]), ro,
+                                                                      st_voff + row_off, (unsigned)col * 4u, 0);
                         }
                     }
                 }
@@ -211,26 +285,38 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     }
 }
 
-template <int EPI, int BM, int BN, int BK, int RING>
+template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(const uint16_t* __restrict__ a_mat, int K, int N,
+                                                                  const void* const* __restrict__ w_ptrs,
+                                                                  const moe_tile* __restrict__ tiles,
+                                                                  const int32_t* __restrict__ hdr, void* __restrict__ out,
+                                                                  int ld_out) {
+    gemm_bf16_body<EPI, BM, BN, BK, RING, WM, WN>(a_mat, K, N, w_ptrs, tiles, hdr, out, ld_out);
+}
+
+template <int EPI, class C>
 int launch(const void* a, int K, int N, const void* const* w, const moe_tile* tiles, const int32_t* hdr, void* out,
            int ld_out, hipStream_t st) {
-    using C = Cfg<BM, BN, BK, RING>;
     static_assert(C::SMEM <= 160 * 1024, "LDS ring too large");
-    auto kern = gemm_bf16_kernel<EPI, BM, BN, BK, RING>;
+    auto kern = gemm_bf16_kernel<EPI, C::BM, C::BN, C::BK, C::RING, C::WM, C::WN>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)C::SMEM);
     if (e != hipSuccess) return moe_fail(MOE_ERR_HIP, "moe_grouped_ffn: shared memory attribute: %s", hipGetErrorString(e));
-    hipLaunchKernelGGL(kern, dim3(MOE_GEMM_GRID), dim3(256), C::SMEM, st, (const uint16_t*)a, K, N, w, tiles, hdr, out,
+    hipLaunchKernelGGL(kern, dim3(MOE_GEMM_GRID), dim3(C::NTH), C::SMEM, st, (const uint16_t*)a, K, N, w, tiles, hdr, out,
                        ld_out);
     MOE_CHECK_LAUNCH("moe_grouped_ffn (bf16 GEMM)");
     return MOE_OK;
 }
 
+//                 BM   BN  BK RING WM WN
+typedef Cfg<256, 256, 32, 4, 2, 4> Tall;     // wavefront tile 128 x 64
+typedef Cfg<128, 256, 64, 3, 2, 4> Short;    // wavefront tile  64 x 64
+
 template <int EPI>
 int launch_tile(int tile_m, const void* a, int K, int N, const void* const* w, const moe_tile* tiles,
                 const int32_t* hdr, void* out, int ld_out, hipStream_t st) {
-    if (tile_m == 256) return launch<EPI, 256, 256, 32, 4>(a, K, N, w, tiles, hdr, out, ld_out, st);
-    return launch<EPI, 128, 256, 64, 3>(a, K, N, w, tiles, hdr, out, ld_out, st);
+    if (tile_m == 256) return launch<EPI, Tall>(a, K, N, w, tiles, hdr, out, ld_out, st);
+    return launch<EPI, Short>(a, K, N, w, tiles, hdr, out, ld_out, st);
 }
 
 }  // namespace
