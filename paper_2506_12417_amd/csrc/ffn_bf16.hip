@@ -16,18 +16,22 @@
 // wavefront fills 1 KB of LDS in lane order).  The loads go through buffer descriptors that
 // cover exactly the rows of the tile (and of the column block): rows past the end read as zero
 // and stores past the end are dropped by the hardware's range check, so ragged tiles need no
-// clamping, and all per-load address arithmetic is scalar.
+// clamping, and the per-load address arithmetic is scalar.  A K-step is 64 wide: one full
+// 128-byte line per row.
 //
 // LDS layout of an operand tile: row r holds BK bf16 (PPR pieces of 16 bytes), piece p stored
 // at position p ^ swz(r); the swizzle is chosen so that the MFMA operand reads of 16 consecutive
 // rows touch all 64 banks once, and it is applied on the global side (which piece a lane
 // fetches).
 //
-// One K-step: the fragments of its first 16-wide slice are already in registers.  Slices are
-// multiplied while the next slice's fragments are read; before the last slice the wavefronts
-// meet (the next stage has landed everywhere and the current stage has been read by everyone),
-// refill the stage just freed, and read the first fragments of the next stage, so the matrix
-// cores stay busy across the barrier.
+// Schedule.  The two wavefronts of a SIMD alternate: while one multiplies a chunk of a K-step
+// (its operand fragments are in registers), the other reads the fragments of its next chunk from
+// LDS, issues its share of the next stage's loads and -- at an item boundary -- stores the
+// finished item.  The wavefronts 0-3 ("group 0") run one phase ahead of the wavefronts 4-7; a
+// work-group barrier closes every phase, so the matrix cores always have exactly one wavefront
+// per SIMD feeding them and never wait for an LDS read.  Both groups execute the same number of
+// barriers: group 1 one more at the start, group 0 one more at the end.
+#include <type_traits>
 #include "common.h"
 #include "ffn_kernels.h"
 
@@ -57,9 +61,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(sgpr_ptr(p)), 0, sgpr((int)bytes), 0x00020000);
 }
 
-template <int BM_, int BN_, int BK_, int RING_, int WM_, int WN_>
+template <int BM_, int BN_, int BK_, int RING_, int WM_, int WN_, int CS_>
 struct Cfg {
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, RING = RING_, WM = WM_, WN = WN_;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, RING = RING_, WM = WM_, WN = WN_, CS = CS_;
     static constexpr int NW = WM * WN, NTH = NW * 64;
     static constexpr int PPR = BK / 8;                    // 16-byte pieces per row
     static constexpr int ROW_BYTES = BK * 2;
@@ -72,27 +76,31 @@ struct Cfg {
     static constexpr int WTM = BM / WM, WTN = BN / WN;    // wavefront tile
     static constexpr int MI = WTM / 32, NI = WTN / 32;
     static constexpr int KS = BK / 16;                    // 16-wide slices per K-step
+    static constexpr int PH = KS / CS;                    // chunks (of CS slices) per K-step
     static constexpr size_t SMEM = (size_t)RING * STAGE_BYTES;
     static_assert(NA >= 1 && NB >= 1 && A_BYTES % (NTH * 16) == 0 && B_BYTES % (NTH * 16) == 0, "tile vs threads");
     static_assert(ROWS_PER_PASS % (WRAP * PPR) == 0 && 32 % (WRAP * PPR) == 0, "swizzle period");
-    static_assert(KS % 2 == 0, "fragment double buffer needs an even number of slices");
+    static_assert(KS % CS == 0 && NW == 8 && WM == 2, "two groups of four wavefronts, row blocks interleaved");
     static_assert(LPS * (RING - 2 > 0 ? RING - 2 : 0) < 64 && RING <= 4, "vmcnt range");
     __device__ static __forceinline__ int swz(int r) { return (r / WRAP) & (PPR - 1); }
 };
 
 // (The body is a __device__ function: it uses buffer-descriptor types that exist only on the
 // device side, and the host pass must still be able to instantiate the kernel's stub.)
-template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN>
+template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS>
 __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_mat, int K, int N,
                                                const void* const* __restrict__ w_ptrs,
                                                const moe_tile* __restrict__ tiles, const int32_t* __restrict__ hdr,
                                                void* __restrict__ out, int ld_out) {
-    using C = Cfg<BM, BN, BK, RING, WM, WN>;
-    constexpr int MI = C::MI, NI = C::NI, KS = C::KS;
+    using C = Cfg<BM, BN, BK, RING, WM, WN, CS>;
+    constexpr int MI = C::MI, NI = C::NI, KS = C::KS, PH = C::PH;
     extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = sgpr(tid >> 6);
-    const int wm = wave / C::WN, wn = wave % C::WN;       // the two wavefronts of a SIMD (w, w+4) differ in wm
+    // Wavefront w sits on SIMD w % 4; group w / 4 takes the 32-row blocks wm, wm + 2, wm + 4, ... of the
+    // tile, so that a ragged tile leaves both wavefronts of a SIMD the same amount of work.
+    const int wm = wave / C::WN, wn = wave % C::WN;
+    const int grp = wm;
     const int l32 = lane & 31, lhi = lane >> 5;
     const int n_col_blocks = (N + BN - 1) / BN;
     const int KT = K / BK;
@@ -151,110 +159,84 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     };
 
     // ---- operand fragment reads.  Row r of a 32-row block is read by lanes r and r + 32 (the
-    // two 8-wide halves of a 16-wide slice); the swizzle depends on r % 32 only.
+    // two 8-wide halves of a 16-wide slice); the swizzle depends on r % 32 only.  Row block mi of
+    // this wavefront is block mi * WM + wm of the tile.
     const int sw = C::swz(l32);
     int a_rd[KS], b_rd[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
         const int piece = ((ks * 2 + lhi) ^ sw) << 4;
-        a_rd[ks] = (wm * C::WTM + l32) * C::ROW_BYTES + piece;
+        a_rd[ks] = (wm * 32 + l32) * C::ROW_BYTES + piece;
         b_rd[ks] = C::A_BYTES + (wn * C::WTN + l32) * C::ROW_BYTES + piece;
     }
-    bf16x8 af[2][MI], bf[2][NI];
-    auto fetch = [&](int buf, int ks, int fb) {
-        const unsigned char* st = ring + buf * C::STAGE_BYTES;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) af[fb][mi] = *(const bf16x8*)(st + a_rd[ks] + mi * 32 * C::ROW_BYTES);
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) bf[fb][ni] = *(const bf16x8*)(st + b_rd[ks] + ni * 32 * C::ROW_BYTES);
-    };
-
-    // ---- prologue: every stage of the ring on its way, the first one landed and its first
-    // fragments read
-    load_item(first);
-#pragma unroll
-    for (int s = 0; s < RING; ++s)
-        if (issued < total) issue();
-    {
-        const int younger = issued - 1;
-        if (RING >= 3 && younger >= 2) MOE_WAIT_VMCNT(2 * C::LPS);
-        else if (RING >= 2 && younger >= 1) MOE_WAIT_VMCNT(C::LPS);
-        else MOE_WAIT_VMCNT(0);
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        fetch(0, 0, 0);
-    }
-
-    int g = 0, c_buf = 0;                                  // K-step counter of the stream, its stage
-    for (int item = first; item < n_items; item += stride) {
-        const int cb = item / n_tiles;
-        const moe_tile tile = tiles[bin_start + (item - cb * n_tiles)];
-        const int rc = sgpr(tile.row_count < BM ? tile.row_count : BM);
-        const int n0 = cb * BN;
-        // 32-row blocks of this wavefront that hold real rows (wave-uniform)
-        int mi_on = (rc - wm * C::WTM + 31) / 32;
-        mi_on = mi_on < 0 ? 0 : (mi_on > MI ? MI : mi_on);
-
-        f32x16 acc[MI][NI];
+    bf16x8 af[CS][MI], bf[CS][NI];
+    f32x16 acc[MI][NI];
+    auto zero_acc = [&]() {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-
-        auto mfmas = [&](int fb) {
+    };
+    // fragments of chunk h (slices h*CS ...) of the stage in buffer buf
+    auto read_chunk = [&](int buf, int h) {
+        const unsigned char* st = ring + buf * C::STAGE_BYTES;
+#pragma unroll
+        for (int s = 0; s < CS; ++s) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) bf[s][ni] = *(const bf16x8*)(st + b_rd[h * CS + s] + ni * 32 * C::ROW_BYTES);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                af[s][mi] = *(const bf16x8*)(st + a_rd[h * CS + s] + mi * (C::WM * 32) * C::ROW_BYTES);
+        }
+    };
+    auto mfma_chunk = [&](auto full, int mi_on) {
+#pragma unroll
+        for (int s = 0; s < CS; ++s)
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
-                if (mi < mi_on) {
+                if (decltype(full)::value || mi < mi_on) {
 #pragma unroll
                     for (int ni = 0; ni < NI; ++ni)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fb][mi], bf[fb][ni], acc[mi][ni], 0, 0, 0);
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][mi], bf[s][ni], acc[mi][ni], 0, 0, 0);
                 }
             }
-        };
+    };
+    // stage g+1 has landed once only the stages issued after it are outstanding
+    auto wait_stage_after = [&](int g) {
+        if (g + 1 >= total) return;
+        const int younger = issued - g - 2;
+        if (RING >= 4 && younger >= 2) MOE_WAIT_VMCNT(2 * C::LPS);
+        else if (RING >= 3 && younger >= 1) MOE_WAIT_VMCNT(C::LPS);
+        else MOE_WAIT_VMCNT(0);
+    };
+    // (nothing may move across a phase boundary: neither memory operations nor matrix-core work)
+    auto phase_barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" ::: "memory");
+    };
 
-        for (int kt = 0; kt < KT; ++kt, ++g) {
-#pragma unroll
-            for (int ks = 0; ks < KS - 1; ++ks) {
-                fetch(c_buf, ks + 1, (ks + 1) & 1);
-                mfmas(ks & 1);
-            }
-            // Before the last slice: its fragments are in registers (every read of stage g is done),
-            // stage g+1 must have landed everywhere; then stage g's buffer is refilled.
-            const int n_buf = c_buf + 1 == RING ? 0 : c_buf + 1;
-            const bool more = g + 1 < total;
-            if (more) {
-                const int younger = issued - g - 2;            // stages after g+1 still on their way
-                if (RING >= 4 && younger >= 2) MOE_WAIT_VMCNT(2 * C::LPS);
-                else if (RING >= 3 && younger >= 1) MOE_WAIT_VMCNT(C::LPS);
-                else MOE_WAIT_VMCNT(0);
-            }
-            MOE_WAIT_LGKMCNT(0);
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            if (issued < total) issue();
-            if (more) fetch(n_buf, 0, 0);
-            mfmas((KS - 1) & 1);
-            c_buf = n_buf;
-        }
-
-        // ---- epilogue.  acc[mi][ni][r]: row 8*(r/4) + 4*lhi + r%4, column l32 of the 32x32 block.
-        // Stores go through a descriptor that ends with the tile's last row.
-        constexpr int ES = EPI == MOE_EPI_STORE ? 4 : 2;
-        const unsigned ld_bytes = (unsigned)ld_out * ES;
-        const __amdgpu_buffer_rsrc_t ro =
-            make_rsrc((const unsigned char*)out + (size_t)tile.row_begin * ld_bytes, (unsigned)(rc > 0 ? rc : 0) * ld_bytes);
-        // (the row part of a store's address is range-checked only in the per-lane offset)
-        const unsigned st_voff = (unsigned)(wm * C::WTM + 4 * lhi) * ld_bytes + (unsigned)l32 * ES;
+    // ---- epilogue of one item.  acc[mi][ni][r]: row 8*(r/4) + 4*lhi + r%4, column l32 of the
+    // 32x32 block.  Stores go through a descriptor that ends with the tile's last row (the row
+    // part of a store's address is range-checked only in the per-lane offset).
+    constexpr int ES = EPI == MOE_EPI_STORE ? 4 : 2;
+    const unsigned ld_bytes = (unsigned)ld_out * ES;
+    const unsigned st_voff = (unsigned)(wm * 32 + 4 * lhi) * ld_bytes + (unsigned)l32 * ES;
+    auto epilogue = [&](__amdgpu_buffer_rsrc_t ro, int mi_on, int n0) {
+        // (the empty asm keeps the compiler from computing all row offsets once, up front, and
+        // holding -- or spilling -- them across the whole kernel)
+        unsigned st_base = st_voff;
+        asm volatile("" : "+v"(st_base));
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             if (mi >= mi_on) continue;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const unsigned row_off = (unsigned)(mi * 32 + 8 * (r >> 2) + (r & 3)) * ld_bytes;
+                const unsigned row_off = (unsigned)(mi * (C::WM * 32) + 8 * (r >> 2) + (r & 3)) * ld_bytes;
                 if (EPI == MOE_EPI_SWIGLU) {
                     // packed weight rows alternate in blocks of 32: gate, up, gate, up, ...
 #pragma unroll
@@ -262,7 +244,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                         const int pc = n0 + wn * C::WTN + ni * 32;          // packed column of the gate block
                         if (pc < N) {
                             const float h = silu_f(acc[mi][ni][r]) * acc[mi][ni + 1][r];
-                            __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(h), ro, st_voff + row_off,
+                            __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(h), ro, st_base + row_off,
                                                                   (unsigned)(pc / 2) * 2u, 0);
                         }
                     }
@@ -273,32 +255,98 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                         if (col < N) {
                             if (EPI == MOE_EPI_RELU)
                                 __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(fmaxf(acc[mi][ni][r], 0.f)), ro,
-                                                                      st_voff + row_off, (unsigned)col * 2u, 0);
+                                                                      st_base + row_off, (unsigned)col * 2u, 0);
                             else
                                 __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mi][ni][r]), ro,
-                                                                      st_voff + row_off, (unsigned)col * 4u, 0);
+                                                                      st_base + row_off, (unsigned)col * 4u, 0);
                         }
                     }
                 }
             }
         }
+    };
+
+    // ---- prologue: RING-1 stages on their way, the first one landed
+    load_item(first);
+#pragma unroll
+    for (int s = 0; s < RING - 1; ++s)
+        if (issued < total) issue();
+    {
+        const int younger = issued - 1;
+        if (RING >= 4 && younger >= 2) MOE_WAIT_VMCNT(2 * C::LPS);
+        else if (RING >= 3 && younger >= 1) MOE_WAIT_VMCNT(C::LPS);
+        else MOE_WAIT_VMCNT(0);
+        phase_barrier();
     }
+    zero_acc();
+    if (grp == 1) phase_barrier();                          // group 1 starts one phase late
+
+    int g = 0, c_buf = 0;                                   // K-step counter of the stream, its stage
+    __amdgpu_buffer_rsrc_t p_ro = make_rsrc(out, 0u);       // the previous item, stored in the next one's first phase
+    int p_mi_on = 0, p_n0 = 0;
+    for (int item = first; item < n_items; item += stride) {
+        const int cb = item / n_tiles;
+        const moe_tile tile = tiles[bin_start + (item - cb * n_tiles)];
+        const int rc = sgpr(tile.row_count < BM ? tile.row_count : BM);
+        const int n0 = cb * BN;
+        // 32-row blocks of this wavefront that hold real rows (wave-uniform)
+        int mi_on = ((rc + 31) / 32 - wm + C::WM - 1) / C::WM;
+        mi_on = mi_on < 0 ? 0 : (mi_on > MI ? MI : mi_on);
+        const __amdgpu_buffer_rsrc_t ro =
+            make_rsrc((const unsigned char*)out + (size_t)tile.row_begin * ld_bytes, (unsigned)(rc > 0 ? rc : 0) * ld_bytes);
+
+        // One K-step of this wavefront: per chunk a memory phase and a multiply phase.
+        auto k_step = [&](auto full, bool first_of_item) {
+#pragma unroll
+            for (int h = 0; h < PH; ++h) {
+                // ---- memory phase: stage g's buffer is complete; the buffer of stage g-1 has been
+                // read by everyone (it is refilled with stage g+RING-1)
+                if (h == 0 && issued < total) issue();
+                if (h == 0 && first_of_item) {
+                    epilogue(p_ro, p_mi_on, p_n0);
+                    zero_acc();
+                }
+                read_chunk(c_buf, h);
+                if (grp == 1 && h == PH - 1) wait_stage_after(g);
+                MOE_WAIT_LGKMCNT(0);
+                phase_barrier();
+                // ---- multiply phase
+                mfma_chunk(full, mi_on);
+                if (grp == 0 && h == PH - 1) wait_stage_after(g);
+                if (!(grp == 1 && g + 1 == total && h == PH - 1)) phase_barrier();
+            }
+            ++g;
+            c_buf = c_buf + 1 == RING ? 0 : c_buf + 1;
+        };
+
+        if (mi_on == MI) {
+            k_step(std::true_type{}, true);
+            for (int kt = 1; kt < KT; ++kt) k_step(std::true_type{}, false);
+        } else {
+            k_step(std::false_type{}, true);
+            for (int kt = 1; kt < KT; ++kt) k_step(std::false_type{}, false);
+        }
+        p_ro = ro;
+        p_mi_on = mi_on;
+        p_n0 = n0;
+    }
+    epilogue(p_ro, p_mi_on, p_n0);
 }
 
-template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN>
+template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(const uint16_t* __restrict__ a_mat, int K, int N,
                                                                   const void* const* __restrict__ w_ptrs,
                                                                   const moe_tile* __restrict__ tiles,
                                                                   const int32_t* __restrict__ hdr, void* __restrict__ out,
                                                                   int ld_out) {
-    gemm_bf16_body<EPI, BM, BN, BK, RING, WM, WN>(a_mat, K, N, w_ptrs, tiles, hdr, out, ld_out);
+    gemm_bf16_body<EPI, BM, BN, BK, RING, WM, WN, CS>(a_mat, K, N, w_ptrs, tiles, hdr, out, ld_out);
 }
 
 template <int EPI, class C>
 int launch(const void* a, int K, int N, const void* const* w, const moe_tile* tiles, const int32_t* hdr, void* out,
            int ld_out, hipStream_t st) {
     static_assert(C::SMEM <= 160 * 1024, "LDS ring too large");
-    auto kern = gemm_bf16_kernel<EPI, C::BM, C::BN, C::BK, C::RING, C::WM, C::WN>;
+    auto kern = gemm_bf16_kernel<EPI, C::BM, C::BN, C::BK, C::RING, C::WM, C::WN, C::CS>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)C::SMEM);
     if (e != hipSuccess) return moe_fail(MOE_ERR_HIP, "moe_grouped_ffn: shared memory attribute: %s", hipGetErrorString(e));
@@ -308,9 +356,9 @@ int launch(const void* a, int K, int N, const void* const* w, const moe_tile* ti
     return MOE_OK;
 }
 
-//                 BM   BN  BK RING WM WN
-typedef Cfg<256, 256, 32, 4, 2, 4> Tall;     // wavefront tile 128 x 64
-typedef Cfg<128, 256, 64, 3, 2, 4> Short;    // wavefront tile  64 x 64
+//          BM   BN  BK RING WM WN CS
+typedef Cfg<256, 256, 64, 2, 2, 4, 2> Tall;     // wavefront tile 128 x 64, two phases pairs per K-step
+typedef Cfg<128, 256, 64, 3, 2, 4, 4> Short;    // wavefront tile  64 x 64, one phase pair per K-step
 
 template <int EPI>
 int launch_tile(int tile_m, const void* a, int K, int N, const void* const* w, const moe_tile* tiles,
