@@ -41,6 +41,22 @@ def g1_algorithmic(wl, A, active):
     return flops, byts
 
 
+def measured_traffic(workload, tag="G1"):
+    """HBM bytes per launch of one grouped GEMM from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reports for a plain copy of
+    known size); None if there is no summary for this workload."""
+    path = os.path.join(ROOT, "profiles", "bench_%s_hbm_traffic.txt" % workload)
+    try:
+        with open(path) as f:
+            for line in f:
+                p = line.split()
+                if len(p) == 5 and p[0] == "traffic" and p[1] == workload and p[2] == tag:
+                    return int(p[3].split("=")[1]) + int(p[4].split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -49,6 +65,9 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-uniform", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of 256 MiB a few times (reference for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
@@ -95,6 +114,14 @@ def main():
             g2 = sum(m[1].elapsed_time(m[2]) for m in marks) / steps
         return ms, g1, g2
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=layer.device).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            B.moe_copy_bytes(src, dst, 256 << 20)   # copy_bytes_kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     ms, g1_ms, g2_ms = timed(args.steps, args.warmup)
     counts = layer.counts.cpu().numpy()
     A = wl.T * wl.k
@@ -116,6 +143,9 @@ def main():
         roofline = {"kernel": "gemm_bf16_kernel<G1>", "bound": "mfma", "achieved": round(g1_tflops, 1),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(g1_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                     "traffic": None, "hbm_frac": round(g1_gbs / HBM_PEAK_GBS, 4)}
+    roofline["traffic"] = measured_traffic(args.workload)
+    roofline["algorithmic_bytes"] = int(g1_bytes)
+    roofline["algorithmic_flops"] = int(g1_flops)
     roofline["avg_launch_ms"] = round(g1_ms, 4)
     roofline["g2_avg_launch_ms"] = round(g2_ms, 4)
 

@@ -244,6 +244,11 @@ MOE_API int moe_token_threshold(double phi, int d_type, double beta);
 enum { MOE_OP_PERMUTE = 1 };
 MOE_API size_t moe_workspace_bytes(int op, int T, int d, int F, int E, int k, moe_dtype dt);
 
+/* Diagnostic: a plain device-to-device copy of `bytes` bytes (a multiple of 16; src and dst
+ * 16-byte aligned, not overlapping), one kernel on `stream`.  It moves a known amount of data
+ * through HBM and serves as the reference when hardware traffic counters are scaled. */
+MOE_API int moe_copy_bytes(const void* src /*device*/, void* dst /*device*/, size_t bytes, void* stream);
+
 MOE_API const char* moe_last_error(void);
 MOE_API const char* moe_version(void);
 

@@ -31,7 +31,7 @@ EXPORTS = [
     "moe_route_topk", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_pack_weights",
     "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_unpermute_combine", "moe_prefetch_create",
     "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_destroy",
-    "moe_token_threshold", "moe_workspace_bytes", "moe_last_error", "moe_version",
+    "moe_token_threshold", "moe_workspace_bytes", "moe_copy_bytes", "moe_last_error", "moe_version",
 ]
 
 _vp, _i, _sz = C.c_void_p, C.c_int, C.c_size_t
@@ -53,6 +53,7 @@ lib.moe_prefetch_destroy.argtypes = [_vp]
 lib.moe_token_threshold.argtypes = [C.c_double, _i, C.c_double]
 lib.moe_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i, _i]
 lib.moe_workspace_bytes.restype = _sz
+lib.moe_copy_bytes.argtypes = [_vp, _vp, _sz, _vp]
 lib.moe_last_error.restype = C.c_char_p
 lib.moe_version.restype = C.c_char_p
 
@@ -156,6 +157,10 @@ def moe_grouped_ffn_phase(phase, x_perm, A, d, F, E, act, dt, w_in, w_out, tiles
 def moe_unpermute_combine(y_perm, inv_perm, gate_w, shared, T, d, k, y, stream=None):
     _check(lib.moe_unpermute_combine(_p(y_perm), _p(inv_perm), _p(gate_w), _p(shared), T, d, k, _p(y),
                                      _stream(stream)))
+
+
+def moe_copy_bytes(src, dst, nbytes: int, stream=None):
+    _check(lib.moe_copy_bytes(_p(src), _p(dst), nbytes, _stream(stream)))
 
 
 def moe_prefetch_create(n_slots: int, slot_bytes: int, slot_base) -> int:

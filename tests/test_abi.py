@@ -1,0 +1,162 @@
+"""The C ABI without a GPU: libmoe.so loads, exports every function include/moe.h declares, and
+every argument error is reported by status code before anything is enqueued (so these calls
+touch no device and run on a CPU-only machine).  Host-only helpers (Eq. 4, capacities,
+workspace sizes) are checked against their closed forms."""
+import ctypes as C
+import math
+import os
+import re
+
+import pytest
+
+from paper_2506_12417_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x1000      # a non-null "pointer" that must never be dereferenced on these paths
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"MOE_API\s+[A-Za-z_][A-Za-z_0-9\s\*]*?\b(moe_[a-z_0-9]+)\s*\(", text)
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert len(names) >= 20 and len(set(names)) == len(names)
+    for n in names:
+        assert hasattr(B.lib, n), "libmoe.so does not export %s" % n
+    assert sorted(names) == sorted(B.EXPORTS), "binding.EXPORTS and include/moe.h disagree"
+    assert "gfx950" in B.moe_version()
+
+
+def status(fn, *args):
+    try:
+        fn(*args)
+    except B.MoeError as e:
+        assert str(e) and B.moe_last_error()
+        return e.status
+    return B.MOE_OK
+
+
+def test_route_argument_errors():
+    r = B.moe_route_topk
+    ok = dict(x=FAKE, w=FAKE, b=None, T=4, d=64, E=8, k=2, renorm=1, dt=B.MOE_BF16, idx=FAKE, gw=FAKE)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return status(r, a["x"], a["w"], a["b"], a["T"], a["d"], a["E"], a["k"], a["renorm"], a["dt"], a["idx"], a["gw"], None, 0)
+
+    assert call(k=9, E=8) == B.MOE_ERR_ARG                 # k > E
+    assert call(k=0) == B.MOE_ERR_ARG
+    assert call(E=0) == B.MOE_ERR_ARG
+    assert call(T=-1) == B.MOE_ERR_ARG
+    assert call(dt=7) == B.MOE_ERR_UNSUPPORTED
+    assert call(d=20) == B.MOE_ERR_UNSUPPORTED             # d % 8
+    assert call(E=B.MOE_MAX_EXPERTS + 1) == B.MOE_ERR_UNSUPPORTED
+    assert call(E=32, k=B.MOE_MAX_TOPK + 1) == B.MOE_ERR_UNSUPPORTED
+    assert call(x=None) == B.MOE_ERR_ARG
+    assert call(idx=None) == B.MOE_ERR_ARG
+    assert call(T=0, x=None, w=None, idx=None, gw=None) == B.MOE_OK      # T = 0 is a no-op
+
+
+def test_permute_argument_errors():
+    def call(x=FAKE, idx=FAKE, T=8, d=64, E=4, k=2, dt=B.MOE_BF16, counts=FAKE, offsets=FAKE, perm=FAKE, inv=FAKE,
+             xp=FAKE, ws=FAKE, ws_bytes=1 << 20):
+        return status(B.moe_permute, x, idx, T, d, E, k, dt, counts, offsets, perm, inv, xp, ws, ws_bytes, 0)
+
+    assert call(E=0) == B.MOE_ERR_ARG
+    assert call(k=0) == B.MOE_ERR_ARG
+    assert call(E=B.MOE_MAX_EXPERTS + 1) == B.MOE_ERR_UNSUPPORTED
+    assert call(dt=5) == B.MOE_ERR_UNSUPPORTED
+    assert call(d=12) == B.MOE_ERR_UNSUPPORTED             # 24-byte rows
+    assert call(x=None) == B.MOE_ERR_ARG                   # x without x_perm
+    assert call(counts=None) == B.MOE_ERR_ARG
+    assert call(perm=None) == B.MOE_ERR_ARG
+    assert call(ws_bytes=8) == B.MOE_ERR_WORKSPACE
+    assert call(T=1 << 29, k=4) == B.MOE_ERR_UNSUPPORTED
+
+
+def test_workspace_and_capacity_closed_forms():
+    # one histogram of E int32 counters per block of 1024 assignments
+    for T, k, E in ((1, 1, 1), (1024, 1, 8), (1025, 1, 8), (16384, 4, 60), (0, 2, 5)):
+        A = T * k
+        assert B.moe_workspace_bytes(B.MOE_OP_PERMUTE, T, 64, 0, E, k, B.MOE_BF16) == max(1, math.ceil(A / 1024)) * E * 4
+    assert B.moe_workspace_bytes(99, 1, 1, 1, 1, 1, 0) == 0
+    # every (expert, bin) block can end with one ragged tile
+    for A, E, tm, G in ((0, 5, 128, 8), (16384, 128, 128, 8), (777, 1, 64, 3), (32768, 32, 256, 16)):
+        cap = B.moe_plan_capacity(A, E, tm, G)
+        assert cap >= math.ceil(A / tm) + E and cap <= A // tm + E * G + G
+    assert B.moe_ffn_tile_m(B.MOE_BF16) == 128 and B.moe_ffn_tile_m(B.MOE_F32) == 64
+    assert B.moe_ffn_pick_tile_m(B.MOE_BF16, 16384, 128) == 128
+    assert B.moe_ffn_pick_tile_m(B.MOE_BF16, 16384, 8) == 256
+    assert B.moe_ffn_pick_tile_m(B.MOE_F32, 16384, 8) == 64
+
+
+def test_token_threshold_is_eq4():
+    # q = ceil(phi * d_type / (2 * beta)), section 4.4 Eq. 4
+    for phi, dtb, beta in ((2.5e15, 2, 64e9), (2.5e15 / 8, 2, 1e12), (14e12, 4, 12e9), (1.0, 1, 1e30)):
+        want = max(1, math.ceil(phi * dtb / (2 * beta)))
+        assert B.moe_token_threshold(phi, dtb, beta) == min(want, 10 ** 9)
+    assert B.moe_token_threshold(2.5e15 / 8, 2, 1e12) == 313
+    assert B.moe_token_threshold(-1.0, 2, 1.0) == 1 and B.moe_token_threshold(1.0, 0, 1.0) == 1
+
+
+def test_plan_argument_errors():
+    def call(counts=FAKE, offsets=FAKE, E=8, A=1000, tile_m=128, G=8, q=10, policy=0, tiles=FAKE, cap=10000, hdr=FAKE):
+        return status(B.moe_plan_tiles, counts, offsets, E, A, tile_m, G, q, policy, tiles, cap, hdr, None, 0)
+
+    assert call(E=0) == B.MOE_ERR_ARG
+    assert call(A=-1) == B.MOE_ERR_ARG
+    assert call(G=0) == B.MOE_ERR_ARG and call(G=B.MOE_MAX_BINS + 1) == B.MOE_ERR_ARG
+    assert call(tile_m=0) == B.MOE_ERR_ARG
+    assert call(q=0) == B.MOE_ERR_ARG                      # Alg. 2 needs a threshold of at least one token
+    assert call(policy=4) == B.MOE_ERR_ARG and call(policy=-1) == B.MOE_ERR_ARG
+    assert call(E=B.MOE_MAX_EXPERTS + 1) == B.MOE_ERR_UNSUPPORTED
+    assert call(A=1 << 26) == B.MOE_ERR_UNSUPPORTED
+    assert call(counts=None) == B.MOE_ERR_ARG and call(hdr=None) == B.MOE_ERR_ARG
+    assert call(cap=3) == B.MOE_ERR_CAPACITY
+
+
+def test_ffn_argument_errors():
+    def call(x=FAKE, A=256, d=128, F=256, E=4, act=B.MOE_RELU, dt=B.MOE_BF16, w_in=FAKE, w_out=FAKE, tiles=FAKE,
+             hdr=FAKE, tile_m=128, h=FAKE, y=FAKE):
+        return status(B.moe_grouped_ffn, x, A, d, F, E, act, dt, w_in, w_out, tiles, hdr, tile_m, h, y, 0)
+
+    assert call(dt=3) == B.MOE_ERR_UNSUPPORTED
+    assert call(act=2) == B.MOE_ERR_UNSUPPORTED
+    assert call(E=0) == B.MOE_ERR_ARG
+    assert call(tile_m=64) == B.MOE_ERR_UNSUPPORTED        # bf16 tiles are 128 or 256 rows
+    assert call(d=96) == B.MOE_ERR_UNSUPPORTED             # bf16 needs multiples of 64
+    assert call(dt=B.MOE_F32, tile_m=128) == B.MOE_ERR_UNSUPPORTED
+    assert call(dt=B.MOE_F32, tile_m=64, d=30) == B.MOE_ERR_UNSUPPORTED
+    assert call(tiles=None) == B.MOE_ERR_ARG
+    assert call(x=None) == B.MOE_ERR_ARG and call(w_out=None) == B.MOE_ERR_ARG
+    assert call(A=0, x=None, tiles=None, hdr=None, h=None, y=None) == B.MOE_OK
+    assert status(B.moe_grouped_ffn_phase, 3, FAKE, 256, 128, 256, 4, 0, 1, FAKE, FAKE, FAKE, FAKE, 128, FAKE, FAKE, 0) == B.MOE_ERR_ARG
+
+
+def test_pack_combine_copy_argument_errors():
+    assert status(B.moe_pack_weights, FAKE, None, 1, 0, 8, B.MOE_F32, FAKE, 0) == B.MOE_ERR_ARG
+    assert status(B.moe_pack_weights, FAKE, FAKE, 1, 8, 48, B.MOE_F32, FAKE, 0) == B.MOE_ERR_UNSUPPORTED   # N % 32
+    assert status(B.moe_pack_weights, None, None, 1, 8, 8, B.MOE_F32, FAKE, 0) == B.MOE_ERR_ARG
+    assert status(B.moe_pack_weights, None, None, 0, 8, 8, B.MOE_F32, None, 0) == B.MOE_OK
+    assert status(B.moe_unpermute_combine, FAKE, FAKE, None, None, 4, 30, 1, FAKE, 0) == B.MOE_ERR_UNSUPPORTED
+    assert status(B.moe_unpermute_combine, FAKE, None, None, None, 4, 32, 1, FAKE, 0) == B.MOE_ERR_ARG
+    assert status(B.moe_unpermute_combine, FAKE, FAKE, None, None, 4, 32, 0, FAKE, 0) == B.MOE_ERR_ARG
+    assert status(B.moe_unpermute_combine, None, None, None, None, 0, 32, 1, None, 0) == B.MOE_OK
+    assert status(B.moe_copy_bytes, FAKE, FAKE + 0x1000, 24, 0) == B.MOE_ERR_UNSUPPORTED
+    assert status(B.moe_copy_bytes, None, FAKE, 32, 0) == B.MOE_ERR_ARG
+    assert status(B.moe_copy_bytes, FAKE + 4, FAKE + 0x1000, 32, 0) == B.MOE_ERR_UNSUPPORTED
+    assert status(B.moe_copy_bytes, None, None, 0, 0) == B.MOE_OK
+
+
+def test_prefetch_argument_errors_before_any_device_work():
+    h = C.c_void_p()
+    assert B.lib.moe_prefetch_create(C.byref(h), 0, 16, FAKE) == B.MOE_ERR_ARG
+    assert B.lib.moe_prefetch_create(C.byref(h), 2, 0, FAKE) == B.MOE_ERR_ARG
+    assert B.lib.moe_prefetch_create(C.byref(h), 2, 16, None) == B.MOE_ERR_ARG
+    assert B.lib.moe_prefetch_create(None, 2, 16, FAKE) == B.MOE_ERR_ARG
+    assert B.lib.moe_prefetch_wait(None, 0, None) == B.MOE_ERR_ARG
+    assert B.lib.moe_prefetch_release(None, 0, None) == B.MOE_ERR_ARG
+    assert B.lib.moe_prefetch_destroy(None) == B.MOE_OK
