@@ -6,7 +6,7 @@
 // Persistent launch, one work-group of 8 wavefronts (2 per SIMD) per CU.  Work-group b serves
 // bin b % n_bins: work-groups are dealt round-robin to the 8 XCDs, so a bin's tiles -- and with
 // them an expert's weights -- stay inside one XCD's L2.  Inside a bin the work items
-// (tile, column block) are taken column-block-major with a fixed stride.
+// (tile, column block) are taken expert after expert with a fixed stride.
 //
 // A work-group's items form ONE stream of K-steps: the operand loads run RING-1 steps ahead of
 // the arithmetic and cross item boundaries, so the next item's first tiles are already on their
@@ -39,6 +39,9 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 typedef __attribute__((address_space(3))) void lds_void_t;
 
 // s_waitcnt on vmcnt only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
@@ -77,7 +80,9 @@ struct Cfg {
     static constexpr int MI = WTM / 32, NI = WTN / 32;
     static constexpr int KS = BK / 16;                    // 16-wide slices per K-step
     static constexpr int PH = KS / CS;                    // chunks (of CS slices) per K-step
-    static constexpr size_t SMEM = (size_t)RING * STAGE_BYTES;
+    static constexpr size_t RING_BYTES = (size_t)RING * STAGE_BYTES;
+    static constexpr int MAX_BLK_TILES = 4096;            // tiles of a bin the block table can hold
+    static constexpr size_t SMEM = RING_BYTES + (size_t)MAX_BLK_TILES * 4;
     static_assert(NA >= 1 && NB >= 1 && A_BYTES % (NTH * 16) == 0 && B_BYTES % (NTH * 16) == 0, "tile vs threads");
     static_assert(ROWS_PER_PASS % (WRAP * PPR) == 0 && 32 % (WRAP * PPR) == 0, "swizzle period");
     static_assert(KS % CS == 0 && NW == 8 && WM == 2, "two groups of four wavefronts, row blocks interleaved");
@@ -116,6 +121,41 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     if (first >= n_items) return;
     const int total = ((n_items - first + stride - 1) / stride) * KT;   // K-steps of this work-group
 
+    // ---- item order.  A bin's table lists its blocks (one expert's rows on this bin) one after
+    // the other.  Items are taken block after block, column-block-major inside a block: the
+    // work-groups of the XCD then run the column blocks of a one-tile expert side by side (its
+    // rows are fetched once and shared through L2), and for an expert with many tiles the same
+    // column block of several row tiles (its weights are fetched once).  blk[p] = first tile and
+    // tile count of the block that tile p belongs to (blocks longer than 256 tiles are cut).
+    uint32_t* blk = (uint32_t*)(ring + C::RING_BYTES);
+    const bool by_block = n_tiles <= C::MAX_BLK_TILES;
+    if (by_block) {
+        int* ex = (int*)ring;                              // the ring is still empty: expert of every tile
+        for (int p = tid; p < n_tiles; p += C::NTH) ex[p] = tiles[bin_start + p].expert;
+        __syncthreads();
+        for (int p = tid; p < n_tiles; p += C::NTH) {
+            const int e = ex[p];
+            int f = p, l = p;
+            while (f > 0 && (f & 255) != 0 && ex[f - 1] == e) --f;
+            while (l + 1 < n_tiles && ((l + 1) & 255) != 0 && ex[l + 1] == e) ++l;
+            blk[p] = (uint32_t)f | ((uint32_t)(l - f + 1) << 16);
+        }
+        __syncthreads();
+    }
+    // item -> (tile of the bin, column block)
+    auto locate = [&](int it, int& tile_idx, int& cb) {
+        if (by_block) {
+            const uint32_t u = (uint32_t)sgpr((int)blk[it / n_col_blocks]);
+            const int f = (int)(u & 0xffffu), sz = (int)(u >> 16);
+            const int local = it - f * n_col_blocks;
+            cb = local / sz;
+            tile_idx = f + (local - cb * sz);
+        } else {
+            cb = it / n_tiles;
+            tile_idx = it - cb * n_tiles;
+        }
+    };
+
     // ---- loader.  Piece id = i * NTH + tid of an operand tile: row id / PPR, position id % PPR;
     // the swizzle does not depend on i, so one per-lane offset serves every load of a stage.
     const int ld_row = tid / C::PPR;
@@ -129,8 +169,9 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     __amdgpu_buffer_rsrc_t l_ra, l_rb;
     int l_item = first, l_kt = 0, l_buf = 0, issued = 0;
     auto load_item = [&](int it) {
-        const int cb = it / n_tiles;
-        const moe_tile t = tiles[bin_start + (it - cb * n_tiles)];
+        int cb, ti;
+        locate(it, ti, cb);
+        const moe_tile t = tiles[bin_start + ti];
         const int rc = t.row_count < BM ? t.row_count : BM;
         const int n0 = cb * BN;
         const int nr = N - n0 < BN ? N - n0 : BN;
@@ -221,11 +262,33 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     };
 
     // ---- epilogue of one item.  acc[mi][ni][r]: row 8*(r/4) + 4*lhi + r%4, column l32 of the
-    // 32x32 block.  Stores go through a descriptor that ends with the tile's last row (the row
-    // part of a store's address is range-checked only in the per-lane offset).
+    // 32x32 block.  Neighbouring lanes (columns c, c+1) swap one value of each register pair
+    // (rows rho, rho+1): the even lane then holds columns c, c+1 of row rho, the odd lane the
+    // same columns of row rho+1, so every lane stores two adjacent outputs at once (one packed
+    // bf16 pair, or two floats) and the number of store instructions halves.  Stores go through
+    // a descriptor that ends with the tile's last row (the row part of a store's address is
+    // range-checked only in the per-lane offset).
     constexpr int ES = EPI == MOE_EPI_STORE ? 4 : 2;
     const unsigned ld_bytes = (unsigned)ld_out * ES;
-    const unsigned st_voff = (unsigned)(wm * 32 + 4 * lhi) * ld_bytes + (unsigned)l32 * ES;
+    const int odd = l32 & 1;
+    const unsigned st_voff = (unsigned)(wm * 32 + 4 * lhi + odd) * ld_bytes + (unsigned)(l32 & ~1) * ES;
+    // (v0, v1) = this lane's values of rows rho, rho+1 -> the two adjacent values this lane stores
+    auto pair_up = [&](float v0, float v1, float& lo, float& hi) {
+        const float give = odd ? v0 : v1;
+        const float got = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(give), 0xB1, 0xf, 0xf, false));
+        lo = odd ? got : v0;
+        hi = odd ? v1 : got;
+    };
+    auto store_pair = [&](__amdgpu_buffer_rsrc_t ro, float lo, float hi, unsigned voff, unsigned soff) {
+        if (EPI == MOE_EPI_STORE) {
+            u32x2 v = {__float_as_uint(lo), __float_as_uint(hi)};
+            __builtin_amdgcn_raw_buffer_store_b64(v, ro, voff, soff, 0);
+        } else {
+            const f32x2 f = {lo, hi};
+            const bf16x2 b = __builtin_convertvector(f, bf16x2);          // v_cvt_pk_bf16_f32: nearest-even
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, b), ro, voff, soff, 0);
+        }
+    };
     auto epilogue = [&](__amdgpu_buffer_rsrc_t ro, int mi_on, int n0) {
         // (the empty asm keeps the compiler from computing all row offsets once, up front, and
         // holding -- or spilling -- them across the whole kernel)
@@ -235,17 +298,19 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         for (int mi = 0; mi < MI; ++mi) {
             if (mi >= mi_on) continue;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const unsigned row_off = (unsigned)(mi * (C::WM * 32) + 8 * (r >> 2) + (r & 3)) * ld_bytes;
+            for (int rp = 0; rp < 8; ++rp) {
+                const int r = 2 * rp;
+                const unsigned voff = st_base + (unsigned)(mi * (C::WM * 32) + 8 * (r >> 2) + (r & 3)) * ld_bytes;
                 if (EPI == MOE_EPI_SWIGLU) {
                     // packed weight rows alternate in blocks of 32: gate, up, gate, up, ...
 #pragma unroll
                     for (int ni = 0; ni < NI; ni += 2) {
                         const int pc = n0 + wn * C::WTN + ni * 32;          // packed column of the gate block
                         if (pc < N) {
-                            const float h = silu_f(acc[mi][ni][r]) * acc[mi][ni + 1][r];
-                            __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(h), ro, st_base + row_off,
-                                                                  (unsigned)(pc / 2) * 2u, 0);
+                            float lo, hi;
+                            pair_up(silu_f(acc[mi][ni][r]) * acc[mi][ni + 1][r],
+                                    silu_f(acc[mi][ni][r + 1]) * acc[mi][ni + 1][r + 1], lo, hi);
+                            store_pair(ro, lo, hi, voff, (unsigned)(pc / 2) * 2u);
                         }
                     }
                 } else {
@@ -253,12 +318,12 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                     for (int ni = 0; ni < NI; ++ni) {
                         const int col = n0 + wn * C::WTN + ni * 32;
                         if (col < N) {
+                            float lo, hi;
                             if (EPI == MOE_EPI_RELU)
-                                __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(fmaxf(acc[mi][ni][r], 0.f)), ro,
-                                                                      st_base + row_off, (unsigned)col * 2u, 0);
+                                pair_up(fmaxf(acc[mi][ni][r], 0.f), fmaxf(acc[mi][ni][r + 1], 0.f), lo, hi);
                             else
-                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mi][ni][r]), ro,
-                                                                      st_base + row_off, (unsigned)col * 4u, 0);
+                                pair_up(acc[mi][ni][r], acc[mi][ni][r + 1], lo, hi);
+                            store_pair(ro, lo, hi, voff, (unsigned)col * ES);
                         }
                     }
                 }
@@ -285,8 +350,9 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     __amdgpu_buffer_rsrc_t p_ro = make_rsrc(out, 0u);       // the previous item, stored in the next one's first phase
     int p_mi_on = 0, p_n0 = 0;
     for (int item = first; item < n_items; item += stride) {
-        const int cb = item / n_tiles;
-        const moe_tile tile = tiles[bin_start + (item - cb * n_tiles)];
+        int cb, ti;
+        locate(item, ti, cb);
+        const moe_tile tile = tiles[bin_start + ti];
         const int rc = sgpr(tile.row_count < BM ? tile.row_count : BM);
         const int n0 = cb * BN;
         // 32-row blocks of this wavefront that hold real rows (wave-uniform)
@@ -301,11 +367,13 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             for (int h = 0; h < PH; ++h) {
                 // ---- memory phase: stage g's buffer is complete; the buffer of stage g-1 has been
                 // read by everyone (it is refilled with stage g+RING-1)
-                if (h == 0 && issued < total) issue();
+                // (the stores go first: they count in vmcnt like the loads, and the wait for the
+                // next stage must not have to cover the loads issued here)
                 if (h == 0 && first_of_item) {
                     epilogue(p_ro, p_mi_on, p_n0);
                     zero_acc();
                 }
+                if (h == 0 && issued < total) issue();
                 read_chunk(c_buf, h);
                 if (grp == 1 && h == PH - 1) wait_stage_after(g);
                 MOE_WAIT_LGKMCNT(0);

@@ -23,11 +23,15 @@ def to_device(a: np.ndarray, device) -> torch.Tensor:
 
 
 def default_q_tokens(dt: int) -> int:
-    """Eq. 4 with one XCD as the unit: phi = its share of the matrix (bf16) or vector (fp32)
-    peak, beta = its share of the HBM bandwidth, d_type = bytes per weight."""
+    """Eq. 4 with one XCD as the unit and the rates this library reaches on an MI355X: phi = its
+    share of the sustained grouped-GEMM rate (about 1.0 PFLOP/s in bf16: the matrix cores run
+    near 1.55 GHz under load; 100 TFLOP/s for the fp32 FMA kernel), beta = its share of the HBM
+    streaming rate (about 6.0 TB/s), d_type = bytes per weight.  With the chip's nominal peaks
+    (2.5 PFLOP/s, 8 TB/s) q would be 313 rows, which overstates what a cold expert costs here
+    and leaves the bins with unequal numbers of tiles."""
     if dt == B.MOE_BF16:
-        return B.moe_token_threshold(2.5e15 / XCDS, 2, 8.0e12 / XCDS)
-    return B.moe_token_threshold(157.3e12 / XCDS, 4, 8.0e12 / XCDS)
+        return B.moe_token_threshold(1.0e15 / XCDS, 2, 6.0e12 / XCDS)
+    return B.moe_token_threshold(100e12 / XCDS, 4, 6.0e12 / XCDS)
 
 
 class ExpertGroup:
