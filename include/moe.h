@@ -77,6 +77,21 @@ MOE_API int moe_route_topk(const void* x, const void* w_gate, const float* bias,
                    int T, int d, int E, int k, int renorm, moe_dtype dt,
                    int32_t* expert_idx, float* gate_w, float* logits_out, void* stream);
 
+/* The same routing step with a router prepared once, outside the hot path (W_g is a parameter
+ * of the layer): moe_pack_router rewrites w_gate [d,E] as w_gate_t [E,d] (contraction index
+ * contiguous, same dtype) and gives w_norm2[e] = sum_i w_gate[i,e]^2 (fp32, rounded up), which
+ * the kernel's error bound uses.  moe_route_topk_packed computes exactly what moe_route_topk
+ * computes (same selection rule, same exact-arithmetic guarantee); it reads x once at HBM speed.
+ * bf16 only, d % 64 == 0 (MOE_ERR_UNSUPPORTED otherwise: use moe_route_topk).
+ *
+ *   w_gate_t [E,d] dt out      w_norm2 [E] fp32 out
+ */
+MOE_API int moe_pack_router(const void* w_gate, int d, int E, moe_dtype dt, void* w_gate_t, float* w_norm2,
+                            void* stream);
+MOE_API int moe_route_topk_packed(const void* x, const void* w_gate_t, const float* w_norm2, const float* bias,
+                                  int T, int d, int E, int k, int renorm, moe_dtype dt,
+                                  int32_t* expert_idx, float* gate_w, float* logits_out, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Step 4 on one GPU (Alg. 1 "scatter tokens"; counts[] is the one-GPU slice of the initial
  * schedule S_initial of step 3): a stable counting sort of the A assignments by expert.

@@ -28,7 +28,7 @@ MOE_PLAN_HDR_INTS = 4 + 2 * (MOE_MAX_BINS + 1)
 MOE_OP_PERMUTE = 1
 
 EXPORTS = [
-    "moe_route_topk", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_pack_weights",
+    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_pack_weights",
     "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_unpermute_combine", "moe_prefetch_create",
     "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_destroy",
     "moe_token_threshold", "moe_workspace_bytes", "moe_copy_bytes", "moe_last_error", "moe_version",
@@ -36,6 +36,8 @@ EXPORTS = [
 
 _vp, _i, _sz = C.c_void_p, C.c_int, C.c_size_t
 lib.moe_route_topk.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
+lib.moe_pack_router.argtypes = [_vp, _i, _i, _i, _vp, _vp, _vp]
+lib.moe_route_topk_packed.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
 lib.moe_permute.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.moe_plan_capacity.argtypes = [_i, _i, _i, _i]
 lib.moe_plan_tiles.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp]
@@ -125,6 +127,16 @@ def moe_ffn_pick_tile_m(dt: int, A: int, E: int) -> int:
 def moe_route_topk(x, w_gate, bias, T, d, E, k, renorm, dt, expert_idx, gate_w, logits_out=None, stream=None):
     _check(lib.moe_route_topk(_p(x), _p(w_gate), _p(bias), T, d, E, k, renorm, dt, _p(expert_idx), _p(gate_w),
                               _p(logits_out), _stream(stream)))
+
+
+def moe_pack_router(w_gate, d, E, dt, w_gate_t, w_norm2, stream=None):
+    _check(lib.moe_pack_router(_p(w_gate), d, E, dt, _p(w_gate_t), _p(w_norm2), _stream(stream)))
+
+
+def moe_route_topk_packed(x, w_gate_t, w_norm2, bias, T, d, E, k, renorm, dt, expert_idx, gate_w, logits_out=None,
+                          stream=None):
+    _check(lib.moe_route_topk_packed(_p(x), _p(w_gate_t), _p(w_norm2), _p(bias), T, d, E, k, renorm, dt,
+                                     _p(expert_idx), _p(gate_w), _p(logits_out), _stream(stream)))
 
 
 def moe_permute(x, expert_idx, T, d, E, k, dt, counts, offsets, perm, inv_perm, x_perm, ws, ws_bytes, stream=None):

@@ -149,13 +149,19 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
     const int n1 = act == MOE_SWIGLU ? 2 * F : F;
     int rc;
     if (dt == MOE_BF16) {
+        // Work items are (tile, column block).  With few of them per CU the last round of a
+        // persistent launch runs half empty, so a GEMM with few column blocks takes narrower
+        // ones.  The number of tiles is known on the device only; this is its expected value.
+        const long long tiles_est = (A + tile_m - 1) / tile_m + E / 2;
+        auto narrow = [&](int N) { return tile_m == 128 && tiles_est * ((N + 255) / 256) < 4 * MOE_GEMM_GRID; };
         if (phases & 1) {
-            rc = moe_launch_gemm_bf16(act == MOE_SWIGLU ? MOE_EPI_SWIGLU : MOE_EPI_RELU, tile_m, x_perm, d, n1, w_in, tiles,
-                                      plan_hdr, h_scratch, F, st);
+            rc = moe_launch_gemm_bf16(act == MOE_SWIGLU ? MOE_EPI_SWIGLU : MOE_EPI_RELU, tile_m, narrow(n1), x_perm, d, n1,
+                                      w_in, tiles, plan_hdr, h_scratch, F, st);
             if (rc != MOE_OK) return rc;
         }
         if (phases & 2) {
-            rc = moe_launch_gemm_bf16(MOE_EPI_STORE, tile_m, h_scratch, F, d, w_out, tiles, plan_hdr, (void*)y_perm, d, st);
+            rc = moe_launch_gemm_bf16(MOE_EPI_STORE, tile_m, narrow(d), h_scratch, F, d, w_out, tiles, plan_hdr,
+                                      (void*)y_perm, d, st);
             if (rc != MOE_OK) return rc;
         }
     } else {

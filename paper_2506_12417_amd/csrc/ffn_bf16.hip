@@ -367,20 +367,30 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             for (int h = 0; h < PH; ++h) {
                 // ---- memory phase: stage g's buffer is complete; the buffer of stage g-1 has been
                 // read by everyone (it is refilled with stage g+RING-1)
-                // (the stores go first: they count in vmcnt like the loads, and the wait for the
-                // next stage must not have to cover the loads issued here)
-                if (h == 0 && first_of_item) {
+                // Stores count in vmcnt like the loads.  With a ring of three or more stages the
+                // wait for the next stage is taken BEFORE the previous item is stored (that stage
+                // was issued a whole K-step ago), so the stores have until the next K-step's wait
+                // to complete; with two stages the stores go first and the wait stays late.
+                constexpr bool EARLY = RING >= 3;
+                const bool store_now = h == 0 && first_of_item;
+                if (store_now && !EARLY) {
                     epilogue(p_ro, p_mi_on, p_n0);
                     zero_acc();
                 }
                 if (h == 0 && issued < total) issue();
                 read_chunk(c_buf, h);
-                if (grp == 1 && h == PH - 1) wait_stage_after(g);
+                if (store_now && EARLY) {
+                    wait_stage_after(g);
+                    epilogue(p_ro, p_mi_on, p_n0);
+                    zero_acc();
+                }
+                const bool waited = EARLY && first_of_item;
+                if (grp == 1 && h == PH - 1 && !waited) wait_stage_after(g);
                 MOE_WAIT_LGKMCNT(0);
                 phase_barrier();
                 // ---- multiply phase
                 mfma_chunk(full, mi_on);
-                if (grp == 0 && h == PH - 1) wait_stage_after(g);
+                if (grp == 0 && h == PH - 1 && !waited) wait_stage_after(g);
                 if (!(grp == 1 && g + 1 == total && h == PH - 1)) phase_barrier();
             }
             ++g;
@@ -427,19 +437,23 @@ int launch(const void* a, int K, int N, const void* const* w, const moe_tile* ti
 //          BM   BN  BK RING WM WN CS
 typedef Cfg<256, 256, 64, 2, 2, 4, 2> Tall;     // wavefront tile 128 x 64, two phases pairs per K-step
 typedef Cfg<128, 256, 64, 3, 2, 4, 4> Short;    // wavefront tile  64 x 64, one phase pair per K-step
+typedef Cfg<128, 128, 64, 4, 2, 4, 4> Narrow;   // wavefront tile  64 x 32: twice the items, for few column blocks
 
 template <int EPI>
-int launch_tile(int tile_m, const void* a, int K, int N, const void* const* w, const moe_tile* tiles,
+int launch_tile(int tile_m, int narrow, const void* a, int K, int N, const void* const* w, const moe_tile* tiles,
                 const int32_t* hdr, void* out, int ld_out, hipStream_t st) {
     if (tile_m == 256) return launch<EPI, Tall>(a, K, N, w, tiles, hdr, out, ld_out, st);
+    if constexpr (EPI != MOE_EPI_SWIGLU) {          // (the SwiGLU epilogue needs a gate and an up block per wavefront)
+        if (narrow) return launch<EPI, Narrow>(a, K, N, w, tiles, hdr, out, ld_out, st);
+    }
     return launch<EPI, Short>(a, K, N, w, tiles, hdr, out, ld_out, st);
 }
 
 }  // namespace
 
-int moe_launch_gemm_bf16(int epi, int tile_m, const void* a, int K, int N, const void* const* w,
+int moe_launch_gemm_bf16(int epi, int tile_m, int narrow, const void* a, int K, int N, const void* const* w,
                          const moe_tile* tiles, const int32_t* hdr, void* out, int ld_out, hipStream_t st) {
-    if (epi == MOE_EPI_RELU) return launch_tile<MOE_EPI_RELU>(tile_m, a, K, N, w, tiles, hdr, out, ld_out, st);
-    if (epi == MOE_EPI_SWIGLU) return launch_tile<MOE_EPI_SWIGLU>(tile_m, a, K, N, w, tiles, hdr, out, ld_out, st);
-    return launch_tile<MOE_EPI_STORE>(tile_m, a, K, N, w, tiles, hdr, out, ld_out, st);
+    if (epi == MOE_EPI_RELU) return launch_tile<MOE_EPI_RELU>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, st);
+    if (epi == MOE_EPI_SWIGLU) return launch_tile<MOE_EPI_SWIGLU>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, st);
+    return launch_tile<MOE_EPI_STORE>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, st);
 }

@@ -8,6 +8,7 @@ enum { MOE_EPI_RELU = 0, MOE_EPI_SWIGLU = 1, MOE_EPI_STORE = 2 };
 constexpr int MOE_GEMM_GRID = 256;
 
 // out = epilogue(a . w_e^T) over the tile table.  epi: RELU / SWIGLU write bf16, STORE writes fp32.
-// tile_m: 128 or 256 (the tile height the table was planned with).
-int moe_launch_gemm_bf16(int epi, int tile_m, const void* a, int K, int N, const void* const* w,
+// tile_m: 128 or 256 (the tile height the table was planned with).  narrow: with tile_m = 128,
+// use column blocks of 128 instead of 256 outputs (ignored for SWIGLU).
+int moe_launch_gemm_bf16(int epi, int tile_m, int narrow, const void* a, int K, int N, const void* const* w,
                          const moe_tile* tiles, const int32_t* hdr, void* out, int ld_out, hipStream_t st);

@@ -25,6 +25,18 @@ __global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ wa, con
         }
     }
 }
+// squared column norms of W_g [d,E], fp32, rounded up a little: an upper bound for the router's error bound
+template <typename T>
+__global__ __launch_bounds__(256) void router_norm_kernel(const T* __restrict__ wg, int d, int E, float* __restrict__ norm2) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= E) return;
+    float s = 0.f;
+    for (int i = 0; i < d; ++i) {
+        const float v = load_as_f32(wg + (size_t)i * E + e);
+        s = fmaf(v, v, s);
+    }
+    norm2[e] = s * 1.002f;
+}
 }  // namespace
 
 extern "C" int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int N, moe_dtype dt, void* out,
@@ -44,5 +56,22 @@ extern "C" int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, 
         hipLaunchKernelGGL(pack_kernel<float>, grid, dim3(256), 0, (hipStream_t)stream, (const float*)w_a,
                            (const float*)w_b, K, N, (float*)out);
     MOE_CHECK_LAUNCH("moe_pack_weights");
+    return MOE_OK;
+}
+
+extern "C" int moe_pack_router(const void* w_gate, int d, int E, moe_dtype dt, void* w_gate_t, float* w_norm2,
+                               void* stream) {
+    MOE_REQUIRE(moe_dtype_ok(dt), MOE_ERR_UNSUPPORTED, "moe_pack_router: dtype %d", (int)dt);
+    MOE_REQUIRE(d >= 1 && E >= 1, MOE_ERR_ARG, "moe_pack_router: d=%d E=%d", d, E);
+    MOE_REQUIRE(w_gate && w_gate_t && w_norm2, MOE_ERR_ARG, "moe_pack_router: null pointer");
+    const int rc = moe_pack_weights(w_gate, nullptr, 1, d, E, dt, w_gate_t, stream);
+    if (rc != MOE_OK) return rc;
+    if (dt == MOE_BF16)
+        hipLaunchKernelGGL(router_norm_kernel<uint16_t>, dim3((E + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                           (const uint16_t*)w_gate, d, E, w_norm2);
+    else
+        hipLaunchKernelGGL(router_norm_kernel<float>, dim3((E + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                           (const float*)w_gate, d, E, w_norm2);
+    MOE_CHECK_LAUNCH("moe_pack_router");
     return MOE_OK;
 }

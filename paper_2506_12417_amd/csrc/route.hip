@@ -280,6 +280,25 @@ int dispatch_route(const void* x, const void* wg, const float* bias, int T, int 
 int moe_route_bf16_mfma(const void* x, const void* wg, const float* bias, int T, int d, int E, int k, int renorm,
                         int32_t* idx, float* w, float* logits, hipStream_t st);
 
+int moe_route_bf16_packed(const void* x, const void* wgt, const float* w_norm2, const float* bias, int T, int d, int E,
+                          int k, int renorm, int32_t* idx, float* w, float* logits, hipStream_t st);
+
+extern "C" int moe_route_topk_packed(const void* x, const void* w_gate_t, const float* w_norm2, const float* bias, int T,
+                                     int d, int E, int k, int renorm, moe_dtype dt, int32_t* expert_idx, float* gate_w,
+                                     float* logits_out, void* stream) {
+    MOE_REQUIRE(dt == MOE_BF16, MOE_ERR_UNSUPPORTED, "moe_route_topk_packed: dtype %d (bf16 only)", (int)dt);
+    MOE_REQUIRE(T >= 0 && d >= 1 && E >= 1, MOE_ERR_ARG, "moe_route_topk_packed: T=%d d=%d E=%d", T, d, E);
+    MOE_REQUIRE(k >= 1 && k <= E, MOE_ERR_ARG, "moe_route_topk_packed: k=%d outside [1, E=%d]", k, E);
+    MOE_REQUIRE(k <= MOE_MAX_TOPK, MOE_ERR_UNSUPPORTED, "moe_route_topk_packed: k=%d > %d", k, MOE_MAX_TOPK);
+    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "moe_route_topk_packed: E=%d > %d", E, MOE_MAX_EXPERTS);
+    MOE_REQUIRE(d % 64 == 0, MOE_ERR_UNSUPPORTED, "moe_route_topk_packed: d=%d is not a multiple of 64", d);
+    MOE_REQUIRE((long long)d * MOE_MAX_EXPERTS * 2 < (1ll << 31), MOE_ERR_UNSUPPORTED, "moe_route_topk_packed: d=%d too large", d);
+    if (T == 0) return MOE_OK;
+    MOE_REQUIRE(x && w_gate_t && w_norm2 && expert_idx && gate_w, MOE_ERR_ARG, "moe_route_topk_packed: null pointer");
+    return moe_route_bf16_packed(x, w_gate_t, w_norm2, bias, T, d, E, k, renorm, expert_idx, gate_w, logits_out,
+                                 (hipStream_t)stream);
+}
+
 extern "C" int moe_route_topk(const void* x, const void* w_gate, const float* bias, int T, int d, int E, int k,
                               int renorm, moe_dtype dt, int32_t* expert_idx, float* gate_w, float* logits_out,
                               void* stream) {

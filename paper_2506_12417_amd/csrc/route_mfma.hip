@@ -15,6 +15,7 @@
 // list in registers, and merge the lists with DPP exchanges inside their group of lanes.
 #include "common.h"
 #include <climits>
+#include <type_traits>
 
 namespace {
 
@@ -24,6 +25,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int NTH = 256;
 constexpr int KC = 64;                 // terms per fp32 chunk (four MFMAs)
+constexpr int KACC = 256;              // prepared-router kernel: terms per fp32 accumulation
 constexpr int PK = KC + 8;             // LDS pitch of a K-row in bf16 elements (144 B: conflict-free 16 B reads)
 constexpr int MAXR = MOE_MAX_TOPK + 1;
 constexpr float NEG_INF = -__builtin_huge_valf();
@@ -377,6 +379,378 @@ __global__ __launch_bounds__(NTH) void route_mfma_kernel(const uint16_t* __restr
     }
 }
 
+
+// =========================================================================================
+// Router with a prepared W_g (moe_pack_router): W_g^T [E,d], so the contraction index is
+// contiguous for both operands and MFMA fragments can be fetched straight from global memory,
+// 16 bytes per lane, with no LDS staging and no barrier in the main loop.
+//
+// One work-group = 32 tokens, 4 wavefronts.  The wavefronts split the contraction: wavefront w
+// takes the 64-term chunks w, w+4, w+8, ... for ALL experts of a pass (up to 128), so every byte
+// of x and of W_g^T is fetched by exactly one wavefront.  A chunk's fp32 MFMA result is added
+// into fp64 accumulators every four chunks (same error model as above, with 256-term chunks);
+// at the end the four partial sums are
+// added in a fixed order through LDS.  Fragments are prefetched one or two chunks ahead (two
+// or three register sets).
+typedef __attribute__((ext_vector_type(4))) unsigned int frag_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// (the body is a __device__ function: buffer-descriptor types exist on the device side only)
+template <int NBW, int RMAX>   // 32-expert blocks per pass (1, 2 or 4); depth of the top list (>= k + 1)
+__device__ __forceinline__ void route_packed_body(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wgt,
+                                                  const float* __restrict__ w_norm2, const float* __restrict__ bias,
+                                                  int T, int d, int E, int k, int renorm, int32_t* __restrict__ idx_out,
+                                                  float* __restrict__ w_out, float* __restrict__ logits_out) {
+    constexpr int TB = 32, TPT = NTH / TB, EPW = 32 * NBW;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int EPT = ((E + 31) / 32) * 32;            // padded expert count
+    const int PL = EPT + 4;                          // pitch of a logit row (floats)
+    // LDS: two fp64 slabs [32][EPW] for the cross-wavefront sum (later the exact path's candidate
+    // lists), the fp32 logits [32][PL], partial token norms, flags
+    double* slab = reinterpret_cast<double*>(smem);
+    float* ls = reinterpret_cast<float*>(smem + 2 * TB * EPW * 8);
+    float* xn2p = ls + TB * PL;                      // [4][32]
+    int* flag_tok = reinterpret_cast<int*>(xn2p + 4 * TB);
+    float* flag_thr = reinterpret_cast<float*>(flag_tok + TB);
+    float* flag_max = flag_thr + TB;
+    float* flag_den = flag_max + TB;
+    float* red = flag_den + TB;                      // [8]
+    int* n_flag = reinterpret_cast<int*>(red + 8);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int t0 = blockIdx.x * TB;
+    const int n_chunks = d / KC;
+    if (tid == 0) *n_flag = 0;
+
+    const int rows = T - t0 < TB ? T - t0 : TB;
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x + (size_t)t0 * d), 0, rows * d * 2, 0x00020000);
+    const unsigned voff = (unsigned)l32 * (unsigned)d * 2u + (unsigned)lhi * 16u;
+    float xsq = 0.f;
+
+    for (int nb0 = 0; nb0 * 32 < E; nb0 += NBW) {
+        const int e_left = E - nb0 * 32;
+        const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(wgt + (size_t)nb0 * 32 * d), 0, (e_left < EPW ? e_left : EPW) * d * 2, 0x00020000);
+        unsigned wvoff[NBW];
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) wvoff[j] = voff + (unsigned)(j * 32) * (unsigned)d * 2u;
+
+        double acc64[NBW][16];
+#pragma unroll
+        for (int j = 0; j < NBW; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc64[j][r] = 0.0;
+
+        // register sets in flight: 3 (two chunks ahead), or 2 when a pass covers 128 experts
+        constexpr int NSETS = NBW >= 4 ? 2 : 3;
+        frag_t xa[NSETS][KC / 16], wb[NSETS][KC / 16][NBW];
+        auto load_set = [&](auto sc, int c) {        // chunk c of the contraction into register set s
+            constexpr int s = decltype(sc)::value;
+            const unsigned so = (unsigned)c * (KC * 2);
+#pragma unroll
+            for (int ks = 0; ks < KC / 16; ++ks) {
+                xa[s][ks] = __builtin_amdgcn_raw_buffer_load_b128(rx, voff, so + ks * 32, 0);
+#pragma unroll
+                for (int j = 0; j < NBW; ++j) wb[s][ks][j] = __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff[j], so + ks * 32, 0);
+            }
+        };
+        const bool first_pass = nb0 == 0;
+        // fp32 accumulators collect up to KACC terms (four of this wavefront's chunks) before
+        // they are added into the fp64 sums: the error bound below is for KACC-term chunks
+        f32x16 acc[NBW];
+        int in_acc = 0;
+        auto clear_acc = [&]() {
+#pragma unroll
+            for (int j = 0; j < NBW; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+            in_acc = 0;
+        };
+        auto flush_acc = [&]() {
+#pragma unroll
+            for (int j = 0; j < NBW; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc64[j][r] += (double)acc[j][r];
+            clear_acc();
+        };
+        clear_acc();
+        auto step = [&](auto sc, int c) {            // multiply set s (chunk c), then refill it with chunk c + 4*NSETS
+            constexpr int s = decltype(sc)::value;
+#pragma unroll
+            for (int ks = 0; ks < KC / 16; ++ks) {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, xa[s][ks]);
+#pragma unroll
+                for (int j = 0; j < NBW; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, wb[s][ks][j]), acc[j], 0, 0, 0);
+                if (first_pass) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const bf16x2 p2 = __builtin_bit_cast(bf16x2, xa[s][ks][i]);
+                        xsq = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, xsq, false);
+                    }
+                }
+            }
+            if (c + 4 * NSETS < n_chunks) load_set(sc, c + 4 * NSETS);
+            if (++in_acc == KACC / KC) flush_acc();
+        };
+        // this wavefront's chunks: wave, wave + 4, wave + 8, ...
+        using S0 = std::integral_constant<int, 0>;
+        using S1 = std::integral_constant<int, 1>;
+        using S2 = std::integral_constant<int, 2>;
+        if (wave < n_chunks) load_set(S0{}, wave);
+        if (wave + 4 < n_chunks) load_set(S1{}, wave + 4);
+        if constexpr (NSETS == 3) {
+            if (wave + 8 < n_chunks) load_set(S2{}, wave + 8);
+        }
+        for (int c = wave; c < n_chunks; c += 4 * NSETS) {
+            step(S0{}, c);
+            if (c + 4 < n_chunks) step(S1{}, c + 4);
+            if constexpr (NSETS == 3) {
+                if (c + 8 < n_chunks) step(S2{}, c + 8);
+            }
+        }
+        if (in_acc) flush_acc();
+
+        // ---- the four partial sums, added in a fixed order: waves 0,1 write the two slabs,
+        // waves 2,3 add theirs, then slab 0 + slab 1 (+ bias) becomes the logit
+        auto slab_at = [&](int sl, int j, int r) -> double& {
+            const int tok = 8 * (r >> 2) + 4 * lhi + (r & 3);
+            return slab[(sl * TB + tok) * EPW + j * 32 + l32];
+        };
+        __syncthreads();                              // (the slabs may still be read as candidate lists / by the last pass)
+        if (wave < 2) {
+#pragma unroll
+            for (int j = 0; j < NBW; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) slab_at(wave, j, r) = acc64[j][r];
+        }
+        __syncthreads();
+        if (wave >= 2) {
+#pragma unroll
+            for (int j = 0; j < NBW; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) slab_at(wave - 2, j, r) += acc64[j][r];
+        }
+        __syncthreads();
+        for (int i = tid; i < TB * EPW; i += NTH) {
+            const int tok = i / EPW, e = nb0 * 32 + i % EPW;
+            if (e < E) {
+                const double be = bias ? (double)bias[e] : 0.0;
+                const float l = (float)(slab[i] + slab[TB * EPW + i] + be);
+                ls[tok * PL + e] = l;
+                if (logits_out && t0 + tok < T) logits_out[(size_t)(t0 + tok) * E + e] = l;
+            }
+        }
+    }
+    // token norms: the two k-halves of a token sit in lanes l and l+32; the four wavefronts' parts
+    // are added in a fixed order
+    xsq += __shfl_xor(xsq, 32);
+    if (lhi == 0) xn2p[wave * TB + l32] = xsq;
+    {   // largest column norm and largest |bias|
+        float w2 = 0.f, bm = 0.f;
+        for (int e = tid; e < E; e += NTH) {
+            w2 = fmaxf(w2, w_norm2[e]);
+            if (bias) bm = fmaxf(bm, fabsf(bias[e]));
+        }
+        w2 = moe_wave_max_nonneg(w2);
+        bm = moe_wave_max_nonneg(bm);
+        if (lane == 0) { red[wave] = w2; red[4 + wave] = bm; }
+    }
+    __syncthreads();
+    const float wmax2 = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float bmax = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
+    const float wn_max = sqrtf(wmax2) * 1.0001f;
+    const int rounds = (k + 1 < E) ? k + 1 : E;
+    const float u = 5.9604645e-8f;   // 2^-24
+
+    // ---- selection: 8 threads per token, thread `sub` scans experts sub, sub+8, ...
+    {
+        const int tok = tid / TPT, sub = tid % TPT, t = t0 + tok;
+        const float* row = ls + tok * PL;
+        float lv[RMAX];
+        int le[RMAX];
+#pragma unroll
+        for (int r = 0; r < RMAX; ++r) { lv[r] = NEG_INF; le[r] = INT_MAX; }
+        float m = NEG_INF;
+        for (int e = sub; e < E; e += TPT) {
+            float v = row[e];
+            int ve = e;
+            m = fmaxf(m, v);
+            if (beats(v, ve, lv[RMAX - 1], le[RMAX - 1])) {     // sorted insertion, static indices
+#pragma unroll
+                for (int r = 0; r < RMAX; ++r) {
+                    if (beats(v, ve, lv[r], le[r])) {
+                        float tv = lv[r]; int te = le[r];
+                        lv[r] = v; le[r] = ve;
+                        v = tv; ve = te;
+                    }
+                }
+            }
+        }
+        m = group_max<TPT>(m);
+        float s = 0.f;
+        for (int e = sub; e < E; e += TPT) s += __expf(row[e] - m);
+        const float denom = group_sum<TPT>(s);
+        float sel_v[RMAX];
+        int sel_e[RMAX];
+#pragma unroll
+        for (int r = 0; r < RMAX; ++r) {
+            sel_v[r] = NEG_INF; sel_e[r] = INT_MAX;
+            if (r < rounds) {
+                float bv = lv[0];
+                int be = le[0];
+                group_best<TPT>(bv, be);
+                sel_v[r] = bv;
+                sel_e[r] = be;
+                if (le[0] == be) {                               // the winner's owner pops its head
+#pragma unroll
+                    for (int i = 0; i + 1 < RMAX; ++i) { lv[i] = lv[i + 1]; le[i] = le[i + 1]; }
+                    lv[RMAX - 1] = NEG_INF; le[RMAX - 1] = INT_MAX;
+                }
+            }
+        }
+        const float xn = sqrtf(((xn2p[tok] + xn2p[TB + tok]) + xn2p[2 * TB + tok]) + xn2p[3 * TB + tok]) * 1.0001f;
+        const float tau = 2.1f * u * ((2 * KACC + 6) * xn * wn_max + bmax);
+        bool near = false;
+#pragma unroll
+        for (int r = 0; r + 1 < RMAX; ++r)
+            if (r + 1 < rounds && sel_v[r] - sel_v[r + 1] < tau) near = true;
+        if (t < T && sub == 0) {
+            if (!near) {
+                float p[RMAX], tot = 0.f;
+#pragma unroll
+                for (int r = 0; r < RMAX; ++r)
+                    if (r < k) { p[r] = __expf(sel_v[r] - m) / denom; tot += p[r]; }
+#pragma unroll
+                for (int r = 0; r < RMAX; ++r)
+                    if (r < k) {
+                        idx_out[(size_t)t * k + r] = sel_e[r];
+                        w_out[(size_t)t * k + r] = renorm ? p[r] / tot : p[r];
+                    }
+            } else {
+                float last = sel_v[0];
+#pragma unroll
+                for (int r = 1; r < RMAX; ++r) if (r < rounds) last = sel_v[r];
+                const int f = atomicAdd(n_flag, 1);
+                flag_tok[f] = tok;
+                flag_thr[f] = last - tau;
+                flag_max[f] = m;
+                flag_den[f] = denom;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- exact path for the flagged tokens: one wavefront per token; every expert whose fp32
+    // logit could still reach the top k is recomputed in fp64 (both operand rows are contiguous)
+    double* cand_v = slab + wave * (MOE_MAX_EXPERTS + 32);                       // [4][288] doubles ...
+    int* cand_e = reinterpret_cast<int*>(slab + 4 * (MOE_MAX_EXPERTS + 32)) + wave * (MOE_MAX_EXPERTS + 32);   // ... then ints
+    constexpr int CJ = (MOE_MAX_EXPERTS + 63) / 64;
+    const int nf = *n_flag;
+    for (int f = wave; f < nf; f += 4) {
+        const int tok = flag_tok[f], t = t0 + tok;
+        const float thr = flag_thr[f];
+        const uint16_t* xr = x + (size_t)t * d;
+        int nc = 0;
+        for (int e0 = 0; e0 < E; e0 += 64) {
+            const int e = e0 + lane;
+            unsigned long long mask = __ballot(e < E && ls[tok * PL + e] >= thr);
+            while (mask) {
+                const int ce = e0 + (int)__builtin_ctzll(mask);
+                mask &= mask - 1;
+                const uint16_t* wr = wgt + (size_t)ce * d;
+                double psum = 0.0;
+                for (int i0 = lane * 8; i0 < d; i0 += 64 * 8) {    // 8 terms per lane and step, 16-byte loads
+                    const frag_t xv = *(const frag_t*)(xr + i0), wv = *(const frag_t*)(wr + i0);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        psum = fma((double)__uint_as_float(xv[i] << 16), (double)__uint_as_float(wv[i] << 16), psum);
+                        psum = fma((double)__uint_as_float(xv[i] & 0xffff0000u), (double)__uint_as_float(wv[i] & 0xffff0000u), psum);
+                    }
+                }
+                const double tot = wave_sum_f64(psum) + (bias ? (double)bias[ce] : 0.0);
+                if (lane == 0) { cand_v[nc] = tot; cand_e[nc] = ce; }
+                ++nc;
+            }
+        }
+        double cv[CJ];
+        int ce_[CJ];
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) {
+            const int c = lane + 64 * j;
+            cv[j] = c < nc ? cand_v[c] : -__builtin_huge_val();
+            ce_[j] = c < nc ? cand_e[c] : INT_MAX;
+        }
+        const double m = (double)flag_max[f], den = (double)flag_den[f];
+        double p[MOE_MAX_TOPK], tot = 0.0;
+        int pe[MOE_MAX_TOPK];
+#pragma unroll
+        for (int r = 0; r < MOE_MAX_TOPK; ++r) {
+            if (r < k) {
+                double bv = -__builtin_huge_val();
+                int be = INT_MAX;
+#pragma unroll
+                for (int j = 0; j < CJ; ++j)
+                    if (beats(cv[j], ce_[j], bv, be)) { bv = cv[j]; be = ce_[j]; }
+                wave_best_f64(bv, be);
+#pragma unroll
+                for (int j = 0; j < CJ; ++j)
+                    if (ce_[j] == be) { cv[j] = -__builtin_huge_val(); ce_[j] = INT_MAX; }
+                p[r] = exp(bv - m) / den;
+                pe[r] = be;
+                tot += p[r];
+            }
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int r = 0; r < MOE_MAX_TOPK; ++r)
+                if (r < k) {
+                    idx_out[(size_t)t * k + r] = pe[r];
+                    w_out[(size_t)t * k + r] = (float)(renorm ? p[r] / tot : p[r]);
+                }
+        }
+    }
+}
+
+template <int NBW, int RMAX>
+__global__ __launch_bounds__(NTH) void route_packed_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wgt,
+                                                           const float* __restrict__ w_norm2,
+                                                           const float* __restrict__ bias, int T, int d, int E, int k,
+                                                           int renorm, int32_t* __restrict__ idx_out,
+                                                           float* __restrict__ w_out, float* __restrict__ logits_out) {
+    route_packed_body<NBW, RMAX>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx_out, w_out, logits_out);
+}
+
+template <int NBW, int RMAX>
+int launch_packed_r(const void* x, const void* wgt, const float* w_norm2, const float* bias, int T, int d, int E, int k,
+                  int renorm, int32_t* idx, float* w, float* logits, hipStream_t st) {
+    const int EPT = ((E + 31) / 32) * 32;
+    size_t smem = (size_t)2 * 32 * (32 * NBW) * 8 + (size_t)32 * (EPT + 4) * 4 + 4 * 32 * 4 + 4 * 32 * 4 + 64;
+    const size_t cand = (size_t)4 * (MOE_MAX_EXPERTS + 32) * 12;           // the exact path's lists reuse the slabs
+    if (smem < cand + (size_t)32 * (EPT + 4) * 4 + 1200) smem = cand + (size_t)32 * (EPT + 4) * 4 + 1200;
+    auto kern = route_packed_kernel<NBW, RMAX>;
+    if (smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return moe_fail(MOE_ERR_HIP, "moe_route_topk_packed: shared memory attribute: %s", hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(kern, dim3((T + 31) / 32), dim3(NTH), smem, st, (const uint16_t*)x, (const uint16_t*)wgt, w_norm2, bias,
+                       T, d, E, k, renorm, idx, w, logits);
+    MOE_CHECK_LAUNCH("moe_route_topk_packed");
+    return MOE_OK;
+}
+
+template <int NBW>
+int launch_packed(const void* x, const void* wgt, const float* w_norm2, const float* bias, int T, int d, int E, int k,
+                  int renorm, int32_t* idx, float* w, float* logits, hipStream_t st) {
+    // the depth of the per-thread top list follows k (a shorter list is less work per logit)
+    if (k <= 1) return launch_packed_r<NBW, 2>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    if (k <= 2) return launch_packed_r<NBW, 3>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    if (k <= 4) return launch_packed_r<NBW, 5>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    return launch_packed_r<NBW, MAXR>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+}
+
 template <int MT, int NJ>
 int launch(const void* x, const void* wg, const float* bias, int T, int d, int E, int k, int renorm, int32_t* idx,
            float* w, float* logits, hipStream_t st) {
@@ -396,4 +770,12 @@ int moe_route_bf16_mfma(const void* x, const void* wg, const float* bias, int T,
     // each other's load latency
     if (E <= 128) return launch<1, 1>(x, wg, bias, T, d, E, k, renorm, idx, w, logits, st);
     return launch<1, 2>(x, wg, bias, T, d, E, k, renorm, idx, w, logits, st);
+}
+
+// bf16 path of moe_route_topk_packed (arguments already validated by the caller)
+int moe_route_bf16_packed(const void* x, const void* wgt, const float* w_norm2, const float* bias, int T, int d, int E,
+                          int k, int renorm, int32_t* idx, float* w, float* logits, hipStream_t st) {
+    if (E <= 32) return launch_packed<1>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    if (E <= 64) return launch_packed<2>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    return launch_packed<4>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
 }

@@ -82,6 +82,7 @@ class MoELayer:
         i32, f32 = torch.int32, torch.float32
         self.W_g = None
         self.bias = None
+        self.packed_router = False
         self.experts = ExpertGroup(E, d, F, self.act, self.dt, dev)
         self.expert_idx = torch.empty((T, k), dtype=i32, device=dev)
         self.gate_w = torch.empty((T, k), dtype=f32, device=dev)
@@ -115,9 +116,18 @@ class MoELayer:
                              B.MOE_PLAN_BALANCED, self.s_tiles, self.s_capacity, self.s_hdr, None)
 
     # ------------------------------------------------------------------ parameters
-    def load_router(self, W_g: np.ndarray, b: Optional[np.ndarray]):
+    def load_router(self, W_g: np.ndarray, b: Optional[np.ndarray], packed: Optional[bool] = None):
+        """packed: prepare the router once with moe_pack_router and route with
+        moe_route_topk_packed (default: whenever that entry point supports the shape)."""
         self.W_g = to_device(W_g, self.device)
         self.bias = None if b is None else to_device(np.asarray(b, dtype=np.float32), self.device)
+        can_pack = self.dt == B.MOE_BF16 and self.d % 64 == 0
+        self.packed_router = can_pack if packed is None else (packed and can_pack)
+        if self.packed_router:
+            self.W_gt = torch.empty((self.E, self.d), dtype=self.tdt, device=self.device)
+            self.w_norm2 = torch.empty(self.E, dtype=torch.float32, device=self.device)
+            B.moe_pack_router(self.W_g, self.d, self.E, self.dt, self.W_gt, self.w_norm2)
+            torch.cuda.synchronize(self.device)
 
     def load_experts(self, weights: Dict[str, np.ndarray]):
         """weights: stacked [E, ...] arrays in the paper's orientation."""
@@ -129,6 +139,10 @@ class MoELayer:
 
     # ------------------------------------------------------------------ the path, step by step
     def route(self, x, logits_out=None, stream=None):
+        if self.packed_router:
+            B.moe_route_topk_packed(x, self.W_gt, self.w_norm2, self.bias, self.T, self.d, self.E, self.k,
+                                    self.renorm, self.dt, self.expert_idx, self.gate_w, logits_out, stream)
+            return
         B.moe_route_topk(x, self.W_g, self.bias, self.T, self.d, self.E, self.k, self.renorm, self.dt,
                          self.expert_idx, self.gate_w, logits_out, stream)
 

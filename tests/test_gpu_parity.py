@@ -36,14 +36,25 @@ ROUTE_CASES = [
 ]
 
 
+@pytest.mark.parametrize("packed", [False, True])
 @pytest.mark.parametrize("name,over", ROUTE_CASES)
-def test_route_topk(torch_gpu, name, over):
+def test_route_topk(torch_gpu, name, over, packed):
+    """packed=False: moe_route_topk on W_g as given; packed=True: moe_pack_router once, then
+    moe_route_topk_packed (bf16 with d % 64 == 0 only; the other cases run the plain entry point)."""
     torch = torch_gpu
     wl = W.WORKLOADS[name].scaled(**over)
-    _note("route %s %s" % (name, over))
+    _note("route %s %s packed=%s" % (name, over, packed))
     inp = W.make_inputs(wl, weights=False)
     idx_o, w_o, l_o = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
     layer = make_layer(wl, inp)
+    layer.load_router(inp["W_g"], inp["b"], packed=packed)
+    if packed and wl.dtype == "bf16" and wl.d % 64 == 0:
+        assert layer.packed_router
+        ref_t = np.ascontiguousarray(np.asarray(inp["W_g"]).T)
+        assert np.array_equal(to_numpy(layer.W_gt), ref_t)             # W_g^T, bit for bit
+        n2 = (O.to_f64(inp["W_g"]) ** 2).sum(axis=0)
+        got = to_numpy(layer.w_norm2).astype(np.float64)
+        assert np.all(got >= n2) and np.all(got <= n2 * 1.004)          # an upper bound, and a tight one
     x = layer_x(layer, inp)
     logits = torch.empty((wl.T, wl.E), dtype=torch.float32, device=layer.device)
     layer.route(x, logits)
@@ -76,6 +87,30 @@ def test_route_near_ties_take_the_exact_path(torch_gpu):
     torch.cuda.synchronize()
     assert np.array_equal(to_numpy(layer.expert_idx), idx_o)
     assert np.abs(to_numpy(layer.gate_w) - w_o).max() <= 2e-6
+
+
+def test_route_near_ties_bf16_both_entry_points(torch_gpu):
+    # the same planted ties in bf16, through the plain and the prepared-router entry points
+    torch = torch_gpu
+    T, d, E, k = 200, 128, 40, 3
+    r = np.random.default_rng(2)
+    x = W.f32_to_bf16_bits(r.standard_normal((T, d)).astype(np.float32))
+    Wf = (r.standard_normal((d, E)) / 8).astype(np.float32)
+    Wf[:, 7] = Wf[:, 30]                       # exact ties between experts 7 and 30
+    Wf[:, 12] = Wf[:, 2]
+    Wg = W.f32_to_bf16_bits(Wf)
+    Wg[5, 12] ^= 1                             # one bf16 ulp in one coefficient: a gap far below the fp32 bound
+    wl = W.WORKLOADS["c2"].scaled(T=T, d=d, E=E, k=k, renorm=1)
+    idx_o, w_o, _ = O.route_topk(x, Wg, None, k, 1)
+    from paper_2506_12417_amd.layer import to_device
+    for packed in (False, True):
+        layer = make_layer(wl, {})
+        layer.load_router(Wg, None, packed=packed)
+        assert layer.packed_router == packed
+        layer.route(to_device(x, layer.device))
+        torch.cuda.synchronize()
+        assert np.array_equal(to_numpy(layer.expert_idx), idx_o), "packed=%s" % packed
+        assert np.abs(to_numpy(layer.gate_w) - w_o).max() <= 2e-6
 
 
 PERMUTE_CASES = [(1, 1, 1, 8), (256, 2, 8, 64), (1000, 1, 128, 32), (5000, 4, 60, 16), (3, 2, 256, 8),
