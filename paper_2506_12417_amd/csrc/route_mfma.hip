@@ -385,188 +385,170 @@ __global__ __launch_bounds__(NTH) void route_mfma_kernel(const uint16_t* __restr
 // contiguous for both operands and MFMA fragments can be fetched straight from global memory,
 // 16 bytes per lane, with no LDS staging and no barrier in the main loop.
 //
-// One work-group = 32 tokens, 4 wavefronts.  The wavefronts split the contraction: wavefront w
-// takes the 64-term chunks w, w+4, w+8, ... for ALL experts of a pass (up to 128), so every byte
-// of x and of W_g^T is fetched by exactly one wavefront.  A chunk's fp32 MFMA result is added
-// into fp64 accumulators every four chunks (same error model as above, with 256-term chunks);
-// at the end the four partial sums are
-// added in a fixed order through LDS.  Fragments are prefetched one or two chunks ahead (two
-// or three register sets).
+// One work-group = 32 tokens.  Its wavefronts split the experts into blocks of 32 (NB blocks)
+// and, when there are fewer than four blocks, also the contraction (KSP parts): wavefront
+// (block, part) takes the 64-term chunks part, part+KSP, ... for its 32 experts.  A wavefront's
+// fp32 MFMA accumulator collects up to KACC terms before it is added into fp64 sums (same error
+// model as above, with KACC-term chunks); the KSP partial sums are added in a fixed order
+// through LDS.  Fragments are prefetched two chunks ahead (three register sets).  A wavefront
+// needs about 180 registers and the work-group at most 64 KB of LDS, so two work-groups share
+// a CU and hide each other's load latency.
 typedef __attribute__((ext_vector_type(4))) unsigned int frag_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 // (the body is a __device__ function: buffer-descriptor types exist on the device side only)
-template <int NBW, int RMAX>   // 32-expert blocks per pass (1, 2 or 4); depth of the top list (>= k + 1)
+template <int NB, int KSP, int RMAX>   // expert blocks, contraction parts, depth of the top list (>= k + 1)
 __device__ __forceinline__ void route_packed_body(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wgt,
                                                   const float* __restrict__ w_norm2, const float* __restrict__ bias,
                                                   int T, int d, int E, int k, int renorm, int32_t* __restrict__ idx_out,
                                                   float* __restrict__ w_out, float* __restrict__ logits_out) {
-    constexpr int TB = 32, TPT = NTH / TB, EPW = 32 * NBW;
+    constexpr int NWV = NB * KSP, NTHR = NWV * 64, TB = 32, TPT = 8, EPT = 32 * NB;
+    constexpr int PL = EPT + 4;                      // pitch of a logit row (floats)
+    constexpr int SLAB = KSP > 1 ? KSP * TB * EPT * 8 : 0;
+    constexpr int CAND = NWV * (MOE_MAX_EXPERTS + 32) * 12;
+    constexpr int REGION0 = SLAB > CAND ? SLAB : CAND;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int EPT = ((E + 31) / 32) * 32;            // padded expert count
-    const int PL = EPT + 4;                          // pitch of a logit row (floats)
-    // LDS: two fp64 slabs [32][EPW] for the cross-wavefront sum (later the exact path's candidate
-    // lists), the fp32 logits [32][PL], partial token norms, flags
+    // LDS: fp64 slabs [KSP][32][EPT] for the sum over the contraction parts (later the exact path's
+    // candidate lists), the fp32 logits [32][PL], partial token norms, flags
     double* slab = reinterpret_cast<double*>(smem);
-    float* ls = reinterpret_cast<float*>(smem + 2 * TB * EPW * 8);
-    float* xn2p = ls + TB * PL;                      // [4][32]
-    int* flag_tok = reinterpret_cast<int*>(xn2p + 4 * TB);
+    float* ls = reinterpret_cast<float*>(smem + REGION0);
+    float* xn2p = ls + TB * PL;                      // [KSP][32]
+    int* flag_tok = reinterpret_cast<int*>(xn2p + KSP * TB);
     float* flag_thr = reinterpret_cast<float*>(flag_tok + TB);
     float* flag_max = flag_thr + TB;
     float* flag_den = flag_max + TB;
-    float* red = flag_den + TB;                      // [8]
-    int* n_flag = reinterpret_cast<int*>(red + 8);
+    float* red = flag_den + TB;                      // [2 * NWV]
+    int* n_flag = reinterpret_cast<int*>(red + 2 * NWV);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
+    const int nbi = wave / KSP, ksi = wave % KSP;    // this wavefront's expert block and contraction part
     const int t0 = blockIdx.x * TB;
     const int n_chunks = d / KC;
     if (tid == 0) *n_flag = 0;
 
     const int rows = T - t0 < TB ? T - t0 : TB;
+    const int e_left = E - nbi * 32;
     const __amdgpu_buffer_rsrc_t rx =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x + (size_t)t0 * d), 0, rows * d * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(wgt + (size_t)nbi * 32 * d), 0, (e_left < 0 ? 0 : (e_left < 32 ? e_left : 32)) * d * 2, 0x00020000);
     const unsigned voff = (unsigned)l32 * (unsigned)d * 2u + (unsigned)lhi * 16u;
     float xsq = 0.f;
 
-    for (int nb0 = 0; nb0 * 32 < E; nb0 += NBW) {
-        const int e_left = E - nb0 * 32;
-        const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint16_t*>(wgt + (size_t)nb0 * 32 * d), 0, (e_left < EPW ? e_left : EPW) * d * 2, 0x00020000);
-        unsigned wvoff[NBW];
+    double acc64[16];
 #pragma unroll
-        for (int j = 0; j < NBW; ++j) wvoff[j] = voff + (unsigned)(j * 32) * (unsigned)d * 2u;
-
-        double acc64[NBW][16];
+    for (int r = 0; r < 16; ++r) acc64[r] = 0.0;
+    f32x16 acc;
+    int in_acc = 0;
+    auto clear_acc = [&]() {
 #pragma unroll
-        for (int j = 0; j < NBW; ++j)
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        in_acc = 0;
+    };
+    auto flush_acc = [&]() {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc64[j][r] = 0.0;
-
-        // register sets in flight: 3 (two chunks ahead), or 2 when a pass covers 128 experts
-        constexpr int NSETS = NBW >= 4 ? 2 : 3;
-        frag_t xa[NSETS][KC / 16], wb[NSETS][KC / 16][NBW];
-        auto load_set = [&](auto sc, int c) {        // chunk c of the contraction into register set s
-            constexpr int s = decltype(sc)::value;
-            const unsigned so = (unsigned)c * (KC * 2);
-#pragma unroll
-            for (int ks = 0; ks < KC / 16; ++ks) {
-                xa[s][ks] = __builtin_amdgcn_raw_buffer_load_b128(rx, voff, so + ks * 32, 0);
-#pragma unroll
-                for (int j = 0; j < NBW; ++j) wb[s][ks][j] = __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff[j], so + ks * 32, 0);
-            }
-        };
-        const bool first_pass = nb0 == 0;
-        // fp32 accumulators collect up to KACC terms (four of this wavefront's chunks) before
-        // they are added into the fp64 sums: the error bound below is for KACC-term chunks
-        f32x16 acc[NBW];
-        int in_acc = 0;
-        auto clear_acc = [&]() {
-#pragma unroll
-            for (int j = 0; j < NBW; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-            in_acc = 0;
-        };
-        auto flush_acc = [&]() {
-#pragma unroll
-            for (int j = 0; j < NBW; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc64[j][r] += (double)acc[j][r];
-            clear_acc();
-        };
+        for (int r = 0; r < 16; ++r) acc64[r] += (double)acc[r];
         clear_acc();
-        auto step = [&](auto sc, int c) {            // multiply set s (chunk c), then refill it with chunk c + 4*NSETS
-            constexpr int s = decltype(sc)::value;
+    };
+    clear_acc();
+
+    constexpr int NSETS = 3;
+    frag_t xa[NSETS][KC / 16], wb[NSETS][KC / 16];
+    auto load_set = [&](auto sc, int c) {            // chunk c of the contraction into register set s
+        constexpr int s = decltype(sc)::value;
+        const unsigned so = (unsigned)c * (KC * 2);
 #pragma unroll
-            for (int ks = 0; ks < KC / 16; ++ks) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, xa[s][ks]);
+        for (int ks = 0; ks < KC / 16; ++ks) {
+            xa[s][ks] = __builtin_amdgcn_raw_buffer_load_b128(rx, voff, so + ks * 32, 0);
+            wb[s][ks] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, so + ks * 32, 0);
+        }
+    };
+    auto step = [&](auto sc, int c) {                // multiply set s (chunk c), then refill it
+        constexpr int s = decltype(sc)::value;
 #pragma unroll
-                for (int j = 0; j < NBW; ++j)
-                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, wb[s][ks][j]), acc[j], 0, 0, 0);
-                if (first_pass) {
+        for (int ks = 0; ks < KC / 16; ++ks) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[s][ks]),
+                                                          __builtin_bit_cast(bf16x8, wb[s][ks]), acc, 0, 0, 0);
+            if (nbi == 0) {                          // the token norms, once per contraction part
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const bf16x2 p2 = __builtin_bit_cast(bf16x2, xa[s][ks][i]);
-                        xsq = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, xsq, false);
-                    }
+                for (int i = 0; i < 4; ++i) {
+                    const bf16x2 p2 = __builtin_bit_cast(bf16x2, xa[s][ks][i]);
+                    xsq = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, xsq, false);
                 }
             }
-            if (c + 4 * NSETS < n_chunks) load_set(sc, c + 4 * NSETS);
-            if (++in_acc == KACC / KC) flush_acc();
-        };
-        // this wavefront's chunks: wave, wave + 4, wave + 8, ...
-        using S0 = std::integral_constant<int, 0>;
-        using S1 = std::integral_constant<int, 1>;
-        using S2 = std::integral_constant<int, 2>;
-        if (wave < n_chunks) load_set(S0{}, wave);
-        if (wave + 4 < n_chunks) load_set(S1{}, wave + 4);
-        if constexpr (NSETS == 3) {
-            if (wave + 8 < n_chunks) load_set(S2{}, wave + 8);
         }
-        for (int c = wave; c < n_chunks; c += 4 * NSETS) {
-            step(S0{}, c);
-            if (c + 4 < n_chunks) step(S1{}, c + 4);
-            if constexpr (NSETS == 3) {
-                if (c + 8 < n_chunks) step(S2{}, c + 8);
+        if (c + KSP * NSETS < n_chunks) load_set(sc, c + KSP * NSETS);
+        if (++in_acc == KACC / KC) flush_acc();
+    };
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    using S2 = std::integral_constant<int, 2>;
+    if (ksi < n_chunks) load_set(S0{}, ksi);
+    if (ksi + KSP < n_chunks) load_set(S1{}, ksi + KSP);
+    if (ksi + 2 * KSP < n_chunks) load_set(S2{}, ksi + 2 * KSP);
+    for (int c = ksi; c < n_chunks; c += KSP * NSETS) {
+        step(S0{}, c);
+        if (c + KSP < n_chunks) step(S1{}, c + KSP);
+        if (c + 2 * KSP < n_chunks) step(S2{}, c + 2 * KSP);
+    }
+    if (in_acc) flush_acc();
+
+    // ---- logits.  acc64[r]: token 8*(r/4) + 4*lhi + r%4, expert nbi*32 + l32.
+    if (KSP > 1) {                                   // the partial sums of the contraction parts, fixed order
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int tok = 8 * (r >> 2) + 4 * lhi + (r & 3);
+            slab[(ksi * TB + tok) * EPT + nbi * 32 + l32] = acc64[r];
+        }
+        __syncthreads();
+        for (int i = tid; i < TB * EPT; i += NTHR) {
+            const int tok = i / EPT, e = i % EPT;
+            if (e < E) {
+                double v = slab[i];
+#pragma unroll
+                for (int p = 1; p < KSP; ++p) v += slab[p * TB * EPT + i];
+                const float l = (float)(v + (bias ? (double)bias[e] : 0.0));
+                ls[tok * PL + e] = l;
+                if (logits_out && t0 + tok < T) logits_out[(size_t)(t0 + tok) * E + e] = l;
             }
         }
-        if (in_acc) flush_acc();
-
-        // ---- the four partial sums, added in a fixed order: waves 0,1 write the two slabs,
-        // waves 2,3 add theirs, then slab 0 + slab 1 (+ bias) becomes the logit
-        auto slab_at = [&](int sl, int j, int r) -> double& {
+    } else {
+        const int e = nbi * 32 + l32;
+        const double be = (bias && e < E) ? (double)bias[e] : 0.0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
             const int tok = 8 * (r >> 2) + 4 * lhi + (r & 3);
-            return slab[(sl * TB + tok) * EPW + j * 32 + l32];
-        };
-        __syncthreads();                              // (the slabs may still be read as candidate lists / by the last pass)
-        if (wave < 2) {
-#pragma unroll
-            for (int j = 0; j < NBW; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) slab_at(wave, j, r) = acc64[j][r];
-        }
-        __syncthreads();
-        if (wave >= 2) {
-#pragma unroll
-            for (int j = 0; j < NBW; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) slab_at(wave - 2, j, r) += acc64[j][r];
-        }
-        __syncthreads();
-        for (int i = tid; i < TB * EPW; i += NTH) {
-            const int tok = i / EPW, e = nb0 * 32 + i % EPW;
+            const float l = (float)(acc64[r] + be);
             if (e < E) {
-                const double be = bias ? (double)bias[e] : 0.0;
-                const float l = (float)(slab[i] + slab[TB * EPW + i] + be);
                 ls[tok * PL + e] = l;
                 if (logits_out && t0 + tok < T) logits_out[(size_t)(t0 + tok) * E + e] = l;
             }
         }
     }
-    // token norms: the two k-halves of a token sit in lanes l and l+32; the four wavefronts' parts
-    // are added in a fixed order
+    // token norms: the two k-halves of a token sit in lanes l and l+32; the parts are added in a fixed order
     xsq += __shfl_xor(xsq, 32);
-    if (lhi == 0) xn2p[wave * TB + l32] = xsq;
+    if (nbi == 0 && lhi == 0) xn2p[ksi * TB + l32] = xsq;
     {   // largest column norm and largest |bias|
         float w2 = 0.f, bm = 0.f;
-        for (int e = tid; e < E; e += NTH) {
+        for (int e = tid; e < E; e += NTHR) {
             w2 = fmaxf(w2, w_norm2[e]);
             if (bias) bm = fmaxf(bm, fabsf(bias[e]));
         }
         w2 = moe_wave_max_nonneg(w2);
         bm = moe_wave_max_nonneg(bm);
-        if (lane == 0) { red[wave] = w2; red[4 + wave] = bm; }
+        if (lane == 0) { red[wave] = w2; red[NWV + wave] = bm; }
     }
     __syncthreads();
-    const float wmax2 = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    const float bmax = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
+    float wmax2 = 0.f, bmax = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < NWV; ++w2) { wmax2 = fmaxf(wmax2, red[w2]); bmax = fmaxf(bmax, red[NWV + w2]); }
     const float wn_max = sqrtf(wmax2) * 1.0001f;
     const int rounds = (k + 1 < E) ? k + 1 : E;
     const float u = 5.9604645e-8f;   // 2^-24
 
-    // ---- selection: 8 threads per token, thread `sub` scans experts sub, sub+8, ...
-    {
+    // ---- selection: TPT threads per token (the first four wavefronts), thread `sub` scans experts sub, sub+TPT, ...
+    if (tid < TB * TPT) {
         const int tok = tid / TPT, sub = tid % TPT, t = t0 + tok;
         const float* row = ls + tok * PL;
         float lv[RMAX];
@@ -611,7 +593,10 @@ __device__ __forceinline__ void route_packed_body(const uint16_t* __restrict__ x
                 }
             }
         }
-        const float xn = sqrtf(((xn2p[tok] + xn2p[TB + tok]) + xn2p[2 * TB + tok]) + xn2p[3 * TB + tok]) * 1.0001f;
+        float xs2 = xn2p[tok];
+#pragma unroll
+        for (int p = 1; p < KSP; ++p) xs2 += xn2p[p * TB + tok];
+        const float xn = sqrtf(xs2) * 1.0001f;
         const float tau = 2.1f * u * ((2 * KACC + 6) * xn * wn_max + bmax);
         bool near = false;
 #pragma unroll
@@ -645,11 +630,11 @@ __device__ __forceinline__ void route_packed_body(const uint16_t* __restrict__ x
 
     // ---- exact path for the flagged tokens: one wavefront per token; every expert whose fp32
     // logit could still reach the top k is recomputed in fp64 (both operand rows are contiguous)
-    double* cand_v = slab + wave * (MOE_MAX_EXPERTS + 32);                       // [4][288] doubles ...
-    int* cand_e = reinterpret_cast<int*>(slab + 4 * (MOE_MAX_EXPERTS + 32)) + wave * (MOE_MAX_EXPERTS + 32);   // ... then ints
+    double* cand_v = slab + wave * (MOE_MAX_EXPERTS + 32);                       // [NWV][288] doubles ...
+    int* cand_e = reinterpret_cast<int*>(slab + NWV * (MOE_MAX_EXPERTS + 32)) + wave * (MOE_MAX_EXPERTS + 32);   // ... then ints
     constexpr int CJ = (MOE_MAX_EXPERTS + 63) / 64;
     const int nf = *n_flag;
-    for (int f = wave; f < nf; f += 4) {
+    for (int f = wave; f < nf; f += NWV) {
         const int tok = flag_tok[f], t = t0 + tok;
         const float thr = flag_thr[f];
         const uint16_t* xr = x + (size_t)t * d;
@@ -714,41 +699,40 @@ __device__ __forceinline__ void route_packed_body(const uint16_t* __restrict__ x
     }
 }
 
-template <int NBW, int RMAX>
-__global__ __launch_bounds__(NTH) void route_packed_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wgt,
-                                                           const float* __restrict__ w_norm2,
-                                                           const float* __restrict__ bias, int T, int d, int E, int k,
-                                                           int renorm, int32_t* __restrict__ idx_out,
-                                                           float* __restrict__ w_out, float* __restrict__ logits_out) {
-    route_packed_body<NBW, RMAX>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx_out, w_out, logits_out);
+template <int NB, int KSP, int RMAX>
+__global__ __launch_bounds__(NB * KSP * 64, 2) void route_packed_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wgt,
+                                                                        const float* __restrict__ w_norm2,
+                                                                        const float* __restrict__ bias, int T, int d, int E, int k,
+                                                                        int renorm, int32_t* __restrict__ idx_out,
+                                                                        float* __restrict__ w_out, float* __restrict__ logits_out) {
+    route_packed_body<NB, KSP, RMAX>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx_out, w_out, logits_out);
 }
 
-template <int NBW, int RMAX>
+template <int NB, int KSP, int RMAX>
 int launch_packed_r(const void* x, const void* wgt, const float* w_norm2, const float* bias, int T, int d, int E, int k,
-                  int renorm, int32_t* idx, float* w, float* logits, hipStream_t st) {
-    const int EPT = ((E + 31) / 32) * 32;
-    size_t smem = (size_t)2 * 32 * (32 * NBW) * 8 + (size_t)32 * (EPT + 4) * 4 + 4 * 32 * 4 + 4 * 32 * 4 + 64;
-    const size_t cand = (size_t)4 * (MOE_MAX_EXPERTS + 32) * 12;           // the exact path's lists reuse the slabs
-    if (smem < cand + (size_t)32 * (EPT + 4) * 4 + 1200) smem = cand + (size_t)32 * (EPT + 4) * 4 + 1200;
-    auto kern = route_packed_kernel<NBW, RMAX>;
+                    int renorm, int32_t* idx, float* w, float* logits, hipStream_t st) {
+    constexpr int NWV = NB * KSP, EPT = 32 * NB;
+    constexpr size_t slab = KSP > 1 ? (size_t)KSP * 32 * EPT * 8 : 0, cand = (size_t)NWV * (MOE_MAX_EXPERTS + 32) * 12;
+    const size_t smem = (slab > cand ? slab : cand) + (size_t)32 * (EPT + 4) * 4 + KSP * 32 * 4 + 4 * 32 * 4 + 2 * NWV * 4 + 16;
+    auto kern = route_packed_kernel<NB, KSP, RMAX>;
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return moe_fail(MOE_ERR_HIP, "moe_route_topk_packed: shared memory attribute: %s", hipGetErrorString(e));
     }
-    hipLaunchKernelGGL(kern, dim3((T + 31) / 32), dim3(NTH), smem, st, (const uint16_t*)x, (const uint16_t*)wgt, w_norm2, bias,
-                       T, d, E, k, renorm, idx, w, logits);
+    hipLaunchKernelGGL(kern, dim3((T + 31) / 32), dim3(NWV * 64), smem, st, (const uint16_t*)x, (const uint16_t*)wgt, w_norm2,
+                       bias, T, d, E, k, renorm, idx, w, logits);
     MOE_CHECK_LAUNCH("moe_route_topk_packed");
     return MOE_OK;
 }
 
-template <int NBW>
+template <int NB, int KSP>
 int launch_packed(const void* x, const void* wgt, const float* w_norm2, const float* bias, int T, int d, int E, int k,
                   int renorm, int32_t* idx, float* w, float* logits, hipStream_t st) {
     // the depth of the per-thread top list follows k (a shorter list is less work per logit)
-    if (k <= 1) return launch_packed_r<NBW, 2>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
-    if (k <= 2) return launch_packed_r<NBW, 3>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
-    if (k <= 4) return launch_packed_r<NBW, 5>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
-    return launch_packed_r<NBW, MAXR>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    if (k <= 1) return launch_packed_r<NB, KSP, 2>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    if (k <= 2) return launch_packed_r<NB, KSP, 3>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    if (k <= 4) return launch_packed_r<NB, KSP, 5>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    return launch_packed_r<NB, KSP, MAXR>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
 }
 
 template <int MT, int NJ>
@@ -775,7 +759,8 @@ int moe_route_bf16_mfma(const void* x, const void* wg, const float* bias, int T,
 // bf16 path of moe_route_topk_packed (arguments already validated by the caller)
 int moe_route_bf16_packed(const void* x, const void* wgt, const float* w_norm2, const float* bias, int T, int d, int E,
                           int k, int renorm, int32_t* idx, float* w, float* logits, hipStream_t st) {
-    if (E <= 32) return launch_packed<1>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
-    if (E <= 64) return launch_packed<2>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
-    return launch_packed<4>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    if (E <= 32) return launch_packed<1, 4>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    if (E <= 64) return launch_packed<2, 2>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    if (E <= 128) return launch_packed<4, 1>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
+    return launch_packed<8, 1>(x, wgt, w_norm2, bias, T, d, E, k, renorm, idx, w, logits, st);
 }
