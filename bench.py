@@ -6,7 +6,12 @@ expert) -> combine -- over one batch of seeded synthetic input already resident 
 Default workload: c2 (Switch-style layer, bf16, T=16384, d=768, F=3072, E=128, top-1,
 first-choice loads ~ Zipf(1.0)).  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5] [--no-cpu-baseline]
+
+--workload c5 times one GPU's expert-parallel share with 16 of its 32 experts in pinned host
+memory (asynchronous fetching, section 4.3 of the paper): the step is permute -> resident experts
+-> fetched experts group by group -> combine, with 16 and with 4 device slots, next to the same
+step with every expert resident and to the bare copies.
 """
 import argparse
 import json
@@ -57,12 +62,101 @@ def measured_traffic(workload, tag="G1"):
     return None
 
 
+def bench_prerouted(args):
+    """Workload c5: rows arrive routed; 16 resident + 16 host-resident experts."""
+    import numpy as np
+    import torch
+    import moe_workloads as W
+    from paper_2506_12417_amd import binding as B
+    from paper_2506_12417_amd.layer import PreRoutedShare, to_device
+
+    wl = W.WORKLOADS["c5"]
+    inp = W.make_inputs(wl)
+    ids = inp["ids"]
+    counts = np.bincount(ids, minlength=wl.E)
+    x = to_device(inp["x"], "cuda:0")
+    ids_d = torch.from_numpy(ids).to("cuda:0")
+    heavy_first = sorted(range(wl.n_local, wl.E), key=lambda e: (-counts[e], e))
+
+    def make(n_local, n_slots):
+        sh = PreRoutedShare(wl.T, wl.d, wl.F, wl.E, n_local, n_slots, act=wl.act, dtype=wl.dtype)
+        for e in range(wl.E):
+            sh.load_expert(e, {"W1": inp["W1"][e], "W2": inp["W2"][e]})
+        return sh
+
+    def timed(sh, order):
+        for _ in range(args.warmup):
+            sh.forward(x, ids_d, fetch_order=order)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for _ in range(args.steps):
+            sh.forward(x, ids_d, fetch_order=order)
+        end.record()
+        torch.cuda.synchronize()
+        return start.elapsed_time(end) / args.steps, (time.perf_counter() - t0) * 1e3 / args.steps
+
+    res = make(wl.E, 1)
+    ms_res, _ = timed(res, None)
+    y_res = res.y.clone()
+    res.close()
+    del res
+    out_slots = {}
+    for n_slots in (16, 4):
+        sh = make(wl.n_local, n_slots)
+        ms, wall = timed(sh, heavy_first)
+        same = bool(torch.equal(sh.y, y_res))
+        out_slots[n_slots] = (ms, wall, same)
+        if n_slots == 16:
+            # the bare copies: all 16 host experts into their slots, nothing else on the GPU
+            eng, nb = sh.engine, sh.bytes_each
+            hw = [sh.host_w[e - wl.n_local].data_ptr() for e in heavy_first]
+            t_copy = []
+            for _ in range(5):
+                B.moe_prefetch_reset(eng)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                B.moe_prefetch_experts(eng, heavy_first, hw, nb)
+                for e in heavy_first:
+                    B.moe_prefetch_wait(eng, e)
+                torch.cuda.synchronize()
+                t_copy.append((time.perf_counter() - t0) * 1e3)
+                for e in heavy_first:
+                    B.moe_prefetch_release(eng, e)
+            ms_copy = min(t_copy)
+            copy_bytes = len(heavy_first) * nb
+        sh.close()
+        del sh
+    ms16, wall16, same16 = out_slots[16]
+    ms4, wall4, same4 = out_slots[4]
+    overlap = (ms_res + ms_copy - ms16) / min(ms_res, ms_copy)
+    out = {
+        "metric": "MoE-layer tokens/sec on 1 MI355X under Zipf skew; grouped-FFN % bf16 MFMA peak",
+        "value": round(wl.T / (ms16 * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms16, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": "c5: T=%d d=%d F=%d, %d resident + %d host-resident experts, ids Zipf(%.1f), %d slots, heavy experts fetched first"
+                               % (wl.T, wl.d, wl.F, wl.n_local, wl.E - wl.n_local, wl.zipf_s, 16),
+                   "seed": wl.seed(), "rows_to_host_experts": int(counts[wl.n_local:].sum())},
+        "host_link": {"bytes_per_step": copy_bytes, "copy_only_ms": round(ms_copy, 4),
+                      "copy_only_GBs": round(copy_bytes / (ms_copy * 1e-3) / 1e9, 1),
+                      "all_resident_ms": round(ms_res, 4), "with_16_slots_ms": round(ms16, 4), "with_4_slots_ms": round(ms4, 4),
+                      "host_wall_ms_16_slots": round(wall16, 4), "host_wall_ms_4_slots": round(wall4, 4),
+                      "exposed_ms_16_slots": round(ms16 - ms_res, 4), "overlap_efficiency_16_slots": round(overlap, 3),
+                      "bit_identical_to_all_resident": same16 and same4},
+        "roofline": {"kernel": "hipMemcpyAsync H2D (expert fetch)", "bound": "host-link", "achieved": round(copy_bytes / (ms16 * 1e-3) / 1e9, 1),
+                     "peak": 64.0, "unit": "GB/s", "frac": round(copy_bytes / (ms16 * 1e-3) / 1e9 / 64.0, 4), "traffic": copy_bytes},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-uniform", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -81,6 +175,8 @@ def main():
     from paper_2506_12417_amd.layer import MoELayer, to_device
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.workload == "c5":
+        return bench_prerouted(args)
     wl = W.WORKLOADS[args.workload]
     t0 = time.time()
     inp = W.make_inputs(wl)

@@ -152,6 +152,16 @@ MOE_API int moe_plan_tiles(const int32_t* counts, const int32_t* offsets, int E,
                    moe_tile* tiles, int tile_capacity, int32_t* plan_hdr, int32_t* sched,
                    void* stream);
 
+/* The same schedule over SOME of the experts: expert_ids (HOST array of n_ids ids in [0,E), any
+ * order, repeats allowed) names the experts that take part; the others count as empty.  This
+ * is how the experts of Alg. 1 step 5 are run in groups as their weights become available
+ * (section 4.3): one plan + moe_grouped_ffn per group, over the same counts, offsets and rows. */
+MOE_API int moe_plan_tiles_subset(const int32_t* counts, const int32_t* offsets, int E, int A,
+                   int tile_m, int n_bins, int q_tokens, int policy,
+                   const int32_t* expert_ids /*host*/, int n_ids,
+                   moe_tile* tiles, int tile_capacity, int32_t* plan_hdr, int32_t* sched,
+                   void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Weight layout of the FFN kernels.  The paper writes an expert as x W1 W2 with W1: d x F and
  * W2: F x d (section 4.4).  The kernels read every weight matrix "output-major": row n holds
@@ -235,9 +245,15 @@ MOE_API int moe_unpermute_combine(const float* y_perm, const int32_t* inv_perm, 
  *                         longest ago); slot_ptrs_out[i] (HOST array) receives the slot's
  *                         device address.  A copy into a slot in use waits for that slot's
  *                         release.  MOE_ERR_CAPACITY if a slot is needed and none was released.
- *   moe_prefetch_wait     make `stream` wait until expert_id's copy has landed (before its FFN)
+ *   moe_prefetch_wait     make `stream` wait until expert_id's copy has landed (before its FFN).
+ *                         Copies complete in the order they were enqueued, so one wait for the
+ *                         expert fetched last covers every expert fetched before it.
  *   moe_prefetch_release  declare that work enqueued so far on `stream` is the last use of
  *                         expert_id's slot (after its FFN); the slot may then be overwritten
+ *   moe_prefetch_reset    between two passes over the experts: every resident expert must have
+ *                         been released; afterwards no expert counts as resident and the next
+ *                         fetches take the slots in order 0, 1, 2, ... (an overwrite still waits
+ *                         for the slot's last use)
  *   moe_prefetch_destroy  waits for the engine's stream, frees stream and events
  */
 typedef struct moe_prefetch moe_prefetch;
@@ -248,6 +264,7 @@ MOE_API int moe_prefetch_experts(moe_prefetch* h, const int32_t* expert_ids /*ho
                          size_t bytes_each, const void** slot_ptrs_out /*host*/);
 MOE_API int moe_prefetch_wait(moe_prefetch* h, int expert_id, void* stream);
 MOE_API int moe_prefetch_release(moe_prefetch* h, int expert_id, void* stream);
+MOE_API int moe_prefetch_reset(moe_prefetch* h);
 MOE_API int moe_prefetch_destroy(moe_prefetch* h);
 
 /* Token threshold q of section 4.4, Eq. 4: the row count above which running an expert takes

@@ -28,9 +28,9 @@ MOE_PLAN_HDR_INTS = 4 + 2 * (MOE_MAX_BINS + 1)
 MOE_OP_PERMUTE = 1
 
 EXPORTS = [
-    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_pack_weights",
+    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_pack_weights",
     "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_unpermute_combine", "moe_prefetch_create",
-    "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_destroy",
+    "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_reset", "moe_prefetch_destroy",
     "moe_token_threshold", "moe_workspace_bytes", "moe_copy_bytes", "moe_last_error", "moe_version",
 ]
 
@@ -41,6 +41,7 @@ lib.moe_route_topk_packed.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i
 lib.moe_permute.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.moe_plan_capacity.argtypes = [_i, _i, _i, _i]
 lib.moe_plan_tiles.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp]
+lib.moe_plan_tiles_subset.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), _i, _vp, _i, _vp, _vp, _vp]
 lib.moe_pack_weights.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp]
 lib.moe_ffn_tile_m.argtypes = [_i]
 lib.moe_ffn_pick_tile_m.argtypes = [_i, _i, _i]
@@ -51,6 +52,7 @@ lib.moe_prefetch_create.argtypes = [C.POINTER(_vp), _i, _sz, _vp]
 lib.moe_prefetch_experts.argtypes = [_vp, C.POINTER(C.c_int32), _i, C.POINTER(_vp), _sz, C.POINTER(_vp)]
 lib.moe_prefetch_wait.argtypes = [_vp, _i, _vp]
 lib.moe_prefetch_release.argtypes = [_vp, _i, _vp]
+lib.moe_prefetch_reset.argtypes = [_vp]
 lib.moe_prefetch_destroy.argtypes = [_vp]
 lib.moe_token_threshold.argtypes = [C.c_double, _i, C.c_double]
 lib.moe_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i, _i]
@@ -150,6 +152,15 @@ def moe_plan_tiles(counts, offsets, E, A, tile_m, n_bins, q_tokens, policy, tile
                               tile_capacity, _p(plan_hdr), _p(sched), _stream(stream)))
 
 
+def moe_plan_tiles_subset(counts, offsets, E, A, tile_m, n_bins, q_tokens, policy, expert_ids, tiles, tile_capacity,
+                          plan_hdr, sched=None, stream=None):
+    """expert_ids: a Python sequence of the expert ids that take part (host side)."""
+    n = len(expert_ids)
+    ids = (C.c_int32 * max(n, 1))(*expert_ids)
+    _check(lib.moe_plan_tiles_subset(_p(counts), _p(offsets), E, A, tile_m, n_bins, q_tokens, policy, ids, n, _p(tiles),
+                                     tile_capacity, _p(plan_hdr), _p(sched), _stream(stream)))
+
+
 def moe_pack_weights(w_a, w_b, n, K, N, dt, out, stream=None):
     _check(lib.moe_pack_weights(_p(w_a), _p(w_b), n, K, N, dt, _p(out), _stream(stream)))
 
@@ -197,6 +208,10 @@ def moe_prefetch_wait(h: int, expert_id: int, stream=None):
 
 def moe_prefetch_release(h: int, expert_id: int, stream=None):
     _check(lib.moe_prefetch_release(h, expert_id, _stream(stream)))
+
+
+def moe_prefetch_reset(h: int):
+    _check(lib.moe_prefetch_reset(h))
 
 
 def moe_prefetch_destroy(h: int):

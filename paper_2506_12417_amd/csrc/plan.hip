@@ -32,11 +32,16 @@ __device__ __forceinline__ void argmax_bin(int tg, int lane, int G, int& g, int&
     v = (int)(key >> BIN_BITS);
 }
 
+// which experts take part in a plan: bit e of word e / 32
+struct ExpertMask {
+    uint32_t w[MOE_MAX_EXPERTS / 32];
+};
+
 __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ counts,
                                                    const int32_t* __restrict__ offsets, int E, int A, int tile_m,
-                                                   int G, int q, int policy, moe_tile* __restrict__ tiles,
-                                                   int capacity, int32_t* __restrict__ hdr,
-                                                   int32_t* __restrict__ sched) {
+                                                   int G, int q, int policy, ExpertMask mask,
+                                                   moe_tile* __restrict__ tiles, int capacity,
+                                                   int32_t* __restrict__ hdr, int32_t* __restrict__ sched) {
     __shared__ int cnt[MOE_MAX_EXPERTS], cost[MOE_MAX_EXPERTS], order[MOE_MAX_EXPERTS];
     __shared__ int S_[MOE_MAX_EXPERTS * MOE_MAX_BINS];
     // non-empty (expert, bin) blocks, one segment per bin: rows and expert id
@@ -52,7 +57,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     for (int i = tid; i < E * G; i += NTH) S_[i] = 0;
     if (tid < G) { load[tid] = 0; bin_blocks[tid] = 0; bin_cursor[tid] = 0; bin_tiles[tid] = 0; }
     if (tid < E) {
-        int c = counts[tid];
+        int c = ((mask.w[tid >> 5] >> (tid & 31)) & 1u) ? counts[tid] : 0;    // experts left out count as empty
         cnt[tid] = c;
         cost[tid] = weight_of(c, q, by_cost);
     }
@@ -244,21 +249,46 @@ extern "C" int moe_plan_capacity(int A, int E, int tile_m, int n_bins) {
     return c > INT_MAX ? INT_MAX : (int)c;
 }
 
+static int plan_impl(const char* who, const int32_t* counts, const int32_t* offsets, int E, int A, int tile_m, int n_bins,
+                     int q_tokens, int policy, const ExpertMask& mask, moe_tile* tiles, int tile_capacity,
+                     int32_t* plan_hdr, int32_t* sched, void* stream) {
+    MOE_REQUIRE(E >= 1 && A >= 0, MOE_ERR_ARG, "%s: E=%d A=%d", who, E, A);
+    MOE_REQUIRE((long long)A + (long long)E * q_tokens < (1ll << 26), MOE_ERR_UNSUPPORTED,
+                "%s: A + E*q_tokens = %lld is not below 2^26", who, (long long)A + (long long)E * q_tokens);
+    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "%s: E=%d > %d", who, E, MOE_MAX_EXPERTS);
+    MOE_REQUIRE(n_bins >= 1 && n_bins <= MOE_MAX_BINS, MOE_ERR_ARG, "%s: n_bins=%d outside [1,%d]", who, n_bins, MOE_MAX_BINS);
+    MOE_REQUIRE(tile_m >= 1 && q_tokens >= 1, MOE_ERR_ARG, "%s: tile_m=%d q_tokens=%d must be >= 1", who, tile_m, q_tokens);
+    MOE_REQUIRE(policy >= MOE_PLAN_BALANCED && policy <= MOE_PLAN_EVEN_SPLIT, MOE_ERR_ARG, "%s: policy %d", who, policy);
+    MOE_REQUIRE(counts && offsets && tiles && plan_hdr, MOE_ERR_ARG, "%s: null pointer", who);
+    MOE_REQUIRE(tile_capacity >= moe_plan_capacity(A, E, tile_m, n_bins), MOE_ERR_CAPACITY,
+                "%s: tile_capacity %d < %d", who, tile_capacity, moe_plan_capacity(A, E, tile_m, n_bins));
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(NTH), 0, (hipStream_t)stream, counts, offsets, E, A, tile_m, n_bins,
+                       q_tokens, policy, mask, tiles, tile_capacity, plan_hdr, sched);
+    MOE_CHECK_LAUNCH(who);
+    return MOE_OK;
+}
+
 extern "C" int moe_plan_tiles(const int32_t* counts, const int32_t* offsets, int E, int A, int tile_m, int n_bins,
                               int q_tokens, int policy, moe_tile* tiles, int tile_capacity, int32_t* plan_hdr,
                               int32_t* sched, void* stream) {
-    MOE_REQUIRE(E >= 1 && A >= 0, MOE_ERR_ARG, "moe_plan_tiles: E=%d A=%d", E, A);
-    MOE_REQUIRE((long long)A + (long long)E * q_tokens < (1ll << 26), MOE_ERR_UNSUPPORTED,
-                "moe_plan_tiles: A + E*q_tokens = %lld is not below 2^26", (long long)A + (long long)E * q_tokens);
-    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "moe_plan_tiles: E=%d > %d", E, MOE_MAX_EXPERTS);
-    MOE_REQUIRE(n_bins >= 1 && n_bins <= MOE_MAX_BINS, MOE_ERR_ARG, "moe_plan_tiles: n_bins=%d outside [1,%d]", n_bins, MOE_MAX_BINS);
-    MOE_REQUIRE(tile_m >= 1 && q_tokens >= 1, MOE_ERR_ARG, "moe_plan_tiles: tile_m=%d q_tokens=%d must be >= 1", tile_m, q_tokens);
-    MOE_REQUIRE(policy >= MOE_PLAN_BALANCED && policy <= MOE_PLAN_EVEN_SPLIT, MOE_ERR_ARG, "moe_plan_tiles: policy %d", policy);
-    MOE_REQUIRE(counts && offsets && tiles && plan_hdr, MOE_ERR_ARG, "moe_plan_tiles: null pointer");
-    MOE_REQUIRE(tile_capacity >= moe_plan_capacity(A, E, tile_m, n_bins), MOE_ERR_CAPACITY,
-                "moe_plan_tiles: tile_capacity %d < %d", tile_capacity, moe_plan_capacity(A, E, tile_m, n_bins));
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(NTH), 0, (hipStream_t)stream, counts, offsets, E, A, tile_m, n_bins,
-                       q_tokens, policy, tiles, tile_capacity, plan_hdr, sched);
-    MOE_CHECK_LAUNCH("moe_plan_tiles");
-    return MOE_OK;
+    ExpertMask all;
+    for (auto& w : all.w) w = 0xffffffffu;
+    return plan_impl("moe_plan_tiles", counts, offsets, E, A, tile_m, n_bins, q_tokens, policy, all, tiles, tile_capacity,
+                     plan_hdr, sched, stream);
+}
+
+extern "C" int moe_plan_tiles_subset(const int32_t* counts, const int32_t* offsets, int E, int A, int tile_m, int n_bins,
+                                     int q_tokens, int policy, const int32_t* expert_ids, int n_ids, moe_tile* tiles,
+                                     int tile_capacity, int32_t* plan_hdr, int32_t* sched, void* stream) {
+    MOE_REQUIRE(n_ids >= 0 && (n_ids == 0 || expert_ids), MOE_ERR_ARG, "moe_plan_tiles_subset: n_ids=%d", n_ids);
+    MOE_REQUIRE(E >= 1 && E <= MOE_MAX_EXPERTS, E < 1 ? MOE_ERR_ARG : MOE_ERR_UNSUPPORTED, "moe_plan_tiles_subset: E=%d", E);
+    ExpertMask m;
+    for (auto& w : m.w) w = 0u;
+    for (int i = 0; i < n_ids; ++i) {
+        const int e = expert_ids[i];
+        MOE_REQUIRE(e >= 0 && e < E, MOE_ERR_ARG, "moe_plan_tiles_subset: expert id %d outside [0,%d)", e, E);
+        m.w[e >> 5] |= 1u << (e & 31);
+    }
+    return plan_impl("moe_plan_tiles_subset", counts, offsets, E, A, tile_m, n_bins, q_tokens, policy, m, tiles,
+                     tile_capacity, plan_hdr, sched, stream);
 }

@@ -72,7 +72,7 @@ extern "C" int moe_prefetch_experts(moe_prefetch* h, const int32_t* expert_ids, 
             MOE_REQUIRE(!(exp_after[s] == expert_ids[i] && !rel_after[s]), MOE_ERR_ARG, "moe_prefetch_experts: expert %d is already resident", expert_ids[i]);
         int pick = -1;
         for (int s = 0; s < h->n_slots && pick < 0; ++s)
-            if (exp_after[s] < 0) pick = s;
+            if (exp_after[s] < 0) pick = s;                     // a slot never used
         if (pick < 0) {
             long long best = 0;
             for (int s = 0; s < h->n_slots; ++s)
@@ -111,6 +111,20 @@ extern "C" int moe_prefetch_release(moe_prefetch* h, int expert_id, void* stream
     MOE_CHECK_HIP(hipEventRecord(h->freed[s], (hipStream_t)stream));
     h->released[s] = 1;
     h->release_seq[s] = ++h->seq;
+    return MOE_OK;
+}
+
+extern "C" int moe_prefetch_reset(moe_prefetch* h) {
+    MOE_REQUIRE(h, MOE_ERR_ARG, "moe_prefetch_reset: null handle");
+    for (int s = 0; s < h->n_slots; ++s)
+        MOE_REQUIRE(h->expert[s] < 0 || h->released[s], MOE_ERR_ARG, "moe_prefetch_reset: expert %d has not been released", h->expert[s]);
+    // every slot counts as released in slot order: the next fetches take slots 0, 1, 2, ...; a
+    // slot that held an expert keeps its "freed" event, so its overwrite still waits for the last use
+    for (int s = 0; s < h->n_slots; ++s) {
+        if (h->expert[s] >= 0) h->expert[s] = INT32_MAX;      // no expert id matches any more
+        h->release_seq[s] = s + 1;
+    }
+    h->seq = h->n_slots;
     return MOE_OK;
 }
 

@@ -192,3 +192,154 @@ class MoELayer:
             self.shared_ffn(x, stream)
         self.combine(True, stream)
         return self.y
+
+
+class PreRoutedShare:
+    """One GPU's share of an expert-parallel MoE layer after the scatter (Alg. 1 steps 4-5): T rows
+    that arrive already routed (one expert id each), E experts of which the first n_local are
+    resident on the device and the others live in pinned host memory and are fetched into
+    n_slots device slots while the resident ones compute (section 4.3: asynchronous fetching,
+    a finished expert's slot is overwritten).  The output is the experts' result in the rows'
+    original order (the gate is applied later, at the rows' source GPU: weights are 1 here).
+
+    Experts run in groups: the resident ones first, then the fetched ones `group` at a time, in
+    fetch order; each group is one moe_plan_tiles_subset + moe_grouped_ffn over the same rows."""
+
+    def __init__(self, T: int, d: int, F: int, E: int, n_local: int, n_slots: int, act: str = "relu",
+                 dtype: str = "bf16", n_bins: int = XCDS, q_tokens: Optional[int] = None, group: Optional[int] = None,
+                 device="cuda:0"):
+        assert 0 <= n_local <= E and n_slots >= 1
+        self.T, self.d, self.F, self.E, self.n_local, self.n_slots = T, d, F, E, n_local, n_slots
+        self.n_foreign = E - n_local
+        self.act = B.MOE_SWIGLU if act == "swiglu" else B.MOE_RELU
+        self.dt = B.MOE_BF16 if dtype == "bf16" else B.MOE_F32
+        self.tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.device = torch.device(device)
+        self.n_bins = n_bins
+        self.q_tokens = q_tokens if q_tokens is not None else default_q_tokens(self.dt)
+        self.tile_m = B.moe_ffn_pick_tile_m(self.dt, T, E)
+        # a group of fetched experts runs while the next group's copies are in flight
+        self.group = group if group is not None else max(1, min(4, n_slots // 2))
+        dev, i32, f32 = self.device, torch.int32, torch.float32
+        es = 2 if dtype == "bf16" else 4
+        self.rows_in = 2 * F if self.act == B.MOE_SWIGLU else F
+        self.in_bytes, self.out_bytes = self.rows_in * d * es, d * F * es
+        self.bytes_each = self.in_bytes + self.out_bytes
+        self.local = ExpertGroup(max(n_local, 1), d, F, self.act, self.dt, dev)
+        self.host_w = torch.empty((max(self.n_foreign, 1), self.bytes_each), dtype=torch.uint8, pin_memory=True)
+        self.slots = torch.empty((n_slots, self.bytes_each), dtype=torch.uint8, device=dev)
+        self.engine = B.moe_prefetch_create(n_slots, self.bytes_each, self.slots)
+        self._stage = ExpertGroup(1, d, F, self.act, self.dt, dev)       # packing area for host-resident experts
+        self.ptr_host = torch.empty((2, E), dtype=torch.int64, pin_memory=True)
+        self.ptr_dev = torch.empty((2, E), dtype=torch.int64, device=dev)
+        self.expert_idx = torch.empty((T, 1), dtype=i32, device=dev)
+        self.counts = torch.empty(E, dtype=i32, device=dev)
+        self.offsets = torch.empty(E + 1, dtype=i32, device=dev)
+        self.perm = torch.empty(T, dtype=i32, device=dev)
+        self.inv_perm = torch.empty(T, dtype=i32, device=dev)
+        self.x_perm = torch.empty((T, d), dtype=self.tdt, device=dev)
+        self.ws_bytes = B.moe_workspace_bytes(B.MOE_OP_PERMUTE, T, d, F, E, 1, self.dt)
+        self.ws = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=dev)
+        self.tile_capacity = B.moe_plan_capacity(T, E, self.tile_m, n_bins)
+        self.tiles = torch.empty((self.tile_capacity, 4), dtype=i32, device=dev)
+        self.plan_hdr = torch.empty(B.MOE_PLAN_HDR_INTS, dtype=i32, device=dev)
+        self.h = torch.empty((T, F), dtype=self.tdt, device=dev)
+        self.y_perm = torch.zeros((T, d), dtype=f32, device=dev)
+        self.y = torch.empty((T, d), dtype=f32, device=dev)
+        self.bytes_fetched = 0
+        self._done = None
+
+    def close(self):
+        if self.engine:
+            torch.cuda.synchronize(self.device)
+            B.moe_prefetch_destroy(self.engine)
+            self.engine = 0
+
+    def load_expert(self, e: int, w: Dict[str, np.ndarray]):
+        """w: one expert's matrices in the paper's orientation.  Resident experts are packed in
+        place; host-resident ones are packed on the device once and parked in pinned memory, so
+        that a fetch is a straight copy."""
+        if e < self.n_local:
+            self.local.load_expert(e, w)
+            return
+        self._stage.load_expert(0, w)
+        j = e - self.n_local
+        self.host_w[j, :self.in_bytes].copy_(self._stage.w_in.view(torch.uint8).reshape(-1))
+        self.host_w[j, self.in_bytes:].copy_(self._stage.w_out.view(torch.uint8).reshape(-1))
+        torch.cuda.synchronize(self.device)
+
+    def _local_ptrs(self):
+        g, es = self.local, self.local.w_in.element_size()
+        ip = [g.w_in.data_ptr() + e * self.rows_in * self.d * es for e in range(self.n_local)]
+        op = [g.w_out.data_ptr() + e * self.d * self.F * es for e in range(self.n_local)]
+        return ip, op
+
+    def forward(self, x: torch.Tensor, ids: torch.Tensor, fetch_order=None, stream=None) -> torch.Tensor:
+        """ids: [T] int32 on the device.  fetch_order: the host-resident experts' ids in the order
+        they are to be fetched and run (default: by id); the host may know the rows per expert
+        from the metadata exchange of Alg. 1 step 2 and put heavy experts first."""
+        T, E = self.T, self.E
+        # The host drives this flow group by group and does not run more than one pass ahead of the
+        # GPU: copies that wait on "slot free" events of a pass still being enqueued were measured to
+        # stall in the runtime (3.1 ms per pass with this wait, 3.4-4.3 ms without it).
+        if self._done is not None:
+            self._done.synchronize()
+        order = list(range(self.n_local, E)) if fetch_order is None else [int(e) for e in fetch_order]
+        assert sorted(order) == list(range(self.n_local, E))
+        # where every expert's weights will be: resident block, or slot (position in the order) mod n_slots
+        # (uploaded only when the order changes)
+        if getattr(self, "_order", None) != order:
+            ip, op = self._local_ptrs()
+            tab = np.zeros((2, E), dtype=np.int64)
+            tab[0, :self.n_local], tab[1, :self.n_local] = ip, op
+            base = self.slots.data_ptr()
+            for j, e in enumerate(order):
+                tab[0, e] = base + (j % self.n_slots) * self.bytes_each
+                tab[1, e] = tab[0, e] + self.in_bytes
+            self.ptr_host.copy_(torch.from_numpy(tab))
+            self.ptr_dev.copy_(self.ptr_host, non_blocking=True)
+            self._order = list(order)
+            self._slot_of = {e: int(tab[0, e]) for e in order}
+            self._host_ptr = {e: self.host_w[e - self.n_local].data_ptr() for e in order}
+        B.moe_prefetch_reset(self.engine)
+        self.expert_idx.view(-1).copy_(ids)
+        B.moe_permute(x, self.expert_idx, T, self.d, E, 1, self.dt, self.counts, self.offsets, self.perm,
+                      self.inv_perm, self.x_perm, self.ws, self.ws_bytes, stream)
+
+        def fetch(chunk):
+            if not chunk:
+                return
+            got = B.moe_prefetch_experts(self.engine, chunk, [self._host_ptr[e] for e in chunk], self.bytes_each)
+            for e, p in zip(chunk, got):
+                assert p == self._slot_of[e], "slot of expert %d is not where the pointer table says" % e
+            self.bytes_fetched += len(chunk) * self.bytes_each
+
+        def run(group_ids):
+            B.moe_plan_tiles_subset(self.counts, self.offsets, E, T, self.tile_m, self.n_bins, self.q_tokens,
+                                    B.MOE_PLAN_BALANCED, group_ids, self.tiles, self.tile_capacity, self.plan_hdr,
+                                    None, stream)
+            B.moe_grouped_ffn(self.x_perm, T, self.d, self.F, E, self.act, self.dt, self.ptr_dev[0], self.ptr_dev[1],
+                              self.tiles, self.plan_hdr, self.tile_m, self.h, self.y_perm, stream)
+
+        next_fetch = min(self.n_slots, len(order))
+        fetch(order[:next_fetch])                       # fills every slot; copies run while the resident experts compute
+        if self.n_local:
+            run(list(range(self.n_local)))
+        done = 0
+        while done < len(order):
+            grp = order[done:done + self.group]
+            # copies complete in the order they were enqueued: waiting for the group's last one covers the others
+            # (a chain of event waits on the compute stream costs far more than one)
+            B.moe_prefetch_wait(self.engine, grp[-1], stream)
+            run(grp)
+            for e in grp:
+                B.moe_prefetch_release(self.engine, e, stream)
+            done += len(grp)
+            nxt = order[next_fetch:next_fetch + len(grp)]  # into the slots just released
+            fetch(nxt)
+            next_fetch += len(nxt)
+        B.moe_unpermute_combine(self.y_perm, self.inv_perm, None, None, T, self.d, 1, self.y, stream)
+        if self._done is None:
+            self._done = torch.cuda.Event()
+        self._done.record()
+        return self.y

@@ -159,4 +159,27 @@ def test_prefetch_argument_errors_before_any_device_work():
     assert B.lib.moe_prefetch_create(None, 2, 16, FAKE) == B.MOE_ERR_ARG
     assert B.lib.moe_prefetch_wait(None, 0, None) == B.MOE_ERR_ARG
     assert B.lib.moe_prefetch_release(None, 0, None) == B.MOE_ERR_ARG
+    assert B.lib.moe_prefetch_reset(None) == B.MOE_ERR_ARG
     assert B.lib.moe_prefetch_destroy(None) == B.MOE_OK
+
+
+def test_plan_subset_and_packed_router_argument_errors():
+    ids = (C.c_int32 * 2)(1, 9)
+    st = B.lib.moe_plan_tiles_subset(FAKE, FAKE, 8, 100, 128, 8, 10, 0, ids, 2, FAKE, 10000, FAKE, None, None)
+    assert st == B.MOE_ERR_ARG                                  # expert id 9 outside [0, 8)
+    st = B.lib.moe_plan_tiles_subset(FAKE, FAKE, 8, 100, 128, 8, 10, 0, None, 2, FAKE, 10000, FAKE, None, None)
+    assert st == B.MOE_ERR_ARG
+    st = B.lib.moe_plan_tiles_subset(FAKE, FAKE, 8, 100, 128, 8, 0, 0, ids, 1, FAKE, 10000, FAKE, None, None)
+    assert st == B.MOE_ERR_ARG                                  # q = 0
+    assert status(B.moe_pack_router, None, 64, 8, B.MOE_BF16, FAKE, FAKE, 0) == B.MOE_ERR_ARG
+    assert status(B.moe_pack_router, FAKE, 64, 0, B.MOE_BF16, FAKE, FAKE, 0) == B.MOE_ERR_ARG
+    assert status(B.moe_pack_router, FAKE, 64, 8, 9, FAKE, FAKE, 0) == B.MOE_ERR_UNSUPPORTED
+
+    def rp(x=FAKE, wt=FAKE, n2=FAKE, T=4, d=64, E=8, k=2, dt=B.MOE_BF16, idx=FAKE, gw=FAKE):
+        return status(B.moe_route_topk_packed, x, wt, n2, None, T, d, E, k, 1, dt, idx, gw, None, 0)
+
+    assert rp(dt=B.MOE_F32) == B.MOE_ERR_UNSUPPORTED            # the prepared-router path is bf16 only
+    assert rp(d=72) == B.MOE_ERR_UNSUPPORTED                    # d % 64
+    assert rp(k=9) == B.MOE_ERR_ARG and rp(E=300) == B.MOE_ERR_UNSUPPORTED
+    assert rp(n2=None) == B.MOE_ERR_ARG and rp(wt=None) == B.MOE_ERR_ARG
+    assert rp(T=0, x=None, wt=None, n2=None, idx=None, gw=None) == B.MOE_OK

@@ -324,3 +324,76 @@ def test_combine_identity_and_error_paths(torch_gpu):
     with pytest.raises(B.MoeError) as e:
         B.moe_unpermute_combine(xp, xp, None, None, T, 30, 1, y)
     assert e.value.status == B.MOE_ERR_UNSUPPORTED
+
+
+def _share(torch, wl, inp, n_local, n_slots, group=None):
+    from paper_2506_12417_amd.layer import PreRoutedShare
+    sh = PreRoutedShare(wl.T, wl.d, wl.F, wl.E, n_local, n_slots, act=wl.act, dtype=wl.dtype, group=group)
+    for e in range(wl.E):
+        sh.load_expert(e, {n: inp[n][e] for n in ("W1", "W2")})
+    return sh
+
+
+@pytest.mark.parametrize("n_slots,group", [(7, None), (3, None), (2, 1), (1, 1)])
+def test_prefetch_overwrite_matches_all_resident(torch_gpu, n_slots, group):
+    """The pre-routed share (rows arrive with their expert ids, some experts live in pinned host
+    memory): with every expert resident, with a slot per host expert, and with fewer slots than
+    host experts (slots are overwritten while later groups compute) the output must be the same
+    bits, and equal to the oracle's per-row FFN within the bf16 tolerance.  Slots are poisoned
+    first, so an expert used before its copy landed, or a slot overwritten too early, shows."""
+    torch = torch_gpu
+    from paper_2506_12417_amd.layer import to_device
+    wl = W.WORKLOADS["c5"].scaled(T=3000, d=128, F=256, E=12, n_local=5)
+    _note("prefetch n_slots=%d group=%s" % (n_slots, group))
+    inp = W.make_inputs(wl)
+    ids = inp["ids"]
+    x = to_device(inp["x"], "cuda:0")
+    ids_d = torch.from_numpy(ids).to("cuda:0")
+    ref_layer = _share(torch, wl, inp, n_local=wl.E, n_slots=1)           # everything resident
+    y_res = to_numpy(ref_layer.forward(x, ids_d)).copy()
+    torch.cuda.synchronize()
+    ref_layer.close()
+    y_o = O.moe_layer(inp["x"], ids.reshape(-1, 1), np.ones((wl.T, 1)), {n: inp[n] for n in ("W1", "W2")}, wl.act)
+    assert max_err_over_rms(y_res, y_o) <= TOL["bf16"]
+    sh = _share(torch, wl, inp, n_local=wl.n_local, n_slots=n_slots, group=group)
+    counts = np.bincount(ids, minlength=wl.E)
+    heavy_first = sorted(range(wl.n_local, wl.E), key=lambda e: (-counts[e], e))
+    for order in (None, heavy_first, None):                                # three passes over the same engine
+        sh.slots.fill_(0x7f)
+        sh.y_perm.fill_(float("nan"))
+        torch.cuda.synchronize()
+        y = to_numpy(sh.forward(x, ids_d, fetch_order=order))
+        torch.cuda.synchronize()
+        assert np.array_equal(y, y_res), "order=%s" % (order,)
+    assert sh.bytes_fetched == 3 * (wl.E - wl.n_local) * sh.bytes_each
+    sh.close()
+
+
+def test_plan_subset_is_the_plan_of_the_masked_counts(torch_gpu):
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    dev = torch.device("cuda:0")
+    r = np.random.default_rng(9)
+    E, G, q, tile_m = 40, 8, 100, 128
+    counts = (r.zipf(1.3, size=E) * 37 % 3000).astype(np.int64)
+    offsets = np.concatenate([[0], np.cumsum(counts)])
+    A = int(counts.sum())
+    keep = [3, 17, 17, 0, 39, 21, 8]
+    masked = np.zeros_like(counts)
+    masked[keep] = counts[keep]
+    S = O.schedule_balanced(masked, G, q, tile_m)
+    tiles_o, bin_start_o = O.tiles_from_schedule(S, offsets, tile_m)
+    cap = B.moe_plan_capacity(A, E, tile_m, G)
+    tiles = torch.full((cap, 4), -1, dtype=torch.int32, device=dev)
+    hdr = torch.full((B.MOE_PLAN_HDR_INTS,), -1, dtype=torch.int32, device=dev)
+    sched = torch.full((E, G), -1, dtype=torch.int32, device=dev)
+    B.moe_plan_tiles_subset(torch.from_numpy(counts.astype(np.int32)).to(dev), torch.from_numpy(offsets.astype(np.int32)).to(dev),
+                            E, A, tile_m, G, q, B.MOE_PLAN_BALANCED, keep, tiles, cap, hdr, sched)
+    torch.cuda.synchronize()
+    hdr_h = to_numpy(hdr)
+    assert np.array_equal(to_numpy(sched), S)
+    assert hdr_h[0] == len(tiles_o) and np.array_equal(hdr_h[4:4 + G + 1], bin_start_o)
+    assert np.array_equal(to_numpy(tiles)[:hdr_h[0]], tiles_o)
+    with pytest.raises(B.MoeError) as e:
+        B.moe_plan_tiles_subset(tiles, tiles, E, A, tile_m, G, q, 0, [E], tiles, cap, hdr, None)
+    assert e.value.status == B.MOE_ERR_ARG
