@@ -253,6 +253,7 @@ def main():
         "config": {"workload": "%s: T=%d d=%d F=%d E=%d top-%d %s%s, skew=%s" % (
             wl.name, wl.T, wl.d, wl.F, wl.E, wl.k, wl.act, (" + shared F=%d" % wl.shared_F) if wl.shared_F else "",
             wl.skew), "seed": wl.seed(), "n_bins": layer.n_bins, "q_tokens": layer.q_tokens,
+            "hidden_activations": "f16" if wl.dtype == "bf16" else "f32",
             "active_experts": active, "max_expert_rows": int(counts.max()), "min_expert_rows": int(counts.min())},
         "ffn_tflops": round(ffn_tflops, 1), "ffn_mfma_frac": round(ffn_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "layer_tflops": round(flops / (ms * 1e-3) / 1e12, 1),

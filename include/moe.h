@@ -178,6 +178,18 @@ MOE_API int moe_plan_tiles_subset(const int32_t* counts, const int32_t* offsets,
 MOE_API int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int N, moe_dtype dt,
                      void* out, void* stream);
 
+/* The same layout for the second matrix of an expert (W2 / W_down: F inputs, d outputs, section
+ * 4.4), in the number format the second product of moe_grouped_ffn reads:
+ *
+ *   w   [n, F, d] dt
+ *   out [n, d, F]   MOE_F32: fp32 as given.  MOE_BF16: every value converted to IEEE half
+ *        (binary16, nearest-even).  That is exact for bf16 values of magnitude 2^-14 .. 65504;
+ *        smaller ones are rounded to the half subnormals (absolute error <= 2^-25), larger ones
+ *        become infinite.  The kernels keep the hidden activations in half as well (see
+ *        moe_grouped_ffn).
+ */
+MOE_API int moe_pack_w_out(const void* w, int n, int F, int d, moe_dtype dt, void* out, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Step 5, expert processing (Alg. 1 "experts(S, x')"; section 2: two dense layers with an
  * activation between; section 4.4: no biases).  For every row r of expert e
@@ -191,13 +203,17 @@ MOE_API int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int
  *   x_perm [A,d] dt
  *   w_in  : device array of E device pointers; w_in[e] = packed [F,d] (ReLU) or [2F,d] (SwiGLU,
  *           gate/up interleaved by moe_pack_weights)
- *   w_out : device array of E device pointers; w_out[e] = packed [d,F]
+ *   w_out : device array of E device pointers; w_out[e] = packed [d,F] from moe_pack_w_out
  *   tiles, plan_hdr : from moe_plan_tiles with the same E and A; tile_m as given to the plan:
  *           moe_ffn_tile_m(dt), or for bf16 128 or 256 (moe_ffn_pick_tile_m)
- *   h_scratch [A,F] dt : hidden activations (written, then read)
+ *   h_scratch [A,F] : hidden activations (written, then read); fp32 for MOE_F32, 2 bytes per
+ *           value for MOE_BF16
  *   y_perm    [A,d] fp32 out
- * Requires d % 64 == 0 and F % 64 == 0 for MOE_BF16 (d % 4, F % 4 for MOE_F32); MOE_BF16
- * accumulates in fp32 and rounds the hidden activations to bf16 once.
+ * Requires d % 64 == 0 and F % 64 == 0 for MOE_BF16 (d % 4, F % 4 for MOE_F32).  MOE_BF16
+ * accumulates both products in fp32 and rounds the hidden activations once, to IEEE half: 11
+ * significant bits, so the result is within about 1e-3 of the output's RMS of the exact one
+ * (bf16 activations would be eight times coarser); a hidden activation beyond +-65504 becomes
+ * infinite and shows as inf/NaN in y_perm.
  */
 MOE_API int moe_ffn_tile_m(moe_dtype dt);
 /* bf16 has two tile heights, 128 and 256 rows; this picks one from the mean rows per expert

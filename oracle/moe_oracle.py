@@ -138,12 +138,12 @@ def silu(z: np.ndarray) -> np.ndarray:
 
 
 def expert_ffn(x_rows: np.ndarray, weights: Dict[str, np.ndarray], act: str,
-               h_bf16: bool = False) -> np.ndarray:
+               h_round: Optional[str] = None) -> np.ndarray:
     """One expert on a block of rows, float64 (section 4.4: x W1 W2, activation between).
     act="relu":   y = max(0, x W1) W2           weights: W1 [d,F], W2 [F,d]
     act="swiglu": y = (silu(x Wg) * (x Wu)) Wd  weights: Wg, Wu [d,F], Wd [F,d]
-    h_bf16=True rounds the hidden activations to bfloat16 before the second product; that is a
-    diagnostic that mimics a bf16 intermediate, not the definition."""
+    h_round="bf16" / "f16" rounds the hidden activations to bfloat16 / IEEE half before the second
+    product; that is a diagnostic that mimics a 16-bit intermediate, not the definition."""
     x = to_f64(x_rows)
     if act == "relu":
         h = np.maximum(x @ to_f64(weights["W1"]), 0.0)
@@ -153,8 +153,12 @@ def expert_ffn(x_rows: np.ndarray, weights: Dict[str, np.ndarray], act: str,
         w_out = weights["Wd"]
     else:
         raise ValueError(act)
-    if h_bf16:
+    if h_round == "bf16":
         h = round_to_bf16(h)
+    elif h_round == "f16":
+        h = h.astype(np.float16).astype(np.float64)      # numpy rounds float64 -> half directly, ties to even
+    elif h_round is not None:
+        raise ValueError(h_round)
     return h @ to_f64(w_out)
 
 
@@ -165,7 +169,7 @@ def _expert_slice(weights: Dict[str, np.ndarray], e: int) -> Dict[str, np.ndarra
 def moe_layer(x: np.ndarray, expert_idx: np.ndarray, gate_w: np.ndarray,
               weights: Dict[str, np.ndarray], act: str,
               shared: Optional[Dict[str, np.ndarray]] = None,
-              tokens: Optional[Sequence[int]] = None, h_bf16: bool = False) -> np.ndarray:
+              tokens: Optional[Sequence[int]] = None, h_round: Optional[str] = None) -> np.ndarray:
     """y[t] = sum_{j<k} gate_w[t,j] * FFN_{idx[t,j]}(x[t])  (+ FFN_shared(x[t])),  float64.
 
     `weights` holds stacked per-expert matrices ([E, ...]).  `tokens` restricts the computation
@@ -185,14 +189,14 @@ def moe_layer(x: np.ndarray, expert_idx: np.ndarray, gate_w: np.ndarray,
             rows = np.nonzero(idx_s[:, j] == e)[0]
             if rows.size == 0:
                 continue
-            y[rows] += w_s[rows, j, None] * expert_ffn(xs[rows], _expert_slice(weights, e), act, h_bf16)
+            y[rows] += w_s[rows, j, None] * expert_ffn(xs[rows], _expert_slice(weights, e), act, h_round)
     if shared is not None:
-        y += expert_ffn(xs, shared, "swiglu", h_bf16)
+        y += expert_ffn(xs, shared, "swiglu", h_round)
     return y
 
 
 def grouped_ffn(x_perm: np.ndarray, offsets: np.ndarray, weights: Dict[str, np.ndarray],
-                act: str, h_bf16: bool = False) -> np.ndarray:
+                act: str, h_round: Optional[str] = None) -> np.ndarray:
     """Expert FFN on rows already grouped by expert: rows [offsets[e], offsets[e+1]) go through
     expert e.  Used to check the grouped-FFN stage on its own."""
     off = np.asarray(offsets, dtype=np.int64)
@@ -200,7 +204,7 @@ def grouped_ffn(x_perm: np.ndarray, offsets: np.ndarray, weights: Dict[str, np.n
     y = np.zeros((x_perm.shape[0], d_out), dtype=np.float64)
     for e in range(off.shape[0] - 1):
         if off[e + 1] > off[e]:
-            y[off[e]:off[e + 1]] = expert_ffn(x_perm[off[e]:off[e + 1]], _expert_slice(weights, e), act, h_bf16)
+            y[off[e]:off[e + 1]] = expert_ffn(x_perm[off[e]:off[e + 1]], _expert_slice(weights, e), act, h_round)
     return y
 
 

@@ -28,7 +28,7 @@ MOE_PLAN_HDR_INTS = 4 + 2 * (MOE_MAX_BINS + 1)
 MOE_OP_PERMUTE = 1
 
 EXPORTS = [
-    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_pack_weights",
+    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_pack_weights", "moe_pack_w_out",
     "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_unpermute_combine", "moe_prefetch_create",
     "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_reset", "moe_prefetch_destroy",
     "moe_token_threshold", "moe_workspace_bytes", "moe_copy_bytes", "moe_last_error", "moe_version",
@@ -43,6 +43,7 @@ lib.moe_plan_capacity.argtypes = [_i, _i, _i, _i]
 lib.moe_plan_tiles.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp]
 lib.moe_plan_tiles_subset.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), _i, _vp, _i, _vp, _vp, _vp]
 lib.moe_pack_weights.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp]
+lib.moe_pack_w_out.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp]
 lib.moe_ffn_tile_m.argtypes = [_i]
 lib.moe_ffn_pick_tile_m.argtypes = [_i, _i, _i]
 lib.moe_grouped_ffn.argtypes = [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp]
@@ -163,6 +164,10 @@ def moe_plan_tiles_subset(counts, offsets, E, A, tile_m, n_bins, q_tokens, polic
 
 def moe_pack_weights(w_a, w_b, n, K, N, dt, out, stream=None):
     _check(lib.moe_pack_weights(_p(w_a), _p(w_b), n, K, N, dt, _p(out), _stream(stream)))
+
+
+def moe_pack_w_out(w, n, F, d, dt, out, stream=None):
+    _check(lib.moe_pack_w_out(_p(w), n, F, d, dt, _p(out), _stream(stream)))
 
 
 def moe_grouped_ffn(x_perm, A, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, y_perm,

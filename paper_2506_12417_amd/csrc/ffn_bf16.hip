@@ -1,7 +1,15 @@
-// Grouped bf16 GEMM on the matrix cores: one of the two products of an expert FFN
+// Grouped 16-bit GEMM on the matrix cores: one of the two products of an expert FFN
 // (section 4.4: x W1 W2) over rows grouped by expert, driven by the tile table.
 //
 //   out[r, n] = epilogue( sum_k a[r, k] * w_e[n, k] )      r in a tile of expert e
+//
+// The first product multiplies bf16 by bf16 and stores the hidden activations H as IEEE half:
+// H is the only value the path rounds between its input and its fp32 output, and half keeps 11
+// significant bits of it where bf16 keeps 8 (the error of y falls eightfold; it is otherwise
+// the largest one, several per cent of the output's RMS for the tokens with the largest gate
+// values).  The second product multiplies half by half: moe_pack_w_out has converted W_out,
+// which is exact for every bf16 weight of magnitude 2^-14 .. 65504.  Both matrix instructions
+// run at the same rate and accumulate in fp32.
 //
 // Persistent launch, one work-group of 8 wavefronts (2 per SIMD) per CU.  Work-group b serves
 // bin b % n_bins: work-groups are dealt round-robin to the 8 XCDs, so a bin's tiles -- and with
@@ -40,7 +48,8 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 typedef __attribute__((address_space(3))) void lds_void_t;
 
@@ -99,6 +108,9 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                                                void* __restrict__ out, int ld_out) {
     using C = Cfg<BM, BN, BK, RING, WM, WN, CS>;
     constexpr int MI = C::MI, NI = C::NI, KS = C::KS, PH = C::PH;
+    // The first product takes bf16 operands and writes the hidden activations as IEEE half; the
+    // second one (plain store of fp32 results) takes those and a half copy of the weights.
+    constexpr bool HALF_IN = EPI == MOE_EPI_STORE;
     extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = sgpr(tid >> 6);
@@ -240,7 +252,12 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                 if (decltype(full)::value || mi < mi_on) {
 #pragma unroll
                     for (int ni = 0; ni < NI; ++ni)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][mi], bf[s][ni], acc[mi][ni], 0, 0, 0);
+                        if constexpr (HALF_IN)
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, af[s][mi]),
+                                                                                 __builtin_bit_cast(f16x8, bf[s][ni]),
+                                                                                 acc[mi][ni], 0, 0, 0);
+                        else
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][mi], bf[s][ni], acc[mi][ni], 0, 0, 0);
                 }
             }
     };
@@ -265,7 +282,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // 32x32 block.  Neighbouring lanes (columns c, c+1) swap one value of each register pair
     // (rows rho, rho+1): the even lane then holds columns c, c+1 of row rho, the odd lane the
     // same columns of row rho+1, so every lane stores two adjacent outputs at once (one packed
-    // bf16 pair, or two floats) and the number of store instructions halves.  Stores go through
+    // half pair, or two floats) and the number of store instructions halves.  Stores go through
     // a descriptor that ends with the tile's last row (the row part of a store's address is
     // range-checked only in the per-lane offset).
     constexpr int ES = EPI == MOE_EPI_STORE ? 4 : 2;
@@ -285,7 +302,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             __builtin_amdgcn_raw_buffer_store_b64(v, ro, voff, soff, 0);
         } else {
             const f32x2 f = {lo, hi};
-            const bf16x2 b = __builtin_convertvector(f, bf16x2);          // v_cvt_pk_bf16_f32: nearest-even
+            const f16x2 b = __builtin_convertvector(f, f16x2);            // nearest-even; beyond +-65504: infinity
             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, b), ro, voff, soff, 0);
         }
     };

@@ -1,10 +1,18 @@
 // moe_pack_weights: the paper's W (K inputs x N outputs, section 4.4) rewritten output-major
 // (N x K, contraction index contiguous), optionally with a second matrix interleaved in blocks
 // of 32 output rows (SwiGLU gate / up).  A 32x32 LDS transpose; done once, outside the hot path.
+// moe_pack_w_out: the same for W_out, whose bf16 values become IEEE half on the way (the second
+// product of the FFN multiplies half by half).
 #include "common.h"
 
 namespace {
-template <typename T>
+// bf16 bits -> IEEE half bits, nearest-even (exact for magnitudes 2^-14 .. 65504: half carries
+// more significant bits than bf16; smaller values land on the half subnormals, spacing 2^-24)
+__device__ __forceinline__ uint16_t bf16_to_half(uint16_t b) {
+    const _Float16 h = (_Float16)__uint_as_float((uint32_t)b << 16);
+    return __builtin_bit_cast(uint16_t, h);
+}
+template <typename T, bool TO_HALF = false>
 __global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ wa, const T* __restrict__ wb, int K, int N,
                                                    T* __restrict__ out) {
     __shared__ T tile[32][33];
@@ -21,7 +29,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const T* __restrict__ wa, con
         const int n = n0 + r;
         if (n < N && k0 + tx < K) {
             const int prow = wb ? (n / 32) * 64 + which * 32 + (n % 32) : n;
-            dst[(size_t)prow * K + k0 + tx] = tile[tx][r];
+            if constexpr (TO_HALF) dst[(size_t)prow * K + k0 + tx] = bf16_to_half(tile[tx][r]);
+            else dst[(size_t)prow * K + k0 + tx] = tile[tx][r];
         }
     }
 }
@@ -39,8 +48,8 @@ __global__ __launch_bounds__(256) void router_norm_kernel(const T* __restrict__ 
 }
 }  // namespace
 
-extern "C" int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int N, moe_dtype dt, void* out,
-                                void* stream) {
+static int pack_impl(bool w_out, const void* w_a, const void* w_b, int n, int K, int N, moe_dtype dt, void* out,
+                     void* stream) {
     MOE_REQUIRE(moe_dtype_ok(dt), MOE_ERR_UNSUPPORTED, "moe_pack_weights: dtype %d", (int)dt);
     MOE_REQUIRE(n >= 0 && K >= 1 && N >= 1, MOE_ERR_ARG, "moe_pack_weights: n=%d K=%d N=%d", n, K, N);
     MOE_REQUIRE(!w_b || N % 32 == 0, MOE_ERR_UNSUPPORTED, "moe_pack_weights: interleaving needs N %% 32 == 0 (N=%d)", N);
@@ -49,7 +58,10 @@ extern "C" int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, 
     MOE_REQUIRE((long long)n * (w_b ? 2 : 1) <= 65535, MOE_ERR_UNSUPPORTED, "moe_pack_weights: too many matrices");
     dim3 grid((N + 31) / 32, (K + 31) / 32, n * (w_b ? 2 : 1));
     MOE_REQUIRE(grid.y <= 65535, MOE_ERR_UNSUPPORTED, "moe_pack_weights: K too large");
-    if (dt == MOE_BF16)
+    if (dt == MOE_BF16 && w_out)
+        hipLaunchKernelGGL((pack_kernel<uint16_t, true>), grid, dim3(256), 0, (hipStream_t)stream, (const uint16_t*)w_a,
+                           (const uint16_t*)w_b, K, N, (uint16_t*)out);
+    else if (dt == MOE_BF16)
         hipLaunchKernelGGL(pack_kernel<uint16_t>, grid, dim3(256), 0, (hipStream_t)stream, (const uint16_t*)w_a,
                            (const uint16_t*)w_b, K, N, (uint16_t*)out);
     else
@@ -57,6 +69,15 @@ extern "C" int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, 
                            (const float*)w_b, K, N, (float*)out);
     MOE_CHECK_LAUNCH("moe_pack_weights");
     return MOE_OK;
+}
+
+extern "C" int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int N, moe_dtype dt, void* out,
+                                void* stream) {
+    return pack_impl(false, w_a, w_b, n, K, N, dt, out, stream);
+}
+
+extern "C" int moe_pack_w_out(const void* w, int n, int F, int d, moe_dtype dt, void* out, void* stream) {
+    return pack_impl(true, w, nullptr, n, F, d, dt, out, stream);
 }
 
 extern "C" int moe_pack_router(const void* w_gate, int d, int E, moe_dtype dt, void* w_gate_t, float* w_norm2,

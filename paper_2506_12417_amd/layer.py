@@ -61,7 +61,7 @@ class ExpertGroup:
         else:
             a, o = to_device(w["W1"], dev), to_device(w["W2"], dev)
             B.moe_pack_weights(a, None, 1, self.d, self.F, self.dt, self.w_in[e], stream)
-        B.moe_pack_weights(o, None, 1, self.F, self.d, self.dt, self.w_out[e], stream)
+        B.moe_pack_w_out(o, 1, self.F, self.d, self.dt, self.w_out[e], stream)
         torch.cuda.synchronize(dev)   # the staging tensors above may be freed now
 
 

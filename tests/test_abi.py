@@ -141,6 +141,10 @@ def test_pack_combine_copy_argument_errors():
     assert status(B.moe_pack_weights, FAKE, FAKE, 1, 8, 48, B.MOE_F32, FAKE, 0) == B.MOE_ERR_UNSUPPORTED   # N % 32
     assert status(B.moe_pack_weights, None, None, 1, 8, 8, B.MOE_F32, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_pack_weights, None, None, 0, 8, 8, B.MOE_F32, None, 0) == B.MOE_OK
+    assert status(B.moe_pack_w_out, FAKE, 1, 0, 8, B.MOE_BF16, FAKE, 0) == B.MOE_ERR_ARG
+    assert status(B.moe_pack_w_out, None, 1, 8, 8, B.MOE_BF16, FAKE, 0) == B.MOE_ERR_ARG
+    assert status(B.moe_pack_w_out, FAKE, 1, 8, 8, 7, FAKE, 0) == B.MOE_ERR_UNSUPPORTED
+    assert status(B.moe_pack_w_out, None, 0, 8, 8, B.MOE_BF16, None, 0) == B.MOE_OK
     assert status(B.moe_unpermute_combine, FAKE, FAKE, None, None, 4, 30, 1, FAKE, 0) == B.MOE_ERR_UNSUPPORTED
     assert status(B.moe_unpermute_combine, FAKE, None, None, None, 4, 32, 1, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_unpermute_combine, FAKE, FAKE, None, None, 4, 32, 0, FAKE, 0) == B.MOE_ERR_ARG

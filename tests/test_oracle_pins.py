@@ -226,14 +226,20 @@ def test_ffn_brute_force_triple_loop():
         assert np.allclose(O.expert_ffn(x, w, act), ref, atol=1e-13)
 
 
-def test_ffn_relu_power_of_two_homogeneity_and_bf16_mode():
+def test_ffn_relu_power_of_two_homogeneity_and_rounded_hidden_modes():
     r = np.random.default_rng(2)
     x = r.standard_normal((7, 8))
     w = {"W1": r.standard_normal((8, 16)), "W2": r.standard_normal((16, 8))}
     assert np.array_equal(O.expert_ffn(2 * x, w, "relu"), 2 * O.expert_ffn(x, w, "relu"))
-    a, b = O.expert_ffn(x, w, "relu"), O.expert_ffn(x, w, "relu", h_bf16=True)
+    a, b = O.expert_ffn(x, w, "relu"), O.expert_ffn(x, w, "relu", h_round="bf16")
+    c = O.expert_ffn(x, w, "relu", h_round="f16")
     rms = np.sqrt(np.mean(a ** 2))
     assert 0 < np.abs(a - b).max() < 2e-2 * rms          # differs, by about bf16 rounding of h
+    assert 0 < np.abs(a - c).max() < 2e-2 / 8 * rms      # half keeps three more bits
+    # hidden activations that half holds exactly leave the result untouched
+    xi = r.integers(-4, 5, (7, 8)).astype(np.float64)
+    wi = {"W1": r.integers(-3, 4, (8, 16)).astype(np.float64), "W2": w["W2"]}
+    assert np.array_equal(O.expert_ffn(xi, wi, "relu"), O.expert_ffn(xi, wi, "relu", h_round="f16"))
 
 
 # ------------------------------------------------------------------------------------ layer
