@@ -191,24 +191,37 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         l_ra = make_rsrc(a_mat + (size_t)t.row_begin * K, (unsigned)(rc > 0 ? rc : 0) * (unsigned)K * 2u);
         l_rb = make_rsrc(wmat + (size_t)n0 * K, (unsigned)nr * (unsigned)K * 2u);
     };
-    auto issue = [&]() {
+    // load q of a stage (the A passes first, then the B passes), and the bookkeeping once all are out
+    auto issue_load = [&](int q) {
         unsigned char* st = ring + l_buf * C::STAGE_BYTES + wave * 1024;
         const unsigned k_off = (unsigned)l_kt * (BK * 2);
-#pragma unroll
-        for (int i = 0; i < C::NA; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(l_ra, (lds_void_t*)(st + i * (C::NW * 1024)), 16, ld_voff[i],
-                                                     k_off, 0, 0);
-#pragma unroll
-        for (int i = 0; i < C::NB; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(l_rb, (lds_void_t*)(st + C::A_BYTES + i * (C::NW * 1024)), 16,
-                                                     ld_voff[i], k_off, 0, 0);
+        if (q < C::NA)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(l_ra, (lds_void_t*)(st + q * (C::NW * 1024)), 16, ld_voff[q], k_off, 0, 0);
+        else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(l_rb, (lds_void_t*)(st + C::A_BYTES + (q - C::NA) * (C::NW * 1024)), 16,
+                                                     ld_voff[q - C::NA], k_off, 0, 0);
+    };
+    auto issue_done = [&]() {
         ++issued;
         l_buf = l_buf + 1 == RING ? 0 : l_buf + 1;
         if (++l_kt == KT) {
             l_kt = 0;
             l_item += stride;
-            if (l_item < n_items) load_item(l_item);
+            if (l_item < n_items) {
+                load_item(l_item);
+            } else {
+                // Past the last item the loads go on with empty descriptors: nothing is fetched, the
+                // free ring buffer receives zeros, and the schedule and the count of outstanding
+                // loads stay those of the steady state (no second copy of the loop without loads).
+                l_ra = make_rsrc(a_mat, 0u);
+                l_rb = l_ra;
+            }
         }
+    };
+    auto issue = [&]() {
+#pragma unroll
+        for (int q = 0; q < C::LPS; ++q) issue_load(q);
+        issue_done();
     };
 
     // ---- operand fragment reads.  Row r of a 32-row block is read by lanes r and r + 32 (the
@@ -232,17 +245,28 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
     };
-    // fragments of chunk h (slices h*CS ...) of the stage in buffer buf
-    auto read_chunk = [&](int buf, int h) {
+    // Memory phase of chunk h: the fragments of the slices h*CS ... of the stage in buffer buf go to
+    // registers; the first chunk also issues the next stage's global -> LDS loads.  A load occupies
+    // the issuing wavefront until the texture path accepts it (some tens of cycles each when four
+    // wavefronts issue at once), the LDS reads do not: the loads are spread between the reads so
+    // that the two kinds of waiting overlap instead of adding up.
+    auto mem_phase = [&](int buf, int h) {
+        constexpr int NR = CS * (NI + MI), NL = C::LPS, STEP = NR / NL;
+        static_assert(STEP >= 1, "more loads than reads in a chunk");
         const unsigned char* st = ring + buf * C::STAGE_BYTES;
 #pragma unroll
-        for (int s = 0; s < CS; ++s) {
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) bf[s][ni] = *(const bf16x8*)(st + b_rd[h * CS + s] + ni * 32 * C::ROW_BYTES);
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                af[s][mi] = *(const bf16x8*)(st + a_rd[h * CS + s] + mi * (C::WM * 32) * C::ROW_BYTES);
+        for (int j = 0; j < NR; ++j) {
+            if (h == 0 && j % STEP == 0 && j / STEP < NL) {
+                issue_load(j / STEP);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const int s = j / (NI + MI), idx = j % (NI + MI);
+            if (idx < NI)
+                bf[s][idx] = *(const bf16x8*)(st + b_rd[h * CS + s] + idx * 32 * C::ROW_BYTES);
+            else
+                af[s][idx - NI] = *(const bf16x8*)(st + a_rd[h * CS + s] + (idx - NI) * (C::WM * 32) * C::ROW_BYTES);
         }
+        if (h == 0) issue_done();
     };
     auto mfma_chunk = [&](auto full, int mi_on) {
 #pragma unroll
@@ -261,7 +285,8 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                 }
             }
     };
-    // stage g+1 has landed once only the stages issued after it are outstanding
+    // Stage g+1 has landed once only the stages issued after it are outstanding.  (Loads
+    // complete in issue order; stores that are still in flight only make the wait longer.)
     auto wait_stage_after = [&](int g) {
         if (g + 1 >= total) return;
         const int younger = issued - g - 2;
@@ -351,8 +376,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // ---- prologue: RING-1 stages on their way, the first one landed
     load_item(first);
 #pragma unroll
-    for (int s = 0; s < RING - 1; ++s)
-        if (issued < total) issue();
+    for (int s = 0; s < RING - 1; ++s) issue();
     {
         const int younger = issued - 1;
         if (RING >= 4 && younger >= 2) MOE_WAIT_VMCNT(2 * C::LPS);
@@ -394,8 +418,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                     epilogue(p_ro, p_mi_on, p_n0);
                     zero_acc();
                 }
-                if (h == 0 && issued < total) issue();
-                read_chunk(c_buf, h);
+                mem_phase(c_buf, h);
                 if (store_now && EARLY) {
                     wait_stage_after(g);
                     epilogue(p_ro, p_mi_on, p_n0);
@@ -405,8 +428,11 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                 if (grp == 1 && h == PH - 1 && !waited) wait_stage_after(g);
                 MOE_WAIT_LGKMCNT(0);
                 phase_barrier();
-                // ---- multiply phase
+                // ---- multiply phase (at raised priority: the matrix instructions go first when the
+                // other wavefront of the SIMD, in its memory phase, wants to issue in the same cycle)
+                __builtin_amdgcn_s_setprio(1);
                 mfma_chunk(full, mi_on);
+                __builtin_amdgcn_s_setprio(0);
                 if (grp == 0 && h == PH - 1 && !waited) wait_stage_after(g);
                 if (!(grp == 1 && g + 1 == total && h == PH - 1)) phase_barrier();
             }
@@ -426,6 +452,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         p_n0 = n0;
     }
     epilogue(p_ro, p_mi_on, p_n0);
+    MOE_WAIT_VMCNT(0);                                      // (the trailing empty loads still target this LDS)
 }
 
 template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS>

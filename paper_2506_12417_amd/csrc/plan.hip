@@ -7,6 +7,7 @@
 // 20-30 % of its layer time (section 5.3.1); here it is a few microseconds on the device.
 #include "common.h"
 #include <climits>
+#include <type_traits>
 
 namespace {
 
@@ -42,25 +43,30 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
                                                    int G, int q, int policy, ExpertMask mask,
                                                    moe_tile* __restrict__ tiles, int capacity,
                                                    int32_t* __restrict__ hdr, int32_t* __restrict__ sched) {
-    __shared__ int cnt[MOE_MAX_EXPERTS], cost[MOE_MAX_EXPERTS], order[MOE_MAX_EXPERTS];
-    __shared__ int S_[MOE_MAX_EXPERTS * MOE_MAX_BINS];
+    __shared__ int cnt[MOE_MAX_EXPERTS], order[MOE_MAX_EXPERTS], row0[MOE_MAX_EXPERTS];
+    __shared__ __attribute__((aligned(16))) int cost[MOE_MAX_EXPERTS + 4];
+    // (not volatile: volatile accesses are compiled to flat instructions that are waited for one by
+    // one; where lanes of the serial wavefront exchange values through S a wavefront fence orders them)
+    __shared__ int S[MOE_MAX_EXPERTS * MOE_MAX_BINS];
     // non-empty (expert, bin) blocks, one segment per bin: rows and expert id
     __shared__ int blk_n[MOE_MAX_EXPERTS * MOE_MAX_BINS];
     __shared__ unsigned char blk_e[MOE_MAX_EXPERTS * MOE_MAX_BINS];
+    __shared__ int blk_t[MOE_MAX_EXPERTS * MOE_MAX_BINS];               // tiles of the block
     __shared__ int load[MOE_MAX_BINS], bin_blocks[MOE_MAX_BINS + 1], bin_cursor[MOE_MAX_BINS], bin_tiles[MOE_MAX_BINS + 1];
     __shared__ int s_tavg, s_moves;
-    volatile int* S = S_;
     const int tid = threadIdx.x, lane = tid & 63;
     const bool by_cost = (policy == MOE_PLAN_BALANCED);
     (void)A;
 
-    for (int i = tid; i < E * G; i += NTH) S_[i] = 0;
+    for (int i = tid; i < E * G; i += NTH) S[i] = 0;
     if (tid < G) { load[tid] = 0; bin_blocks[tid] = 0; bin_cursor[tid] = 0; bin_tiles[tid] = 0; }
     if (tid < E) {
         int c = ((mask.w[tid >> 5] >> (tid & 31)) & 1u) ? counts[tid] : 0;    // experts left out count as empty
         cnt[tid] = c;
+        row0[tid] = offsets[tid];                  // (fetched now: a global load at the end would be waited for in full)
         cost[tid] = weight_of(c, q, by_cost);
     }
+    if (tid < 4) cost[E + tid] = -1;
     if (tid == 0) s_moves = 0;
     __syncthreads();
 
@@ -69,38 +75,68 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         if (tid < E) {   // experts by falling weight, equal weights by rising id
             const int c = cost[tid];
             int r = 0;
-#pragma unroll 8
-            for (int e2 = 0; e2 < E; ++e2) {
-                const int c2 = cost[e2];
-                r += (c2 > c || (c2 == c && e2 < tid)) ? 1 : 0;
+            const int4* c4 = (const int4*)cost;                 // (entries past E are never ahead: -1)
+#pragma unroll 4
+            for (int e2 = 0; e2 < E; e2 += 4) {
+                const int4 v = c4[e2 >> 2];
+                r += (v.x > c || (v.x == c && e2 < tid)) ? 1 : 0;
+                r += (v.y > c || (v.y == c && e2 + 1 < tid)) ? 1 : 0;
+                r += (v.z > c || (v.z == c && e2 + 2 < tid)) ? 1 : 0;
+                r += (v.w > c || (v.w == c && e2 + 3 < tid)) ? 1 : 0;
             }
             order[r] = tid;
         }
         __syncthreads();
-        if (tid < 64) {  // each expert whole, on the least loaded bin so far; the list lives in registers
+        if (tid < 64) {
+            // Each expert whole, on the least loaded bin so far.  The loop is serial and a lone
+            // wavefront issues an instruction only every few cycles, so what counts is the number of
+            // instructions per expert.  The bins are a list of keys (load << BIN_BITS | bin) sorted
+            // by rising key in scalar registers: the head is the least loaded bin (the lowest one
+            // among equals); it takes the expert and sinks back to its place by compare-and-swap with
+            // its successors.  Unused entries are all ones and stay at the end.  Lane r % 64 notes
+            // the bin of the r-th expert; the lanes write S afterwards, all at once.
             constexpr int NJ = MOE_MAX_EXPERTS / 64;
-            int ord[NJ], cst[NJ], cn[NJ];
+            int ord[NJ], cst[NJ], cn[NJ], bin_of[NJ];
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 const int r = lane + 64 * j;
                 ord[j] = r < E ? order[r] : 0;
                 cst[j] = r < E ? cost[ord[j]] : 0;
                 cn[j] = r < E ? cnt[ord[j]] : 0;
+                bin_of[j] = -1;
             }
             int tg = 0;
+            auto place = [&](auto max_bins) {
+                constexpr int MB = decltype(max_bins)::value;
+                unsigned key[MB];
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                const int n = E - 64 * j < 64 ? E - 64 * j : 64;
-                for (int r = 0; r < n; ++r) {
-                    const int c = __builtin_amdgcn_readlane(cst[j], r);
-                    if (c == 0) break;
-                    const int e = __builtin_amdgcn_readlane(ord[j], r), rows = __builtin_amdgcn_readlane(cn[j], r);
-                    int g, v;
-                    argmin_bin(tg, lane, G, g, v);
-                    if (lane == 0) S[e * G + g] = rows;
-                    if (lane == g) tg += c;
+                for (int i = 0; i < MB; ++i) key[i] = i < G ? (unsigned)i : 0xffffffffu;
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const int n = E - 64 * j < 64 ? E - 64 * j : 64;
+                    for (int r = 0; r < n; ++r) {
+                        const unsigned c = (unsigned)__builtin_amdgcn_readlane(cst[j], r);
+                        if (c == 0) break;
+                        bin_of[j] = lane == r ? (int)(key[0] & ((1u << BIN_BITS) - 1u)) : bin_of[j];
+                        key[0] += c << BIN_BITS;
+#pragma unroll
+                        for (int i = 0; i + 1 < MB; ++i) {
+                            const unsigned lo = key[i] < key[i + 1] ? key[i] : key[i + 1];
+                            const unsigned hi = key[i] < key[i + 1] ? key[i + 1] : key[i];
+                            key[i] = lo;
+                            key[i + 1] = hi;
+                        }
+                    }
                 }
-            }
+#pragma unroll
+                for (int i = 0; i < MB; ++i)
+                    if (i < G && lane == (int)(key[i] & ((1u << BIN_BITS) - 1u))) tg = (int)(key[i] >> BIN_BITS);
+            };
+            if (G <= 8) place(std::integral_constant<int, 8>{});
+            else place(std::integral_constant<int, MOE_MAX_BINS>{});
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                if (bin_of[j] >= 0) S[ord[j] * G + bin_of[j]] = cn[j];
             if (lane < G) load[lane] = tg;
         }
     } else if (policy == MOE_PLAN_EVEN_SPLIT) {
@@ -161,6 +197,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
                     S[e_max * G + g_max] = n_from - t_s;
                     S[e_max * G + g_min] = n_to + t_s;
                 }
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");   // the next round's lanes read these
                 if (lane == g_max) tg -= d_from;
                 if (lane == g_min) tg += d_to;
                 ++moves;
@@ -173,7 +210,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
 
     // ---- the non-empty blocks of every bin, gathered into per-bin segments (any order)
     for (int p = tid; p < E * G; p += NTH) {
-        const int n = S_[p];
+        const int n = S[p];
         if (sched) sched[p] = n;
         if (n > 0) atomicAdd(&bin_blocks[p % G], 1);
     }
@@ -185,13 +222,15 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     }
     __syncthreads();
     for (int p = tid; p < E * G; p += NTH) {
-        const int n = S_[p];
+        const int n = S[p];
         if (n > 0) {
             const int g = p % G;
             const int at = bin_blocks[g] + atomicAdd(&bin_cursor[g], 1);
+            const int nt = (n + tile_m - 1) / tile_m;
             blk_n[at] = n;
             blk_e[at] = (unsigned char)(p / G);
-            atomicAdd(&bin_tiles[g], (n + tile_m - 1) / tile_m);
+            blk_t[at] = nt;
+            atomicAdd(&bin_tiles[g], nt);
         }
     }
     __syncthreads();
@@ -221,11 +260,11 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         int before = 0;
         for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o) {
             const int n2 = blk_n[o], e2 = blk_e[o];
-            if (n2 > n || (n2 == n && e2 < e)) before += (n2 + tile_m - 1) / tile_m;
+            if (n2 > n || (n2 == n && e2 < e)) before += blk_t[o];
         }
-        int row = offsets[e];
-        for (int g2 = 0; g2 < g; ++g2) row += S_[e * G + g2];
-        const int nt = (n + tile_m - 1) / tile_m;
+        int row = row0[e];
+        for (int g2 = 0; g2 < g; ++g2) row += S[e * G + g2];
+        const int nt = blk_t[b];
         for (int i = 0; i < nt; ++i) {
             const int at = bin_tiles[g] + before + i;
             if (at < capacity) {
