@@ -136,6 +136,7 @@ MOE_API int moe_permute(const void* x, const int32_t* expert_idx, int T, int d, 
  *       [0] n_tiles  [1] n_bins  [2] number of Alg. 2 moves made  [3] t_avg
  *       [4 .. 4+n_bins]  bin_start (n_bins+1 entries; bin g owns tiles [bin_start[g], bin_start[g+1]))
  *       [4+MOE_MAX_BINS+1 .. +n_bins)  load of each bin after rebalancing (in the policy's unit)
+ *       [MOE_PLAN_HDR_CTR .. +MOE_MAX_BINS]  work counters of moe_grouped_ffn, left at zero
  *   sched  [E*n_bins] int32 out, may be NULL: the schedule S, row-major [E, n_bins]
  * Requires 1 <= E <= MOE_MAX_EXPERTS, 1 <= n_bins <= MOE_MAX_BINS, tile_m >= 1, q_tokens >= 1,
  * A + E*q_tokens < 2^26.
@@ -143,7 +144,8 @@ MOE_API int moe_permute(const void* x, const int32_t* expert_idx, int T, int d, 
 typedef struct { int32_t expert, row_begin, row_count, bin; } moe_tile;
 
 enum { MOE_PLAN_BALANCED = 0, MOE_PLAN_HARMOENY = 1, MOE_PLAN_STATIC = 2, MOE_PLAN_EVEN_SPLIT = 3 };
-#define MOE_PLAN_HDR_INTS (4 + 2 * (MOE_MAX_BINS + 1))
+#define MOE_PLAN_HDR_CTR (4 + 2 * (MOE_MAX_BINS + 1))
+#define MOE_PLAN_HDR_INTS (MOE_PLAN_HDR_CTR + MOE_MAX_BINS + 1)
 
 MOE_API int moe_plan_capacity(int A, int E, int tile_m, int n_bins);
 
@@ -205,7 +207,11 @@ MOE_API int moe_pack_w_out(const void* w, int n, int F, int d, moe_dtype dt, voi
  *           gate/up interleaved by moe_pack_weights)
  *   w_out : device array of E device pointers; w_out[e] = packed [d,F] from moe_pack_w_out
  *   tiles, plan_hdr : from moe_plan_tiles with the same E and A; tile_m as given to the plan:
- *           moe_ffn_tile_m(dt), or for bf16 128 or 256 (moe_ffn_pick_tile_m)
+ *           moe_ffn_tile_m(dt), or for bf16 128 or 256 (moe_ffn_pick_tile_m).  The bf16 kernels
+ *           hand the tiles of a bin to its work-groups through the counters at
+ *           plan_hdr[MOE_PLAN_HDR_CTR ...]: they must be zero on entry (moe_plan_tiles leaves
+ *           them so) and are zero again when the call's kernels have finished, so a plan can be
+ *           run any number of times; two calls that use the same plan_hdr must not overlap.
  *   h_scratch [A,F] : hidden activations (written, then read); fp32 for MOE_F32, 2 bytes per
  *           value for MOE_BF16
  *   y_perm    [A,d] fp32 out
@@ -222,7 +228,7 @@ MOE_API int moe_ffn_pick_tile_m(moe_dtype dt, int A, int E);
 
 MOE_API int moe_grouped_ffn(const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,
                     const void* const* w_in, const void* const* w_out,
-                    const moe_tile* tiles, const int32_t* plan_hdr, int tile_m,
+                    const moe_tile* tiles, int32_t* plan_hdr, int tile_m,
                     void* h_scratch, float* y_perm, void* stream);
 
 /* One of the two grouped GEMMs of moe_grouped_ffn on its own (same kernels, same arguments):
@@ -232,7 +238,7 @@ MOE_API int moe_grouped_ffn(const void* x_perm, int A, int d, int F, int E, moe_
  * interleave other work between, the two products of section 4.4's x W1 W2. */
 MOE_API int moe_grouped_ffn_phase(int phase, const void* x_perm, int A, int d, int F, int E, moe_act act,
                                   moe_dtype dt, const void* const* w_in, const void* const* w_out,
-                                  const moe_tile* tiles, const int32_t* plan_hdr, int tile_m,
+                                  const moe_tile* tiles, int32_t* plan_hdr, int tile_m,
                                   void* h_scratch, float* y_perm, void* stream);
 
 /* ------------------------------------------------------------------------------------------

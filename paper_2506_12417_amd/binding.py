@@ -24,7 +24,8 @@ MOE_F32, MOE_BF16 = 0, 1
 MOE_RELU, MOE_SWIGLU = 0, 1
 MOE_PLAN_BALANCED, MOE_PLAN_HARMOENY, MOE_PLAN_STATIC, MOE_PLAN_EVEN_SPLIT = 0, 1, 2, 3
 MOE_MAX_EXPERTS, MOE_MAX_TOPK, MOE_MAX_BINS = 256, 8, 16
-MOE_PLAN_HDR_INTS = 4 + 2 * (MOE_MAX_BINS + 1)
+MOE_PLAN_HDR_CTR = 4 + 2 * (MOE_MAX_BINS + 1)
+MOE_PLAN_HDR_INTS = MOE_PLAN_HDR_CTR + MOE_MAX_BINS + 1
 MOE_OP_PERMUTE = 1
 
 EXPORTS = [

@@ -129,7 +129,7 @@ extern "C" int moe_ffn_pick_tile_m(moe_dtype dt, int A, int E) {
 
 static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,
                             const void* const* w_in, const void* const* w_out, const moe_tile* tiles,
-                            const int32_t* plan_hdr, int tile_m, void* h_scratch, float* y_perm, void* stream) {
+                            int32_t* plan_hdr, int tile_m, void* h_scratch, float* y_perm, void* stream) {
     MOE_REQUIRE(moe_dtype_ok(dt), MOE_ERR_UNSUPPORTED, "moe_grouped_ffn: dtype %d", (int)dt);
     MOE_REQUIRE(act == MOE_RELU || act == MOE_SWIGLU, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn: activation %d", (int)act);
     MOE_REQUIRE(A >= 0 && d >= 1 && F >= 1 && E >= 1, MOE_ERR_ARG, "moe_grouped_ffn: A=%d d=%d F=%d E=%d", A, d, F, E);
@@ -149,11 +149,12 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
     const int n1 = act == MOE_SWIGLU ? 2 * F : F;
     int rc;
     if (dt == MOE_BF16) {
-        // Work items are (tile, column block).  With few of them per CU the last round of a
-        // persistent launch runs half empty, so a GEMM with few column blocks takes narrower
-        // ones.  The number of tiles is known on the device only; this is its expected value.
+        // Work items are (tile, column block), handed to the work-groups as they become free.
+        // Wide column blocks read an activation tile fewer times; only when there would not be
+        // two items per CU does a GEMM take narrower ones.  The number of tiles is known on the
+        // device only; this is its expected value.
         const long long tiles_est = (A + tile_m - 1) / tile_m + E / 2;
-        auto narrow = [&](int N) { return tile_m == 128 && tiles_est * ((N + 255) / 256) < 4 * MOE_GEMM_GRID; };
+        auto narrow = [&](int N) { return tile_m == 128 && tiles_est * ((N + 255) / 256) < 2 * MOE_GEMM_GRID; };
         if (phases & 1) {
             rc = moe_launch_gemm_bf16(act == MOE_SWIGLU ? MOE_EPI_SWIGLU : MOE_EPI_RELU, tile_m, narrow(n1), x_perm, d, n1,
                                       w_in, tiles, plan_hdr, h_scratch, F, st);
@@ -185,13 +186,13 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
 
 extern "C" int moe_grouped_ffn(const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,
                                const void* const* w_in, const void* const* w_out, const moe_tile* tiles,
-                               const int32_t* plan_hdr, int tile_m, void* h_scratch, float* y_perm, void* stream) {
+                               int32_t* plan_hdr, int tile_m, void* h_scratch, float* y_perm, void* stream) {
     return grouped_ffn_impl(3, x_perm, A, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, y_perm, stream);
 }
 
 extern "C" int moe_grouped_ffn_phase(int phase, const void* x_perm, int A, int d, int F, int E, moe_act act,
                                      moe_dtype dt, const void* const* w_in, const void* const* w_out,
-                                     const moe_tile* tiles, const int32_t* plan_hdr, int tile_m, void* h_scratch,
+                                     const moe_tile* tiles, int32_t* plan_hdr, int tile_m, void* h_scratch,
                                      float* y_perm, void* stream) {
     MOE_REQUIRE(phase == 1 || phase == 2, MOE_ERR_ARG, "moe_grouped_ffn_phase: phase %d", phase);
     return grouped_ffn_impl(phase, x_perm, A, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, y_perm, stream);

@@ -73,6 +73,32 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(sgpr_ptr(p)), 0, sgpr((int)bytes), 0x00020000);
 }
 
+// take_ticket: lane 0 adds one to *ctr; the old value arrives some time later, like a load, in
+// register v250.  read_ticket fetches it from there; the caller does so only after a vmcnt wait
+// that covers the request.  Written as assembly with a fixed register, because the compiler would
+// wait for the answer on the spot (draining the whole queue of operand loads in flight), and
+// because a result register it knows of gets copied around before the answer is in it.  This is
+// sound only in kernels whose own code never touches v250: the kernels that use it stay well
+// below 250 registers, and a unit test compiles this file and checks that v250 appears in these
+// two instructions only.
+#define MOE_TICKET_REG "v250"
+__device__ __forceinline__ void take_ticket(int32_t* ctr) {
+    unsigned long long saved;
+    asm volatile(
+        "s_mov_b64 %0, exec\n\t"
+        "s_mov_b64 exec, 1\n\t"
+        "global_atomic_add " MOE_TICKET_REG ", %1, %2, %3 sc0\n\t"
+        "s_mov_b64 exec, %0"
+        : "=&s"(saved)
+        : "v"(0), "v"(1), "s"(ctr)
+        : "memory", MOE_TICKET_REG);
+}
+__device__ __forceinline__ int read_ticket() {
+    int v;
+    asm volatile("v_readfirstlane_b32 %0, " MOE_TICKET_REG : "=s"(v) : : MOE_TICKET_REG);
+    return v;
+}
+
 template <int BM_, int BN_, int BK_, int RING_, int WM_, int WN_, int CS_>
 struct Cfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, RING = RING_, WM = WM_, WN = WN_, CS = CS_;
@@ -90,8 +116,8 @@ struct Cfg {
     static constexpr int KS = BK / 16;                    // 16-wide slices per K-step
     static constexpr int PH = KS / CS;                    // chunks (of CS slices) per K-step
     static constexpr size_t RING_BYTES = (size_t)RING * STAGE_BYTES;
-    static constexpr int MAX_BLK_TILES = 4096;            // tiles of a bin the block table can hold
-    static constexpr size_t SMEM = RING_BYTES + (size_t)MAX_BLK_TILES * 4;
+    static constexpr int MAX_BLK_TILES = 4092;            // tiles of a bin the block table can hold
+    static constexpr size_t SMEM = RING_BYTES + (size_t)MAX_BLK_TILES * 4 + 16;   // + ids[4] of the work hand-out
     static_assert(NA >= 1 && NB >= 1 && A_BYTES % (NTH * 16) == 0 && B_BYTES % (NTH * 16) == 0, "tile vs threads");
     static_assert(ROWS_PER_PASS % (WRAP * PPR) == 0 && 32 % (WRAP * PPR) == 0, "swizzle period");
     static_assert(KS % CS == 0 && NW == 8 && WM == 2, "two groups of four wavefronts, row blocks interleaved");
@@ -104,7 +130,7 @@ struct Cfg {
 template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS>
 __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_mat, int K, int N,
                                                const void* const* __restrict__ w_ptrs,
-                                               const moe_tile* __restrict__ tiles, const int32_t* __restrict__ hdr,
+                                               const moe_tile* __restrict__ tiles, int32_t* __restrict__ hdr,
                                                void* __restrict__ out, int ld_out) {
     using C = Cfg<BM, BN, BK, RING, WM, WN, CS>;
     constexpr int MI = C::MI, NI = C::NI, KS = C::KS, PH = C::PH;
@@ -130,8 +156,34 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     const int bin_start = hdr[4 + bin];
     const int n_tiles = hdr[4 + bin + 1] - bin_start;
     const int n_items = n_tiles * n_col_blocks;
-    if (first >= n_items) return;
-    const int total = ((n_items - first + stride - 1) / stride) * KT;   // K-steps of this work-group
+
+    // ---- who takes which item.  The first round is fixed: work-group j of the bin starts with
+    // item j.  After that an item goes to whichever work-group of the bin asks next (a counter per
+    // bin in the plan header): items differ a lot in duration -- a tile of a cold expert waits for
+    // its weights from HBM, a tile of a hot expert finds them in L2 -- and with a fixed stride the
+    // work-groups of a bin finish far apart.  The counter is read one item ahead by wavefront 0
+    // and handed to the others through LDS (ids[seq % 4]); the answer has a whole item's time to
+    // arrive.  Very short contractions (fewer K-steps per item than the answer needs) keep the
+    // fixed stride.  The last work-group to finish zeroes the counters for the next launch.
+    int32_t* next_ctr = hdr + MOE_PLAN_HDR_CTR + bin;
+    int32_t* done_ctr = hdr + MOE_PLAN_HDR_CTR + MOE_MAX_BINS;
+    // (the 256-row configuration needs every register: it keeps the fixed stride; its items are long
+    // and alike)
+    const bool dyn = RING >= 3 && KT >= 4;
+    int* ids = (int*)(ring + C::SMEM - 16);
+    auto leave = [&]() {                                    // (every work-group of a dynamic launch passes here once)
+        if (dyn && tid == 0) {
+            const int before = __hip_atomic_fetch_add(done_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (before == (int)gridDim.x - 1) {
+                for (int b = 0; b < G; ++b) __hip_atomic_store(hdr + MOE_PLAN_HDR_CTR + b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(done_ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    };
+    if (first >= n_items) {
+        leave();
+        return;
+    }
 
     // ---- item order.  A bin's table lists its blocks (one expert's rows on this bin) one after
     // the other.  Items are taken block after block, column-block-major inside a block: the
@@ -152,8 +204,15 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             while (l + 1 < n_tiles && ((l + 1) & 255) != 0 && ex[l + 1] == e) ++l;
             blk[p] = (uint32_t)f | ((uint32_t)(l - f + 1) << 16);
         }
-        __syncthreads();
     }
+    // the second item of this work-group (nothing is in flight yet: the answer is simply waited for)
+    if (dyn && tid == 0) ids[1] = stride + __hip_atomic_fetch_add(next_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    // id of the seq-th item of this work-group (seq >= 1)
+    auto item_of = [&](int seq, int prev) { return dyn ? sgpr(ids[seq & 3]) : prev + stride; };
+    // Wavefront 0 asks for the id of item `seq`; the answer is passed on by publish() once the
+    // wait of a later K-step has covered it (loads and this request complete in issue order).
+    int f_seq = -1, f_ready = 0;
     // item -> (tile of the bin, column block)
     auto locate = [&](int it, int& tile_idx, int& cb) {
         if (by_block) {
@@ -172,14 +231,12 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // the swizzle does not depend on i, so one per-lane offset serves every load of a stage.
     const int ld_row = tid / C::PPR;
     // The row part of an address must sit in the per-lane offset: only that one is range-checked.
-    constexpr int NPASS = C::NA > C::NB ? C::NA : C::NB;
-    unsigned ld_voff[NPASS];
-#pragma unroll
-    for (int i = 0; i < NPASS; ++i)
-        ld_voff[i] = (unsigned)(ld_row + i * C::ROWS_PER_PASS) * (unsigned)K * 2u +
-                     (unsigned)(((tid % C::PPR) ^ C::swz(ld_row)) << 4);
+    // (pass i of a stage lies a wave-uniform distance further down: one register, one add per load)
+    const unsigned ld_voff0 = (unsigned)ld_row * (unsigned)K * 2u + (unsigned)(((tid % C::PPR) ^ C::swz(ld_row)) << 4);
+    const unsigned ld_pass = (unsigned)sgpr(C::ROWS_PER_PASS * K * 2);
     __amdgpu_buffer_rsrc_t l_ra, l_rb;
-    int l_item = first, l_kt = 0, l_buf = 0, issued = 0;
+    int l_item = first, l_seq = 0, l_kt = 0, l_buf = 0, issued = 0;
+    int g = 0, c_buf = 0;                                   // K-step counter of the stream, its stage
     auto load_item = [&](int it) {
         int cb, ti;
         locate(it, ti, cb);
@@ -196,19 +253,24 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         unsigned char* st = ring + l_buf * C::STAGE_BYTES + wave * 1024;
         const unsigned k_off = (unsigned)l_kt * (BK * 2);
         if (q < C::NA)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(l_ra, (lds_void_t*)(st + q * (C::NW * 1024)), 16, ld_voff[q], k_off, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(l_ra, (lds_void_t*)(st + q * (C::NW * 1024)), 16, ld_voff0 + (unsigned)q * ld_pass, k_off, 0, 0);
         else
             __builtin_amdgcn_raw_ptr_buffer_load_lds(l_rb, (lds_void_t*)(st + C::A_BYTES + (q - C::NA) * (C::NW * 1024)), 16,
-                                                     ld_voff[q - C::NA], k_off, 0, 0);
+                                                     ld_voff0 + (unsigned)(q - C::NA) * ld_pass, k_off, 0, 0);
     };
     auto issue_done = [&]() {
         ++issued;
         l_buf = l_buf + 1 == RING ? 0 : l_buf + 1;
         if (++l_kt == KT) {
             l_kt = 0;
-            l_item += stride;
+            if (l_item < n_items) l_item = item_of(++l_seq, l_item);
             if (l_item < n_items) {
                 load_item(l_item);
+                if (dyn && wave == 0) {
+                    take_ticket(next_ctr);
+                    f_seq = l_seq + 1;
+                    f_ready = g + RING - 2;
+                }
             } else {
                 // Past the last item the loads go on with empty descriptors: nothing is fetched, the
                 // free ring buffer receives zeros, and the schedule and the count of outstanding
@@ -227,14 +289,13 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // ---- operand fragment reads.  Row r of a 32-row block is read by lanes r and r + 32 (the
     // two 8-wide halves of a 16-wide slice); the swizzle depends on r % 32 only.  Row block mi of
     // this wavefront is block mi * WM + wm of the tile.
-    const int sw = C::swz(l32);
-    int a_rd[KS], b_rd[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        const int piece = ((ks * 2 + lhi) ^ sw) << 4;
-        a_rd[ks] = (wm * 32 + l32) * C::ROW_BYTES + piece;
-        b_rd[ks] = C::A_BYTES + (wn * C::WTN + l32) * C::ROW_BYTES + piece;
-    }
+    // Slice ks of a row is piece (2 ks + lhi) ^ swz = (2 ks) ^ (lhi ^ swz), and every row and stage
+    // starts on a multiple of the row size: the address of slice ks is the address of slice 0 with
+    // bits flipped, so one per-lane register (and one XOR per read) serves all slices.  The B rows
+    // of lane l32 sit a wave-uniform distance behind its A rows, with the same swizzle.
+    static_assert(C::STAGE_BYTES % C::ROW_BYTES == 0 && (C::ROW_BYTES & (C::ROW_BYTES - 1)) == 0, "slice addressing");
+    int a_rd0 = (wm * 32 + l32) * C::ROW_BYTES + ((lhi ^ C::swz(l32)) << 4);
+    const int b_delta = sgpr(C::A_BYTES + (wn * C::WTN - wm * 32) * C::ROW_BYTES);
     bf16x8 af[CS][MI], bf[CS][NI];
     f32x16 acc[MI][NI];
     auto zero_acc = [&]() {
@@ -253,7 +314,11 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     auto mem_phase = [&](int buf, int h) {
         constexpr int NR = CS * (NI + MI), NL = C::LPS, STEP = NR / NL;
         static_assert(STEP >= 1, "more loads than reads in a chunk");
-        const unsigned char* st = ring + buf * C::STAGE_BYTES;
+        // (the empty asm keeps the compiler from forming all slice addresses once, outside the loop,
+        // and holding them in registers the 256-row configuration does not have)
+        asm volatile("" : "+v"(a_rd0));
+        const unsigned a_at = (unsigned)(buf * C::STAGE_BYTES) + (unsigned)a_rd0;
+        const unsigned b_at = a_at + (unsigned)b_delta;
 #pragma unroll
         for (int j = 0; j < NR; ++j) {
             if (h == 0 && j % STEP == 0 && j / STEP < NL) {
@@ -262,9 +327,9 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             }
             const int s = j / (NI + MI), idx = j % (NI + MI);
             if (idx < NI)
-                bf[s][idx] = *(const bf16x8*)(st + b_rd[h * CS + s] + idx * 32 * C::ROW_BYTES);
+                bf[s][idx] = *(const bf16x8*)(ring + (b_at ^ (unsigned)((h * CS + s) << 5)) + idx * 32 * C::ROW_BYTES);
             else
-                af[s][idx - NI] = *(const bf16x8*)(st + a_rd[h * CS + s] + (idx - NI) * (C::WM * 32) * C::ROW_BYTES);
+                af[s][idx - NI] = *(const bf16x8*)(ring + (a_at ^ (unsigned)((h * CS + s) << 5)) + (idx - NI) * (C::WM * 32) * C::ROW_BYTES);
         }
         if (h == 0) issue_done();
     };
@@ -288,11 +353,19 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // Stage g+1 has landed once only the stages issued after it are outstanding.  (Loads
     // complete in issue order; stores that are still in flight only make the wait longer.)
     auto wait_stage_after = [&](int g) {
-        if (g + 1 >= total) return;
         const int younger = issued - g - 2;
         if (RING >= 4 && younger >= 2) MOE_WAIT_VMCNT(2 * C::LPS);
         else if (RING >= 3 && younger >= 1) MOE_WAIT_VMCNT(C::LPS);
         else MOE_WAIT_VMCNT(0);
+    };
+    // (wavefront 0, after its wait of a K-step)
+    auto publish = [&]() {
+        if (dyn && wave == 0 && f_seq >= 0 && g >= f_ready) {
+            const int id = stride + read_ticket();
+            if (lane == 0) ids[f_seq & 3] = id;
+            f_seq = -1;
+            MOE_WAIT_LGKMCNT(0);
+        }
     };
     // (nothing may move across a phase boundary: neither memory operations nor matrix-core work)
     auto phase_barrier = [&]() {
@@ -387,10 +460,10 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     zero_acc();
     if (grp == 1) phase_barrier();                          // group 1 starts one phase late
 
-    int g = 0, c_buf = 0;                                   // K-step counter of the stream, its stage
     __amdgpu_buffer_rsrc_t p_ro = make_rsrc(out, 0u);       // the previous item, stored in the next one's first phase
     int p_mi_on = 0, p_n0 = 0;
-    for (int item = first; item < n_items; item += stride) {
+    int item = first, c_seq = 0;
+    while (item < n_items) {
         int cb, ti;
         locate(item, ti, cb);
         const moe_tile tile = tiles[bin_start + ti];
@@ -403,7 +476,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             make_rsrc((const unsigned char*)out + (size_t)tile.row_begin * ld_bytes, (unsigned)(rc > 0 ? rc : 0) * ld_bytes);
 
         // One K-step of this wavefront: per chunk a memory phase and a multiply phase.
-        auto k_step = [&](auto full, bool first_of_item) {
+        auto k_step = [&](auto full, bool first_of_item, bool last_of_all) {
 #pragma unroll
             for (int h = 0; h < PH; ++h) {
                 // ---- memory phase: stage g's buffer is complete; the buffer of stage g-1 has been
@@ -421,6 +494,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                 mem_phase(c_buf, h);
                 if (store_now && EARLY) {
                     wait_stage_after(g);
+                    publish();
                     epilogue(p_ro, p_mi_on, p_n0);
                     zero_acc();
                 }
@@ -433,25 +507,40 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                 __builtin_amdgcn_s_setprio(1);
                 mfma_chunk(full, mi_on);
                 __builtin_amdgcn_s_setprio(0);
-                if (grp == 0 && h == PH - 1 && !waited) wait_stage_after(g);
-                if (!(grp == 1 && g + 1 == total && h == PH - 1)) phase_barrier();
+                if (grp == 0 && h == PH - 1 && !waited) {
+                    wait_stage_after(g);
+                    publish();
+                }
+                if (!(grp == 1 && last_of_all && h == PH - 1)) phase_barrier();
             }
             ++g;
             c_buf = c_buf + 1 == RING ? 0 : c_buf + 1;
         };
 
-        if (mi_on == MI) {
-            k_step(std::true_type{}, true);
-            for (int kt = 1; kt < KT; ++kt) k_step(std::true_type{}, false);
-        } else {
-            k_step(std::false_type{}, true);
-            for (int kt = 1; kt < KT; ++kt) k_step(std::false_type{}, false);
-        }
+        // The id of the next item is known by this item's last K-step: the loader needed it
+        // RING-1 K-steps ago.  (With one K-step per item there is no handing out: fixed stride.)
+        int next = item + stride;
+        auto run_item = [&](auto full) {
+            k_step(full, true, KT == 1 && next >= n_items);
+            for (int kt = 1; kt < KT; ++kt) {
+                bool last = false;
+                if (kt == KT - 1) {
+                    next = item_of(c_seq + 1, item);
+                    last = next >= n_items;
+                }
+                k_step(full, false, last);
+            }
+        };
+        if (mi_on == MI) run_item(std::true_type{});
+        else run_item(std::false_type{});
         p_ro = ro;
         p_mi_on = mi_on;
         p_n0 = n0;
+        item = next;
+        ++c_seq;
     }
     epilogue(p_ro, p_mi_on, p_n0);
+    leave();
     MOE_WAIT_VMCNT(0);                                      // (the trailing empty loads still target this LDS)
 }
 
@@ -459,13 +548,13 @@ template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(const uint16_t* __restrict__ a_mat, int K, int N,
                                                                   const void* const* __restrict__ w_ptrs,
                                                                   const moe_tile* __restrict__ tiles,
-                                                                  const int32_t* __restrict__ hdr, void* __restrict__ out,
+                                                                  int32_t* __restrict__ hdr, void* __restrict__ out,
                                                                   int ld_out) {
     gemm_bf16_body<EPI, BM, BN, BK, RING, WM, WN, CS>(a_mat, K, N, w_ptrs, tiles, hdr, out, ld_out);
 }
 
 template <int EPI, class C>
-int launch(const void* a, int K, int N, const void* const* w, const moe_tile* tiles, const int32_t* hdr, void* out,
+int launch(const void* a, int K, int N, const void* const* w, const moe_tile* tiles, int32_t* hdr, void* out,
            int ld_out, hipStream_t st) {
     static_assert(C::SMEM <= 160 * 1024, "LDS ring too large");
     auto kern = gemm_bf16_kernel<EPI, C::BM, C::BN, C::BK, C::RING, C::WM, C::WN, C::CS>;
@@ -485,7 +574,7 @@ typedef Cfg<128, 128, 64, 4, 2, 4, 4> Narrow;   // wavefront tile  64 x 32: twic
 
 template <int EPI>
 int launch_tile(int tile_m, int narrow, const void* a, int K, int N, const void* const* w, const moe_tile* tiles,
-                const int32_t* hdr, void* out, int ld_out, hipStream_t st) {
+                int32_t* hdr, void* out, int ld_out, hipStream_t st) {
     if (tile_m == 256) return launch<EPI, Tall>(a, K, N, w, tiles, hdr, out, ld_out, st);
     if constexpr (EPI != MOE_EPI_SWIGLU) {          // (the SwiGLU epilogue needs a gate and an up block per wavefront)
         if (narrow) return launch<EPI, Narrow>(a, K, N, w, tiles, hdr, out, ld_out, st);
@@ -496,7 +585,7 @@ int launch_tile(int tile_m, int narrow, const void* a, int K, int N, const void*
 }  // namespace
 
 int moe_launch_gemm_bf16(int epi, int tile_m, int narrow, const void* a, int K, int N, const void* const* w,
-                         const moe_tile* tiles, const int32_t* hdr, void* out, int ld_out, hipStream_t st) {
+                         const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st) {
     if (epi == MOE_EPI_RELU) return launch_tile<MOE_EPI_RELU>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, st);
     if (epi == MOE_EPI_SWIGLU) return launch_tile<MOE_EPI_SWIGLU>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, st);
     return launch_tile<MOE_EPI_STORE>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, st);

@@ -11,4 +11,4 @@ constexpr int MOE_GEMM_GRID = 256;
 // tile_m: 128 or 256 (the tile height the table was planned with).  narrow: with tile_m = 128,
 // use column blocks of 128 instead of 256 outputs (ignored for SWIGLU).
 int moe_launch_gemm_bf16(int epi, int tile_m, int narrow, const void* a, int K, int N, const void* const* w,
-                         const moe_tile* tiles, const int32_t* hdr, void* out, int ld_out, hipStream_t st);
+                         const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st);

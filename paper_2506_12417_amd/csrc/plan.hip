@@ -278,6 +278,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         }
     }
     if (tid < G) hdr[4 + MOE_MAX_BINS + 1 + tid] = load[tid];
+    if (tid <= MOE_MAX_BINS) hdr[MOE_PLAN_HDR_CTR + tid] = 0;     // work counters of the FFN kernels
 }
 
 }  // namespace

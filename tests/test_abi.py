@@ -187,3 +187,24 @@ def test_plan_subset_and_packed_router_argument_errors():
     assert rp(k=9) == B.MOE_ERR_ARG and rp(E=300) == B.MOE_ERR_UNSUPPORTED
     assert rp(n2=None) == B.MOE_ERR_ARG and rp(wt=None) == B.MOE_ERR_ARG
     assert rp(T=0, x=None, wt=None, n2=None, idx=None, gw=None) == B.MOE_OK
+
+
+def test_ticket_register_check():
+    """The build refuses GEMM kernels in which the compiler touches the register that receives
+    the work-counter's answer behind its back; the check itself, on hand-made assembly."""
+    from paper_2506_12417_amd import build as b
+    r = b.TICKET_REG
+    ok = ("_Z1av:\n\tglobal_atomic_add v%d, v1, v2, s[4:5] sc0\n\tv_add_u32_e32 v3, v4, v5\n"
+          "\tv_readfirstlane_b32 s3, v%d\n" % (r, r))
+    # another kernel may use the register freely as long as it has no ticket instructions
+    free = "_Z1bv:\n\tv_mfma_f32_32x32x16_bf16 v[240:255], v[0:3], v[4:7], v[240:255]\n\tv_mov_b32_e32 v%d, 0\n" % r
+    assert b.check_ticket_register(ok + free) == []
+    for line in ("v_mov_b32_e32 v3, v%d" % r, "scratch_store_dword off, v%d, off" % r,
+                 "ds_read_b128 v[%d:%d], v31" % (r - 2, r + 1), "v_writelane_b32 v%d, s2, 0" % r):
+        bad = b.check_ticket_register(ok + "\t" + line + "\n" + free)
+        assert bad == [("_Z1av", line)], line
+    asm = os.path.join(os.path.dirname(b.LIB), "_build", "ffn_bf16.s")
+    if os.path.exists(asm):          # the assembly of the library that is loaded here
+        text = open(asm).read()
+        assert "global_atomic_add v%d," % r in text
+        assert b.check_ticket_register(text) == []
