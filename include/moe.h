@@ -241,6 +241,33 @@ MOE_API int moe_grouped_ffn_phase(int phase, const void* x_perm, int A, int d, i
                                   const moe_tile* tiles, int32_t* plan_hdr, int tile_m,
                                   void* h_scratch, float* y_perm, void* stream);
 
+/* Steps 5 and 6 in one call for top-1 routing (k = 1, so A = T and row r of x_perm is token
+ * perm[r]): the second product writes its rows straight to their tokens' places, weighted,
+ *
+ *   y[perm[r]] = gate_w[perm[r]] * FFN_e(x_perm[r])          r in expert e's group
+ *
+ * which is what moe_grouped_ffn followed by moe_unpermute_combine computes (bit for bit: one
+ * fp32 multiplication either way) without writing and re-reading y_perm.
+ *
+ *   perm   [T] int32 : from moe_permute (a permutation of 0..T-1)
+ *   gate_w [T] fp32 or NULL (all ones)
+ *   y      [T,d] fp32 out; every row is written exactly once
+ * other arguments as moe_grouped_ffn.  MOE_BF16 only, F >= 512 (MOE_ERR_UNSUPPORTED otherwise:
+ * use the two separate calls).
+ */
+MOE_API int moe_grouped_ffn_top1(const void* x_perm, int T, int d, int F, int E, moe_act act, moe_dtype dt,
+                                 const void* const* w_in, const void* const* w_out,
+                                 const moe_tile* tiles, int32_t* plan_hdr, int tile_m,
+                                 void* h_scratch, const int32_t* perm, const float* gate_w, float* y,
+                                 void* stream);
+/* One of its two products on its own, like moe_grouped_ffn_phase (phase 1 is the same first
+ * product; perm, gate_w and y may then be NULL). */
+MOE_API int moe_grouped_ffn_top1_phase(int phase, const void* x_perm, int T, int d, int F, int E, moe_act act,
+                                       moe_dtype dt, const void* const* w_in, const void* const* w_out,
+                                       const moe_tile* tiles, int32_t* plan_hdr, int tile_m,
+                                       void* h_scratch, const int32_t* perm, const float* gate_w, float* y,
+                                       void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Step 6 (Alg. 1 "reconstruct"; section 2: the experts' outputs are weighted by the router's
  * values and combined):

@@ -127,9 +127,17 @@ extern "C" int moe_ffn_pick_tile_m(moe_dtype dt, int A, int E) {
     return (E >= 1 && A / E >= 512) ? 256 : 128;
 }
 
+// top1: step 6 folded into the second product (perm: output row of every row; gate_w may be null)
+struct Top1 {
+    const int32_t* perm = nullptr;
+    const float* gate_w = nullptr;
+    bool on = false;
+};
+
 static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,
                             const void* const* w_in, const void* const* w_out, const moe_tile* tiles,
-                            int32_t* plan_hdr, int tile_m, void* h_scratch, float* y_perm, void* stream) {
+                            int32_t* plan_hdr, int tile_m, void* h_scratch, float* y_perm, void* stream,
+                            const Top1& top1 = Top1()) {
     MOE_REQUIRE(moe_dtype_ok(dt), MOE_ERR_UNSUPPORTED, "moe_grouped_ffn: dtype %d", (int)dt);
     MOE_REQUIRE(act == MOE_RELU || act == MOE_SWIGLU, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn: activation %d", (int)act);
     MOE_REQUIRE(A >= 0 && d >= 1 && F >= 1 && E >= 1, MOE_ERR_ARG, "moe_grouped_ffn: A=%d d=%d F=%d E=%d", A, d, F, E);
@@ -161,8 +169,12 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
             if (rc != MOE_OK) return rc;
         }
         if (phases & 2) {
-            rc = moe_launch_gemm_bf16(MOE_EPI_STORE, tile_m, narrow(d), h_scratch, F, d, w_out, tiles, plan_hdr,
-                                      (void*)y_perm, d, st);
+            if (top1.on)
+                rc = moe_launch_gemm_bf16(MOE_EPI_SCATTER, tile_m, narrow(d), h_scratch, F, d, w_out, tiles, plan_hdr,
+                                          (void*)y_perm, d, st, top1.perm, top1.gate_w, A);
+            else
+                rc = moe_launch_gemm_bf16(MOE_EPI_STORE, tile_m, narrow(d), h_scratch, F, d, w_out, tiles, plan_hdr,
+                                          (void*)y_perm, d, st);
             if (rc != MOE_OK) return rc;
         }
     } else {
@@ -196,4 +208,33 @@ extern "C" int moe_grouped_ffn_phase(int phase, const void* x_perm, int A, int d
                                      float* y_perm, void* stream) {
     MOE_REQUIRE(phase == 1 || phase == 2, MOE_ERR_ARG, "moe_grouped_ffn_phase: phase %d", phase);
     return grouped_ffn_impl(phase, x_perm, A, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, y_perm, stream);
+}
+
+static int top1_impl(int phases, const void* x_perm, int T, int d, int F, int E, moe_act act, moe_dtype dt,
+                     const void* const* w_in, const void* const* w_out, const moe_tile* tiles, int32_t* plan_hdr,
+                     int tile_m, void* h_scratch, const int32_t* perm, const float* gate_w, float* y, void* stream) {
+    MOE_REQUIRE(dt == MOE_BF16, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_top1: MOE_BF16 only (dtype %d)", (int)dt);
+    MOE_REQUIRE(F >= 512, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_top1: needs F >= 512 (F=%d)", F);
+    MOE_REQUIRE(T == 0 || !(phases & 2) || (perm && y), MOE_ERR_ARG, "moe_grouped_ffn_top1: null pointer");
+    MOE_REQUIRE((long long)T * d * 4 < (1ll << 31), MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_top1: y must be smaller than 2 GiB (T=%d d=%d)", T, d);
+    Top1 t;
+    t.perm = perm;
+    t.gate_w = gate_w;
+    t.on = true;
+    return grouped_ffn_impl(phases, x_perm, T, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, y, stream, t);
+}
+
+extern "C" int moe_grouped_ffn_top1(const void* x_perm, int T, int d, int F, int E, moe_act act, moe_dtype dt,
+                                    const void* const* w_in, const void* const* w_out, const moe_tile* tiles,
+                                    int32_t* plan_hdr, int tile_m, void* h_scratch, const int32_t* perm,
+                                    const float* gate_w, float* y, void* stream) {
+    return top1_impl(3, x_perm, T, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, perm, gate_w, y, stream);
+}
+
+extern "C" int moe_grouped_ffn_top1_phase(int phase, const void* x_perm, int T, int d, int F, int E, moe_act act,
+                                          moe_dtype dt, const void* const* w_in, const void* const* w_out,
+                                          const moe_tile* tiles, int32_t* plan_hdr, int tile_m, void* h_scratch,
+                                          const int32_t* perm, const float* gate_w, float* y, void* stream) {
+    MOE_REQUIRE(phase == 1 || phase == 2, MOE_ERR_ARG, "moe_grouped_ffn_top1_phase: phase %d", phase);
+    return top1_impl(phase, x_perm, T, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, perm, gate_w, y, stream);
 }

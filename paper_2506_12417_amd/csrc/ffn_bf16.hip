@@ -116,8 +116,9 @@ struct Cfg {
     static constexpr int KS = BK / 16;                    // 16-wide slices per K-step
     static constexpr int PH = KS / CS;                    // chunks (of CS slices) per K-step
     static constexpr size_t RING_BYTES = (size_t)RING * STAGE_BYTES;
-    static constexpr int MAX_BLK_TILES = 4092;            // tiles of a bin the block table can hold
-    static constexpr size_t SMEM = RING_BYTES + (size_t)MAX_BLK_TILES * 4 + 16;   // + ids[4] of the work hand-out
+    static constexpr int MAX_BLK_TILES = 3068;            // tiles of a bin the block table can hold
+    static constexpr int ROWINFO_BYTES = 2 * 2 * BM * 4;  // (token, gate) of a tile's rows, for two items (scatter epilogue)
+    static constexpr size_t SMEM = RING_BYTES + (size_t)MAX_BLK_TILES * 4 + 16 + ROWINFO_BYTES;   // + ids[4] of the work hand-out
     static_assert(NA >= 1 && NB >= 1 && A_BYTES % (NTH * 16) == 0 && B_BYTES % (NTH * 16) == 0, "tile vs threads");
     static_assert(ROWS_PER_PASS % (WRAP * PPR) == 0 && 32 % (WRAP * PPR) == 0, "swizzle period");
     static_assert(KS % CS == 0 && NW == 8 && WM == 2, "two groups of four wavefronts, row blocks interleaved");
@@ -131,12 +132,17 @@ template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS>
 __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_mat, int K, int N,
                                                const void* const* __restrict__ w_ptrs,
                                                const moe_tile* __restrict__ tiles, int32_t* __restrict__ hdr,
-                                               void* __restrict__ out, int ld_out) {
+                                               void* __restrict__ out, int ld_out,
+                                               const int32_t* __restrict__ row_token,
+                                               const float* __restrict__ row_gate, int out_rows) {
     using C = Cfg<BM, BN, BK, RING, WM, WN, CS>;
     constexpr int MI = C::MI, NI = C::NI, KS = C::KS, PH = C::PH;
     // The first product takes bf16 operands and writes the hidden activations as IEEE half; the
     // second one (plain store of fp32 results) takes those and a half copy of the weights.
-    constexpr bool HALF_IN = EPI == MOE_EPI_STORE;
+    // SCATTER is STORE with Alg. 1's step 6 folded in for top-1 routing: row r goes to output row
+    // row_token[r], times row_gate[that token].
+    constexpr bool SCAT = EPI == MOE_EPI_SCATTER;
+    constexpr bool HALF_IN = EPI == MOE_EPI_STORE || SCAT;
     extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = sgpr(tid >> 6);
@@ -170,7 +176,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // (the 256-row configuration needs every register: it keeps the fixed stride; its items are long
     // and alike)
     const bool dyn = RING >= 3 && KT >= 4;
-    int* ids = (int*)(ring + C::SMEM - 16);
+    int* ids = (int*)(ring + C::SMEM - C::ROWINFO_BYTES - 16);
     auto leave = [&]() {                                    // (every work-group of a dynamic launch passes here once)
         if (dyn && tid == 0) {
             const int before = __hip_atomic_fetch_add(done_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -383,7 +389,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // half pair, or two floats) and the number of store instructions halves.  Stores go through
     // a descriptor that ends with the tile's last row (the row part of a store's address is
     // range-checked only in the per-lane offset).
-    constexpr int ES = EPI == MOE_EPI_STORE ? 4 : 2;
+    constexpr int ES = HALF_IN ? 4 : 2;
     const unsigned ld_bytes = (unsigned)ld_out * ES;
     const int odd = l32 & 1;
     const unsigned st_voff = (unsigned)(wm * 32 + 4 * lhi + odd) * ld_bytes + (unsigned)(l32 & ~1) * ES;
@@ -395,7 +401,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         hi = odd ? v1 : got;
     };
     auto store_pair = [&](__amdgpu_buffer_rsrc_t ro, float lo, float hi, unsigned voff, unsigned soff) {
-        if (EPI == MOE_EPI_STORE) {
+        if (HALF_IN) {
             u32x2 v = {__float_as_uint(lo), __float_as_uint(hi)};
             __builtin_amdgcn_raw_buffer_store_b64(v, ro, voff, soff, 0);
         } else {
@@ -446,6 +452,61 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         }
     };
 
+    // ---- scatter epilogue.  The token and the gate value of every row of a tile wait in LDS
+    // (rinfo[parity of the item][0: tokens, 1: gates][row]); they were fetched there by two small
+    // global -> LDS loads during the item's first K-steps: first the tokens of the tile's rows,
+    // then, indexed by them, the gate values.
+    int* rinfo = (int*)(ring + C::SMEM - C::ROWINFO_BYTES);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(out, (unsigned)out_rows * ld_bytes);
+    auto fetch_tokens = [&](int par, int row_begin, int rc) {
+        if (wave < BM / 64) {
+            const __amdgpu_buffer_rsrc_t rt = make_rsrc(row_token + row_begin, (unsigned)(rc > 0 ? rc : 0) * 4u);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rt, (lds_void_t*)(rinfo + par * 2 * BM + wave * 64), 4,
+                                                     (unsigned)(wave * 64 + lane) * 4u, 0, 0, 0);
+            if (!row_gate) ((float*)rinfo)[par * 2 * BM + BM + wave * 64 + lane] = 1.f;
+        }
+    };
+    auto fetch_gates = [&](int par) {
+        if (row_gate && wave < BM / 64) {
+            const unsigned tok = (unsigned)rinfo[par * 2 * BM + wave * 64 + lane];
+            const __amdgpu_buffer_rsrc_t rg = make_rsrc(row_gate, (unsigned)out_rows * 4u);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rg, (lds_void_t*)(rinfo + par * 2 * BM + BM + wave * 64), 4, tok * 4u, 0, 0, 0);
+        }
+    };
+    auto epilogue_scatter = [&](int par, int rc, int mi_on, int n0) {
+        const int lane_row = wm * 32 + 4 * lhi + odd;
+        const unsigned col_off = (unsigned)(l32 & ~1) * 4u;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            if (mi >= mi_on) continue;
+#pragma unroll
+            for (int rp = 0; rp < 8; ++rp) {
+                const int r = 2 * rp;
+                const int rr = lane_row + mi * (C::WM * 32) + 8 * (r >> 2) + (r & 3);
+                const unsigned tok = (unsigned)rinfo[par * 2 * BM + rr];
+                const float gate = ((const float*)rinfo)[par * 2 * BM + BM + rr];
+                // (a row past the tile's end gets an offset no output has: the range check drops it)
+                const unsigned voff = (rr < rc ? tok * ld_bytes : 0x80000000u) + col_off;
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const int col = n0 + wn * C::WTN + ni * 32;
+                    if (col < N) {
+                        float lo, hi;
+                        pair_up(acc[mi][ni][r], acc[mi][ni][r + 1], lo, hi);
+                        store_pair(ry, lo * gate, hi * gate, voff, (unsigned)col * 4u);
+                    }
+                }
+            }
+        }
+    };
+    // the finished item: p_* describe it
+    int p_mi_on = 0, p_n0 = 0, p_rc = 0, p_par = 0;
+    __amdgpu_buffer_rsrc_t p_ro = make_rsrc(out, 0u);       // the previous item, stored in the next one's first phase
+    auto finish_prev = [&]() {
+        if constexpr (SCAT) epilogue_scatter(p_par, p_rc, p_mi_on, p_n0);
+        else epilogue(p_ro, p_mi_on, p_n0);
+    };
+
     // ---- prologue: RING-1 stages on their way, the first one landed
     load_item(first);
 #pragma unroll
@@ -460,8 +521,6 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     zero_acc();
     if (grp == 1) phase_barrier();                          // group 1 starts one phase late
 
-    __amdgpu_buffer_rsrc_t p_ro = make_rsrc(out, 0u);       // the previous item, stored in the next one's first phase
-    int p_mi_on = 0, p_n0 = 0;
     int item = first, c_seq = 0;
     while (item < n_items) {
         int cb, ti;
@@ -488,14 +547,14 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                 constexpr bool EARLY = RING >= 3;
                 const bool store_now = h == 0 && first_of_item;
                 if (store_now && !EARLY) {
-                    epilogue(p_ro, p_mi_on, p_n0);
+                    finish_prev();
                     zero_acc();
                 }
                 mem_phase(c_buf, h);
                 if (store_now && EARLY) {
                     wait_stage_after(g);
                     publish();
-                    epilogue(p_ro, p_mi_on, p_n0);
+                    finish_prev();
                     zero_acc();
                 }
                 const bool waited = EARLY && first_of_item;
@@ -521,8 +580,12 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         // RING-1 K-steps ago.  (With one K-step per item there is no handing out: fixed stride.)
         int next = item + stride;
         auto run_item = [&](auto full) {
+            if constexpr (SCAT) fetch_tokens(c_seq & 1, tile.row_begin, rc);
             k_step(full, true, KT == 1 && next >= n_items);
             for (int kt = 1; kt < KT; ++kt) {
+                // (three K-steps of operand loads have been issued since: the waits of the last two
+                // K-steps have covered the token load)
+                if constexpr (SCAT) { if (kt == 3) fetch_gates(c_seq & 1); }
                 bool last = false;
                 if (kt == KT - 1) {
                     next = item_of(c_seq + 1, item);
@@ -536,10 +599,16 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         p_ro = ro;
         p_mi_on = mi_on;
         p_n0 = n0;
+        p_rc = rc;
+        p_par = c_seq & 1;
         item = next;
         ++c_seq;
     }
-    epilogue(p_ro, p_mi_on, p_n0);
+    if constexpr (SCAT) {                                   // (the last item's gates may have been fetched by other wavefronts)
+        MOE_WAIT_VMCNT(0);
+        __syncthreads();
+    }
+    finish_prev();
     leave();
     MOE_WAIT_VMCNT(0);                                      // (the trailing empty loads still target this LDS)
 }
@@ -549,20 +618,28 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(const uint16_t*
                                                                   const void* const* __restrict__ w_ptrs,
                                                                   const moe_tile* __restrict__ tiles,
                                                                   int32_t* __restrict__ hdr, void* __restrict__ out,
-                                                                  int ld_out) {
-    gemm_bf16_body<EPI, BM, BN, BK, RING, WM, WN, CS>(a_mat, K, N, w_ptrs, tiles, hdr, out, ld_out);
+                                                                  int ld_out, const int32_t* __restrict__ row_token,
+                                                                  const float* __restrict__ row_gate, int out_rows) {
+    gemm_bf16_body<EPI, BM, BN, BK, RING, WM, WN, CS>(a_mat, K, N, w_ptrs, tiles, hdr, out, ld_out, row_token, row_gate,
+                                                      out_rows);
 }
+
+struct ScatterArgs {             // MOE_EPI_SCATTER only
+    const int32_t* row_token = nullptr;
+    const float* row_gate = nullptr;
+    int out_rows = 0;
+};
 
 template <int EPI, class C>
 int launch(const void* a, int K, int N, const void* const* w, const moe_tile* tiles, int32_t* hdr, void* out,
-           int ld_out, hipStream_t st) {
+           int ld_out, const ScatterArgs& sc, hipStream_t st) {
     static_assert(C::SMEM <= 160 * 1024, "LDS ring too large");
     auto kern = gemm_bf16_kernel<EPI, C::BM, C::BN, C::BK, C::RING, C::WM, C::WN, C::CS>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)C::SMEM);
     if (e != hipSuccess) return moe_fail(MOE_ERR_HIP, "moe_grouped_ffn: shared memory attribute: %s", hipGetErrorString(e));
     hipLaunchKernelGGL(kern, dim3(MOE_GEMM_GRID), dim3(C::NTH), C::SMEM, st, (const uint16_t*)a, K, N, w, tiles, hdr, out,
-                       ld_out);
+                       ld_out, sc.row_token, sc.row_gate, sc.out_rows);
     MOE_CHECK_LAUNCH("moe_grouped_ffn (bf16 GEMM)");
     return MOE_OK;
 }
@@ -574,19 +651,27 @@ typedef Cfg<128, 128, 64, 4, 2, 4, 4> Narrow;   // wavefront tile  64 x 32: twic
 
 template <int EPI>
 int launch_tile(int tile_m, int narrow, const void* a, int K, int N, const void* const* w, const moe_tile* tiles,
-                int32_t* hdr, void* out, int ld_out, hipStream_t st) {
-    if (tile_m == 256) return launch<EPI, Tall>(a, K, N, w, tiles, hdr, out, ld_out, st);
+                int32_t* hdr, void* out, int ld_out, const ScatterArgs& sc, hipStream_t st) {
+    if (tile_m == 256) return launch<EPI, Tall>(a, K, N, w, tiles, hdr, out, ld_out, sc, st);
     if constexpr (EPI != MOE_EPI_SWIGLU) {          // (the SwiGLU epilogue needs a gate and an up block per wavefront)
-        if (narrow) return launch<EPI, Narrow>(a, K, N, w, tiles, hdr, out, ld_out, st);
+        if (narrow) return launch<EPI, Narrow>(a, K, N, w, tiles, hdr, out, ld_out, sc, st);
     }
-    return launch<EPI, Short>(a, K, N, w, tiles, hdr, out, ld_out, st);
+    return launch<EPI, Short>(a, K, N, w, tiles, hdr, out, ld_out, sc, st);
 }
 
 }  // namespace
 
 int moe_launch_gemm_bf16(int epi, int tile_m, int narrow, const void* a, int K, int N, const void* const* w,
-                         const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st) {
-    if (epi == MOE_EPI_RELU) return launch_tile<MOE_EPI_RELU>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, st);
-    if (epi == MOE_EPI_SWIGLU) return launch_tile<MOE_EPI_SWIGLU>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, st);
-    return launch_tile<MOE_EPI_STORE>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, st);
+                         const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st,
+                         const int32_t* row_token, const float* row_gate, int out_rows) {
+    ScatterArgs sc;
+    if (epi == MOE_EPI_RELU) return launch_tile<MOE_EPI_RELU>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, sc, st);
+    if (epi == MOE_EPI_SWIGLU) return launch_tile<MOE_EPI_SWIGLU>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, sc, st);
+    if (epi == MOE_EPI_SCATTER) {
+        sc.row_token = row_token;
+        sc.row_gate = row_gate;
+        sc.out_rows = out_rows;
+        return launch_tile<MOE_EPI_SCATTER>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, sc, st);
+    }
+    return launch_tile<MOE_EPI_STORE>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, sc, st);
 }

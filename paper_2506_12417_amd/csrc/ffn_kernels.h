@@ -2,13 +2,16 @@
 #pragma once
 #include "common.h"
 
-enum { MOE_EPI_RELU = 0, MOE_EPI_SWIGLU = 1, MOE_EPI_STORE = 2 };
+enum { MOE_EPI_RELU = 0, MOE_EPI_SWIGLU = 1, MOE_EPI_STORE = 2, MOE_EPI_SCATTER = 3 };
 
 // persistent grid: one work-group per CU (256 CUs; 32 per XCD, dealt round-robin)
 constexpr int MOE_GEMM_GRID = 256;
 
-// out = epilogue(a . w_e^T) over the tile table.  epi: RELU / SWIGLU write bf16, STORE writes fp32.
+// out = epilogue(a . w_e^T) over the tile table.  epi: RELU / SWIGLU write half, STORE writes fp32,
+// SCATTER writes fp32 row r to out[row_token[r]] times row_gate[row_token[r]] (row_gate may be null;
+// out has out_rows rows).
 // tile_m: 128 or 256 (the tile height the table was planned with).  narrow: with tile_m = 128,
 // use column blocks of 128 instead of 256 outputs (ignored for SWIGLU).
 int moe_launch_gemm_bf16(int epi, int tile_m, int narrow, const void* a, int K, int N, const void* const* w,
-                         const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st);
+                         const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st,
+                         const int32_t* row_token = nullptr, const float* row_gate = nullptr, int out_rows = 0);

@@ -101,6 +101,9 @@ class MoELayer:
         self.y_perm = torch.empty((A, d), dtype=f32, device=dev)
         self.y = torch.empty((T, d), dtype=f32, device=dev)
         self.shared_F = shared_F
+        # top-1 routing without a shared expert: step 6 is folded into the second GEMM (128-row tiles;
+        # the 256-row kernel has no registers left for it)
+        self.fold_combine = (k == 1 and self.dt == B.MOE_BF16 and not shared_F and self.tile_m == 128 and F >= 512)
         if shared_F:
             # the always-on shared expert is one more group: E = 1, every token, rows in place
             self.shared = ExpertGroup(1, d, shared_F, B.MOE_SWIGLU, self.dt, dev)
@@ -180,6 +183,20 @@ class MoELayer:
         self.route(x, None, stream)
         self.permute(x, stream)
         self.plan(stream)
+        if self.fold_combine:
+            # top-1: the second product writes y directly (no y_perm round trip, no combine kernel)
+            g = self.experts
+            args = (self.x_perm, self.T, self.d, self.F, self.E, self.act, self.dt, g.in_ptrs, g.out_ptrs, self.tiles,
+                    self.plan_hdr, self.tile_m, self.h, self.perm, self.gate_w, self.y, stream)
+            if marks is None:
+                B.moe_grouped_ffn_top1(*args)
+            else:
+                marks[0].record()
+                B.moe_grouped_ffn_top1_phase(1, *args)
+                marks[1].record()
+                B.moe_grouped_ffn_top1_phase(2, *args)
+                marks[2].record()
+            return self.y
         if marks is None:
             self.ffn(stream)
         else:

@@ -142,6 +142,14 @@ def test_pack_combine_copy_argument_errors():
     assert status(B.moe_pack_weights, None, None, 1, 8, 8, B.MOE_F32, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_pack_weights, None, None, 0, 8, 8, B.MOE_F32, None, 0) == B.MOE_OK
     assert status(B.moe_pack_w_out, FAKE, 1, 0, 8, B.MOE_BF16, FAKE, 0) == B.MOE_ERR_ARG
+    top1 = lambda dt, F, perm, y: status(B.moe_grouped_ffn_top1, FAKE, 8, 64, F, 2, B.MOE_RELU, dt, FAKE, FAKE, FAKE, FAKE,
+                                         128, FAKE, perm, None, y, 0)
+    assert top1(B.MOE_F32, 512, FAKE, FAKE) == B.MOE_ERR_UNSUPPORTED
+    assert top1(B.MOE_BF16, 448, FAKE, FAKE) == B.MOE_ERR_UNSUPPORTED
+    assert top1(B.MOE_BF16, 512, None, FAKE) == B.MOE_ERR_ARG
+    assert top1(B.MOE_BF16, 512, FAKE, None) == B.MOE_ERR_ARG
+    assert status(B.moe_grouped_ffn_top1_phase, 3, FAKE, 8, 64, 512, 2, B.MOE_RELU, B.MOE_BF16, FAKE, FAKE, FAKE, FAKE,
+                  128, FAKE, FAKE, None, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_pack_w_out, None, 1, 8, 8, B.MOE_BF16, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_pack_w_out, FAKE, 1, 8, 8, 7, FAKE, 0) == B.MOE_ERR_UNSUPPORTED
     assert status(B.moe_pack_w_out, None, 0, 8, 8, B.MOE_BF16, None, 0) == B.MOE_OK

@@ -285,6 +285,13 @@ def _stage_check(torch, wl, inp, tol_scale=1.0):
     x = layer_x(layer, inp)
     y = layer.forward(x)
     torch.cuda.synchronize()
+    if layer.fold_combine:
+        # forward() took the top-1 entry point (no y_perm); the separate calls must give the same bits
+        y_folded = y.clone()
+        layer.ffn()
+        layer.combine(True)
+        torch.cuda.synchronize()
+        assert torch.equal(y_folded, layer.y)
     idx_o, w_o, _ = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
     assert np.array_equal(to_numpy(layer.expert_idx), idx_o)
     p = O.permute(idx_o, wl.E)
@@ -483,3 +490,43 @@ def test_full_size_workloads_sampled(torch_gpu, name, n_sample):
     print("   %s: %d tokens, max err / rms = %.3e (tol %.0e)" % (name, tok.size, err, TOL[wl.dtype]), flush=True)
     assert err <= TOL[wl.dtype]
     assert np.isfinite(y_h).all()
+
+
+@pytest.mark.parametrize("T,d,F,E,gate,skew", [(1500, 128, 512, 16, True, "zipf"), (1500, 128, 512, 16, False, "zipf"),
+                                               (4096, 768, 3072, 128, True, "zipf"), (777, 192, 640, 5, True, "hot"),
+                                               (300, 64, 1024, 40, True, "uniform")])
+def test_ffn_top1_is_ffn_then_combine(torch_gpu, T, d, F, E, gate, skew):
+    """moe_grouped_ffn_top1 writes what moe_grouped_ffn + moe_unpermute_combine write, bit for bit:
+    ragged tiles, empty experts, with and without gate values, and twice in a row on one plan."""
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    from paper_2506_12417_amd.layer import MoELayer
+    dev = torch.device("cuda:0")
+    r = np.random.default_rng(T + F)
+    if skew == "zipf":
+        p_e = 1.0 / np.arange(1, E + 1)
+    elif skew == "hot":
+        p_e = np.array([0.9] + [0.1 / (E - 1)] * (E - 1))
+    else:
+        p_e = np.ones(E)
+    p_e[E // 2] = 0.0                                     # one expert stays empty
+    ids = r.choice(E, size=T, p=p_e / p_e.sum()).astype(np.int32)
+    L = MoELayer(T, d, F, E, 1, "relu", "bf16", 0, tile_m=128)
+    L.experts.w_in.normal_(0, d ** -0.5)
+    B.moe_pack_w_out(torch.randn(E, F, d, device=dev).mul_(F ** -0.5).to(torch.bfloat16), E, F, d, B.MOE_BF16, L.experts.w_out)
+    L.expert_idx.copy_(torch.from_numpy(ids).view(T, 1))
+    L.gate_w.copy_(torch.rand(T, 1, device=dev) + 0.05)
+    x = torch.randn(T, d, device=dev).to(torch.bfloat16)
+    L.permute(x)
+    L.plan()
+    L.ffn()
+    L.combine(gate)
+    y_sep = L.y.clone()
+    for rep in range(2):
+        L.y.fill_(float("nan"))
+        g = L.experts
+        B.moe_grouped_ffn_top1(L.x_perm, T, d, F, E, L.act, L.dt, g.in_ptrs, g.out_ptrs, L.tiles, L.plan_hdr, L.tile_m,
+                               L.h, L.perm, L.gate_w if gate else None, L.y)
+        torch.cuda.synchronize()
+        assert torch.equal(L.y, y_sep), rep
+    assert int(L.plan_hdr[B.MOE_PLAN_HDR_CTR:].abs().sum()) == 0      # the work counters are back at zero
