@@ -159,6 +159,7 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-uniform", action="store_true")
+    ap.add_argument("--no-ablation", action="store_true", help="skip the plan-policy and alpha-skew legs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 256 MiB a few times (reference for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -266,6 +267,44 @@ def main():
         out["uniform_tokens_per_s"] = round(wl.T / (ms_u * 1e-3), 1)
         out["skew_over_uniform"] = round(ms_u / ms, 4)
         layer.load_router(inp["W_g"], inp["b"])
+
+    if not args.no_ablation:
+        # The scheduling policies of section 5.3.2 / Fig. "skewnew" as modes of the same plan kernel
+        # (same rows, same kernels, bit-identical outputs; only the tile schedule differs).
+        # (timed without the event records between the kernels, which cost a few microseconds a step)
+        abl = {"alg2": round(timed(max(10, args.steps // 2), 3, marks_on=False)[0], 4)}   # the default: Alg. 2 as printed
+        for name, pol in (("balanced_tiles", B.MOE_PLAN_BALANCED), ("static", B.MOE_PLAN_STATIC), ("even_split", B.MOE_PLAN_EVEN_SPLIT)):
+            layer.policy = pol
+            abl[name] = round(timed(max(10, args.steps // 2), 3, marks_on=False)[0], 4)
+        layer.policy = B.MOE_PLAN_HARMOENY
+        out["plan_ablation_ms_per_step"] = abl
+    if not args.no_ablation and wl.k == 1:
+        # Section 5.1's synthetic router: the first n_hot experts share probability alpha, ids are
+        # sampled per token; alpha changes from batch to batch (the dynamic-skew experiment).
+        # The router product is not part of these steps (the ids are the router's output).
+        rs = np.random.default_rng(wl.seed() + 7)
+        layer.gate_w.fill_(1.0)
+        batches = []
+        for bi in range(12):
+            alpha = float(rs.uniform(0.0, 0.95)) if bi >= 3 else (0.0, 0.5, 0.9)[bi]
+            n_hot = 1 if bi != 2 else 10
+            ids = W.alpha_skew_ids(wl.T, wl.E, alpha, n_hot, wl.seed() + 100 + bi)
+            layer.expert_idx.copy_(torch.from_numpy(ids).view(wl.T, 1))
+            for _ in range(3):
+                layer.forward(x, routed=True)
+            s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            s_ev.record()
+            for _ in range(10):
+                layer.forward(x, routed=True)
+            e_ev.record()
+            torch.cuda.synchronize()
+            batches.append({"alpha": round(alpha, 3), "n_hot": n_hot, "ms": round(s_ev.elapsed_time(e_ev) / 10, 4)})
+        t = np.array([b["ms"] for b in batches])
+        out["alpha_skew"] = {"note": "sampled ids (no router product), 12 batches, alpha in [0, 0.95]",
+                             "tokens_per_s_mean": round(float(wl.T / (t.mean() * 1e-3)), 1),
+                             "ms_min": round(float(t.min()), 4), "ms_max": round(float(t.max()), 4),
+                             "ms_std": round(float(t.std()), 4), "batches": batches}
 
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as O       # the CPU oracle, timed as it stands

@@ -113,13 +113,14 @@ MOE_API int moe_permute(const void* x, const int32_t* expert_idx, int T, int d, 
  * n_bins XCDs in the role of the paper's GPUs.  S[e,g] = rows of expert e processed by bin g.
  *
  * policy
- *   MOE_PLAN_BALANCED  experts are first placed whole, heaviest first, each on the least
- *                      loaded bin; then Alg. 2's loop moves rows of the largest block of the
- *                      most loaded bin to the least loaded one while that helps.  A block of n
- *                      rows of one expert in one bin weighs max(n, q_tokens): below q_tokens
- *                      rows an expert's time is the fetch of its weights, not its arithmetic
- *                      (section 4.4, Eq. 1).  Moves are whole multiples of tile_m rows unless a
- *                      whole block moves.
+ *   MOE_PLAN_BALANCED  Alg. 2 in units of tiles: a block of n rows of one expert on one bin
+ *                      weighs ceil(n / tile_m), because the kernels work tile by tile and a tile
+ *                      costs about the same whether it holds many rows (arithmetic) or few (the
+ *                      fetch of the expert's weights; section 4.4, Eq. 1).  Experts are first
+ *                      placed whole, heaviest first, each on the least loaded bin; then, until
+ *                      the most and the least loaded bin differ by at most one tile, half their
+ *                      difference moves from the one to the other, taken in whole tiles from
+ *                      the largest block (or the whole block).  q_tokens is not used.
  *   MOE_PLAN_HARMOENY  Alg. 2 as printed: expert e starts on bin e*n_bins/E (contiguous
  *                      blocks of experts), loads are row counts, any number of rows may move,
  *                      a move needs at least q_tokens rows.

@@ -293,8 +293,9 @@ def token_threshold_q_exact(phi: float, d_type: int, beta: float, m: int, p: int
 # The library runs Alg. 2 with the GPU's XCDs ("bins") in the role of the paper's GPUs and one
 # source (G_src = 1), so S is [E, n_bins].  Two of its policies are the paper's own
 # (schedule_harmoeny, schedule_static, schedule_even_split); schedule_balanced is this build's
-# extension of Alg. 2 and is DEFINED by the function below (no paper counterpart to pin it to
-# beyond: it reduces to Alg. 2 when weights are row counts, and the invariants in the tests).
+# variant of Alg. 2 in units of tiles and is DEFINED by the function below (no paper counterpart
+# to pin it to beyond a hand-worked case, the invariants in the tests, and its by_cost=False
+# form, which is Alg. 2).
 
 def contiguous_home(E: int, G: int):
     """Experts in contiguous blocks per GPU (Fig. 2 of the paper: experts 1,2 on GPU 0, ...)."""
@@ -325,25 +326,24 @@ def schedule_even_split(counts, G: int) -> np.ndarray:
     return S
 
 
-def block_weight(n: int, q: int) -> int:
-    """Weight of n rows of one expert on one bin, in row equivalents: below q rows the time is
-    the fetch of the expert's weights, which by Eq. 1 equals the arithmetic of q rows."""
-    return 0 if n <= 0 else max(int(n), int(q))
-
-
 def schedule_balanced(counts, G: int, q: int, tile_m: int, by_cost: bool = True) -> np.ndarray:
-    """This build's default schedule.
+    """This build's default schedule (by_cost=True): the bins get equal numbers of TILES.
+    A block of n rows of one expert on one bin weighs ceil(n / tile_m): the kernels work tile by
+    tile, and a tile costs about the same whether its rows are many (arithmetic) or few (the
+    fetch of the expert's weights, section 4.4).
     1. initialAssign: experts in order of falling weight (equal weights: rising id), each whole
        onto the bin with the least weight so far (lowest bin among equals).
-    2. Alg. 2's loop on bin weights t_g = sum_e block_weight(S[e,g]); t_avg = floor(sum t_g / G).
-       Differences from the printed loop: weights instead of row counts; when only part of a
-       block moves, at least q rows stay behind and the part is rounded down to whole tiles of
-       tile_m rows (stop if fewer than q rows would move).
-    by_cost=False makes the weight the row count and the granule one row: then step 2 IS Alg. 2."""
+    2. Alg. 2's loop in tiles: take the most and the least loaded bin (lowest index among
+       equals); stop when they differ by at most one tile; otherwise move m = min(tiles of the
+       block, floor(difference / 2)) tiles of the largest block (most rows, lowest expert among
+       equals) of the most loaded bin to the least loaded one: the whole block if m covers it,
+       else m * tile_m rows.  q is not used.
+    by_cost=False: weights are row counts, the granule is one row, the stop rules are those of
+    the printed loop (a move needs q rows, the receiver stays below the average): step 2 IS Alg. 2."""
     counts = np.asarray(counts, dtype=np.int64)
     E = len(counts)
-    w = (lambda n: block_weight(n, q)) if by_cost else (lambda n: int(n))
-    gran = tile_m if by_cost else 1
+    tiles_of = lambda n: (int(n) + tile_m - 1) // tile_m
+    w = tiles_of if by_cost else (lambda n: int(n))
     S = np.zeros((E, G), dtype=np.int64)
     order = sorted(range(E), key=lambda e: (-w(counts[e]), e))
     t_g = np.zeros(G, dtype=np.int64)
@@ -353,6 +353,21 @@ def schedule_balanced(counts, G: int, q: int, tile_m: int, by_cost: bool = True)
         g = int(np.argmin(t_g))
         S[e, g] = counts[e]
         t_g[g] += w(counts[e])
+    if by_cost:
+        for _ in range(E * G + 16):
+            g_max, g_min = int(np.argmax(t_g)), int(np.argmin(t_g))
+            diff = int(t_g[g_max] - t_g[g_min])
+            if diff <= 1:
+                break
+            e_max = int(np.argmax(S[:, g_max]))
+            n_from, n_to = int(S[e_max, g_max]), int(S[e_max, g_min])
+            m = min(tiles_of(n_from), diff // 2)
+            t_s = n_from if m == tiles_of(n_from) else m * tile_m
+            t_g[g_max] -= tiles_of(n_from) - tiles_of(n_from - t_s)
+            t_g[g_min] += tiles_of(n_to + t_s) - tiles_of(n_to)
+            S[e_max, g_max] = n_from - t_s
+            S[e_max, g_min] = n_to + t_s
+        return S
     t_avg = int(t_g.sum()) // G
     for _ in range(E * G + 16):
         if not np.any(t_g > t_avg):
@@ -366,17 +381,10 @@ def schedule_balanced(counts, G: int, q: int, tile_m: int, by_cost: bool = True)
         if g_min == g_max or t_g[g_min] + q > t_avg:
             break
         t_s = min(t_move, t_avg - int(t_g[g_min]))
-        if by_cost and t_s < t_move:
-            if t_move - t_s < q:
-                t_s = t_move - q
-            t_s = (t_s // gran) * gran
-            if t_s < q or t_s <= 0:
-                break
-        n_from, n_to = int(S[e_max, g_max]), int(S[e_max, g_min])
-        t_g[g_max] -= w(n_from) - w(n_from - t_s)
-        t_g[g_min] += w(n_to + t_s) - w(n_to)
-        S[e_max, g_max] = n_from - t_s
-        S[e_max, g_min] = n_to + t_s
+        t_g[g_max] -= t_s
+        t_g[g_min] += t_s
+        S[e_max, g_max] -= t_s
+        S[e_max, g_min] += t_s
     return S
 
 

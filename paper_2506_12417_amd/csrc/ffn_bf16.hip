@@ -173,8 +173,8 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // fixed stride.  The last work-group to finish zeroes the counters for the next launch.
     int32_t* next_ctr = hdr + MOE_PLAN_HDR_CTR + bin;
     int32_t* done_ctr = hdr + MOE_PLAN_HDR_CTR + MOE_MAX_BINS;
-    // (the 256-row configuration needs every register: it keeps the fixed stride; its items are long
-    // and alike)
+    // (the 256-row configuration keeps the fixed stride: its items are long and alike, handing
+    // them out on demand measured no gain there, and it has no register to spare)
     const bool dyn = RING >= 3 && KT >= 4;
     int* ids = (int*)(ring + C::SMEM - C::ROWINFO_BYTES - 16);
     auto leave = [&]() {                                    // (every work-group of a dynamic launch passes here once)

@@ -13,8 +13,9 @@ namespace {
 
 constexpr int NTH = 256;   // >= MOE_MAX_EXPERTS: one thread per expert
 
-__device__ __forceinline__ int weight_of(int n, int q, bool by_cost) {
-    return by_cost ? (n > 0 ? (n > q ? n : q) : 0) : n;
+// weight of a block of n rows: its tiles (MOE_PLAN_BALANCED) or its rows
+__device__ __forceinline__ int weight_of(int n, int tile_m, bool in_tiles) {
+    return in_tiles ? (n + tile_m - 1) / tile_m : n;
 }
 
 // Loads are kept below 2^26 so that (load << 5 | bin) fits 32 bits (bins < 32): one reduction gives both the
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         int c = ((mask.w[tid >> 5] >> (tid & 31)) & 1u) ? counts[tid] : 0;    // experts left out count as empty
         cnt[tid] = c;
         row0[tid] = offsets[tid];                  // (fetched now: a global load at the end would be waited for in full)
-        cost[tid] = weight_of(c, q, by_cost);
+        cost[tid] = weight_of(c, tile_m, by_cost);
     }
     if (tid < 4) cost[E + tid] = -1;
     if (tid == 0) s_moves = 0;
@@ -162,37 +163,37 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         int tg = lane < G ? load[lane] : 0;
         const int t_avg = (int)(moe_wave_sum_u32((unsigned)tg) / (unsigned)G);
         int moves = 0;
-        if (policy == MOE_PLAN_BALANCED || policy == MOE_PLAN_HARMOENY) {
-            const int gran = by_cost ? tile_m : 1;
-            const int max_iters = E * G + 16;
+        // the largest block of bin g (most rows, lowest expert among equals)
+        auto largest_block = [&](int g, int& e_max, int& rows) {
+            int best = -1;
+            for (int e = lane; e < E; e += 64) {
+                const int sv = S[e * G + g];
+                best = sv > best ? sv : best;
+            }
+            rows = (int)moe_wave_max_u32((unsigned)(best + 1)) - 1;
+            unsigned first = 0xffffffffu;
+            for (int e = lane; e < E; e += 64)
+                if (S[e * G + g] == rows) { first = (unsigned)e; break; }
+            e_max = (int)moe_wave_min_u32(first);
+        };
+        const int max_iters = E * G + 16;
+        if (policy == MOE_PLAN_BALANCED) {
+            // in tiles: until the most and the least loaded bin differ by at most one tile, half
+            // the difference (in whole tiles, or the whole block) moves from the one to the other
             for (int it = 0; it < max_iters; ++it) {
-                int g_max, t_max;
+                int g_max, t_max, g_min, t_min;
                 argmax_bin(tg, lane, G, g_max, t_max);
-                if (t_max <= t_avg) break;                       // no bin above the average
-                int best = -1;
-                for (int e = lane; e < E; e += 64) {
-                    const int sv = S[e * G + g_max];
-                    best = sv > best ? sv : best;
-                }
-                const int t_move = (int)moe_wave_max_u32((unsigned)(best + 1)) - 1;
-                unsigned first = 0xffffffffu;                    // lowest expert holding t_move rows
-                for (int e = lane; e < E; e += 64)
-                    if (S[e * G + g_max] == t_move) { first = (unsigned)e; break; }
-                const int e_max = (int)moe_wave_min_u32(first);
-                if (t_move < q) break;
-                int g_min, t_min;
                 argmin_bin(tg, lane, G, g_min, t_min);
-                if (g_min == g_max || t_min + q > t_avg) break;
-                int t_s = t_move < t_avg - t_min ? t_move : t_avg - t_min;
-                if (by_cost && t_s < t_move) {
-                    // a split leaves at least q rows behind and moves whole tiles
-                    if (t_move - t_s < q) t_s = t_move - q;
-                    t_s = t_s / gran * gran;
-                    if (t_s < q || t_s <= 0) break;
-                }
-                const int n_from = S[e_max * G + g_max], n_to = S[e_max * G + g_min];
-                const int d_from = weight_of(n_from, q, by_cost) - weight_of(n_from - t_s, q, by_cost);
-                const int d_to = weight_of(n_to + t_s, q, by_cost) - weight_of(n_to, q, by_cost);
+                const int diff = t_max - t_min;
+                if (diff <= 1) break;
+                int e_max, n_from;
+                largest_block(g_max, e_max, n_from);
+                const int n_to = S[e_max * G + g_min];
+                const int tiles_from = weight_of(n_from, tile_m, true);
+                const int m = tiles_from < diff / 2 ? tiles_from : diff / 2;
+                const int t_s = m == tiles_from ? n_from : m * tile_m;
+                const int d_from = tiles_from - weight_of(n_from - t_s, tile_m, true);
+                const int d_to = weight_of(n_to + t_s, tile_m, true) - weight_of(n_to, tile_m, true);
                 if (lane == 0) {
                     S[e_max * G + g_max] = n_from - t_s;
                     S[e_max * G + g_min] = n_to + t_s;
@@ -200,6 +201,29 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
                 __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");   // the next round's lanes read these
                 if (lane == g_max) tg -= d_from;
                 if (lane == g_min) tg += d_to;
+                ++moves;
+            }
+        } else if (policy == MOE_PLAN_HARMOENY) {
+            // Alg. 2 as printed, loads in rows
+            for (int it = 0; it < max_iters; ++it) {
+                int g_max, t_max;
+                argmax_bin(tg, lane, G, g_max, t_max);
+                if (t_max <= t_avg) break;                       // no bin above the average
+                int e_max, t_move;
+                largest_block(g_max, e_max, t_move);
+                if (t_move < q) break;
+                int g_min, t_min;
+                argmin_bin(tg, lane, G, g_min, t_min);
+                if (g_min == g_max || t_min + q > t_avg) break;
+                const int t_s = t_move < t_avg - t_min ? t_move : t_avg - t_min;
+                const int n_from = S[e_max * G + g_max], n_to = S[e_max * G + g_min];
+                if (lane == 0) {
+                    S[e_max * G + g_max] = n_from - t_s;
+                    S[e_max * G + g_min] = n_to + t_s;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");   // the next round's lanes read these
+                if (lane == g_max) tg -= t_s;
+                if (lane == g_min) tg += t_s;
                 ++moves;
             }
         }

@@ -68,7 +68,7 @@ class ExpertGroup:
 class MoELayer:
     def __init__(self, T: int, d: int, F: int, E: int, k: int, act: str, dtype: str, renorm: int,
                  shared_F: int = 0, n_bins: int = XCDS, q_tokens: Optional[int] = None,
-                 policy: int = B.MOE_PLAN_BALANCED, tile_m: Optional[int] = None, device="cuda:0"):
+                 policy: int = B.MOE_PLAN_HARMOENY, tile_m: Optional[int] = None, device="cuda:0"):
         self.T, self.d, self.F, self.E, self.k, self.renorm = T, d, F, E, k, renorm
         self.A = T * k
         self.act = B.MOE_SWIGLU if act == "swiglu" else B.MOE_RELU
@@ -116,7 +116,7 @@ class MoELayer:
             self.s_h = torch.empty((T, shared_F), dtype=self.tdt, device=dev)
             self.s_y = torch.empty((T, d), dtype=f32, device=dev)
             B.moe_plan_tiles(self.s_counts, self.s_offsets, 1, T, self.s_tile_m, n_bins, self.q_tokens,
-                             B.MOE_PLAN_BALANCED, self.s_tiles, self.s_capacity, self.s_hdr, None)
+                             B.MOE_PLAN_HARMOENY, self.s_tiles, self.s_capacity, self.s_hdr, None)
 
     # ------------------------------------------------------------------ parameters
     def load_router(self, W_g: np.ndarray, b: Optional[np.ndarray], packed: Optional[bool] = None):
@@ -176,11 +176,13 @@ class MoELayer:
         B.moe_unpermute_combine(self.y_perm, self.inv_perm, self.gate_w if use_gate else None,
                                 self.s_y if self.shared_F else None, self.T, self.d, self.k, self.y, stream)
 
-    def forward(self, x: torch.Tensor, stream=None, marks=None) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, stream=None, marks=None, routed: bool = False) -> torch.Tensor:
         """Enqueues the whole layer on the current (or given) stream; returns the output buffer.
         marks: optional list of 3 torch.cuda.Event recorded before / between / after the two
-        grouped GEMMs (for per-kernel timing)."""
-        self.route(x, None, stream)
+        grouped GEMMs (for per-kernel timing).  routed: expert_idx and gate_w are already set
+        (a router that samples ids, section 5.1's synthetic skew): step 1 is skipped."""
+        if not routed:
+            self.route(x, None, stream)
         self.permute(x, stream)
         self.plan(stream)
         if self.fold_combine:
@@ -333,7 +335,7 @@ class PreRoutedShare:
 
         def run(group_ids):
             B.moe_plan_tiles_subset(self.counts, self.offsets, E, T, self.tile_m, self.n_bins, self.q_tokens,
-                                    B.MOE_PLAN_BALANCED, group_ids, self.tiles, self.tile_capacity, self.plan_hdr,
+                                    B.MOE_PLAN_HARMOENY, group_ids, self.tiles, self.tile_capacity, self.plan_hdr,
                                     None, stream)
             B.moe_grouped_ffn(self.x_perm, T, self.d, self.F, E, self.act, self.dt, self.ptr_dev[0], self.ptr_dev[1],
                               self.tiles, self.plan_hdr, self.tile_m, self.h, self.y_perm, stream)

@@ -302,7 +302,7 @@ def _stage_check(torch, wl, inp, tol_scale=1.0):
     hdr = to_numpy(layer.plan_hdr)
     O.validate_tiles(to_numpy(layer.tiles)[:hdr[0]], hdr[4:4 + layer.n_bins + 1], p["counts"], p["offsets"],
                      layer.tile_m, layer.n_bins)
-    assert np.array_equal(to_numpy(layer.sched), O.schedule_balanced(p["counts"], layer.n_bins, layer.q_tokens, layer.tile_m))
+    assert np.array_equal(to_numpy(layer.sched), O.schedule_harmoeny(p["counts"], layer.n_bins, layer.q_tokens))
     ew = expert_dict(wl, inp)
     yp_o = O.grouped_ffn(xp, p["offsets"], ew, wl.act)
     tol = TOL[wl.dtype] * tol_scale
@@ -469,7 +469,7 @@ def test_full_size_workloads_sampled(torch_gpu, name, n_sample):
     assert np.array_equal(to_numpy(layer.inv_perm), inv)
     hdr = to_numpy(layer.plan_hdr)
     O.validate_tiles(to_numpy(layer.tiles)[:hdr[0]], hdr[4:4 + layer.n_bins + 1], counts, offsets, layer.tile_m, layer.n_bins)
-    assert np.array_equal(to_numpy(layer.sched), O.schedule_balanced(counts, layer.n_bins, layer.q_tokens, layer.tile_m))
+    assert np.array_equal(to_numpy(layer.sched), O.schedule_harmoeny(counts, layer.n_bins, layer.q_tokens))
     # sampled tokens
     r = np.random.default_rng(123)
     tok = set(r.choice(wl.T, n_sample, replace=False).tolist())
@@ -530,3 +530,43 @@ def test_ffn_top1_is_ffn_then_combine(torch_gpu, T, d, F, E, gate, skew):
         torch.cuda.synchronize()
         assert torch.equal(L.y, y_sep), rep
     assert int(L.plan_hdr[B.MOE_PLAN_HDR_CTR:].abs().sum()) == 0      # the work counters are back at zero
+
+
+@pytest.mark.parametrize("name,over", [("c2", dict(T=2048, d=128, F=512, E=16)), ("c4", dict(T=900, d=256, F=512, E=4)),
+                                       ("c1", {})])
+def test_plan_policies_give_the_same_layer_output(torch_gpu, name, over):
+    """The four schedules (section 5.3.2's comparison) run the same rows through the same kernels:
+    only which work-group takes which tile differs, so the layer output is bit-identical."""
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    wl = W.WORKLOADS[name].scaled(**over)
+    inp = W.make_inputs(wl)
+    layer = make_layer(wl, inp)
+    x = layer_x(layer, inp)
+    ref = layer.forward(x).clone()
+    torch.cuda.synchronize()
+    for pol in (B.MOE_PLAN_BALANCED, B.MOE_PLAN_STATIC, B.MOE_PLAN_EVEN_SPLIT):
+        layer.policy = pol
+        y = layer.forward(x)
+        torch.cuda.synchronize()
+        assert torch.equal(y, ref), pol
+
+
+@pytest.mark.parametrize("alpha,n_hot", [(0.0, 1), (0.5, 1), (0.9, 10), (0.95, 1)])
+def test_layer_with_sampled_ids_alpha_skew(torch_gpu, alpha, n_hot):
+    """Section 5.1's synthetic router (ids sampled, the first n_hot experts share probability
+    alpha): permute -> plan -> FFN -> combine on given ids against the oracle's layer."""
+    torch = torch_gpu
+    wl = W.WORKLOADS["c2"].scaled(T=3000, d=128, F=512, E=32)
+    inp = W.make_inputs(wl)
+    layer = make_layer(wl, inp)
+    x = layer_x(layer, inp)
+    ids = W.alpha_skew_ids(wl.T, wl.E, alpha, n_hot, 77)
+    layer.expert_idx.copy_(torch.from_numpy(ids).view(wl.T, 1))
+    layer.gate_w.fill_(1.0)
+    y = layer.forward(x, routed=True)
+    torch.cuda.synchronize()
+    p = O.permute(ids.reshape(-1, 1), wl.E)
+    assert np.array_equal(to_numpy(layer.counts), p["counts"]) and np.array_equal(to_numpy(layer.perm), p["perm"])
+    y_o = O.moe_layer(inp["x"], ids.reshape(-1, 1), np.ones((wl.T, 1)), expert_dict(wl, inp), wl.act)
+    assert max_err_over_rms(to_numpy(y), y_o) <= TOL[wl.dtype]

@@ -431,29 +431,34 @@ def test_schedule_policies_invariants():
             O.validate_tiles(tiles, bin_start, counts, offsets, tile_m, G)
             assert len(tiles) <= -(-int(counts.sum()) // tile_m) + E * G
         Sb = O.schedule_balanced(counts, G, q, tile_m)
-        # a split block keeps at least q rows in every part
-        for e in range(E):
+        tiles_of = lambda n: -(-int(n) // tile_m)
+        per_bin = np.array([[tiles_of(n) for n in row] for row in Sb]).sum(axis=0)
+        assert per_bin.max() - per_bin.min() <= 1                              # equal tile counts
+        assert per_bin.sum() <= sum(tiles_of(c) for c in counts)               # splitting in whole tiles adds none
+        for e in range(E):                                                      # at most one ragged part per expert
             parts = Sb[e][Sb[e] > 0]
-            assert len(parts) <= 1 or parts.min() >= min(q, counts[e])
+            assert (parts % tile_m != 0).sum() <= 1
         Se = O.schedule_even_split(counts, G)
         assert np.all(Se.max(axis=1) - Se.min(axis=1) <= 1)
 
 
 def test_schedule_balanced_splits_hot_expert_and_balances():
-    # one expert with half of all rows, 8 bins: its rows must be spread, bin weights near equal
+    # one expert with half of all rows, 8 bins: its rows must be spread, tile counts equal
     counts = np.array([8192, 2600, 1500, 1100, 900, 800, 700, 592])
     q, tile_m, G = 313, 128, 8
     S = O.schedule_balanced(counts, G, q, tile_m)
     assert (S[0] > 0).sum() >= 4
-    w = np.array([[O.block_weight(n, q) for n in row] for row in S]).sum(axis=0)
-    assert w.max() <= w.sum() // G + q + tile_m          # the loop stops when no bin has room for q more rows
+    per_bin = np.array([[-(-int(n) // tile_m) for n in row] for row in S]).sum(axis=0)
+    assert per_bin.max() - per_bin.min() <= 1 and per_bin.sum() == sum(-(-int(c) // tile_m) for c in counts)
     assert np.all(np.sort(S[0][S[0] > 0])[:-1] % tile_m == 0)   # moved parts are whole tiles
+    # worked by hand: tiles 4, 1, 1 on 2 bins -> LPT gives (4 | 1+1), one move of floor(2/2) = 1 tile
+    S = O.schedule_balanced(np.array([400, 100, 60]), 2, 1, 100)
+    assert S.tolist() == [[300, 100], [0, 100], [0, 60]]
     # uniform small experts: nothing to split, experts dealt evenly
     S = O.schedule_balanced(np.full(128, 128), 8, 313, 128)
     assert np.all((S > 0).sum(axis=1) == 1) and np.all((S > 0).sum(axis=0) == 16)
     # all rows on one expert: spread over all bins in whole tiles
     S = O.schedule_balanced(np.array([4096, 0, 0, 0]), 8, 313, 128)
-    assert (S[0] > 0).sum() == 8 and S[0].sum() == 4096
+    assert (S[0] > 0).sum() == 8 and S[0].sum() == 4096 and np.all(S[0] == 512)
     # static placement never splits; contiguous homes
     assert O.contiguous_home(6, 3) == [0, 0, 1, 1, 2, 2]
-    assert O.block_weight(0, 5) == 0 and O.block_weight(3, 5) == 5 and O.block_weight(9, 5) == 9
