@@ -278,6 +278,29 @@ def main():
             abl[name] = round(timed(max(10, args.steps // 2), 3, marks_on=False)[0], 4)
         layer.policy = B.MOE_PLAN_HARMOENY
         out["plan_ablation_ms_per_step"] = abl
+        # Alg. 2 in its three-dimensional form for 8 GPUs (the paper's deployment): this step's
+        # assignments as if they had arrived on 8 source GPUs (T/8 consecutive tokens each), experts
+        # housed in contiguous blocks.  One kernel, no host loop.
+        idx_h = layer.expert_idx.cpu().numpy().reshape(8, -1)
+        m_all = np.stack([np.bincount(idx_h[g], minlength=wl.E) for g in range(8)]).astype(np.int32)
+        S0 = np.zeros((8, wl.E, 8), dtype=np.int32)
+        for e in range(wl.E):
+            S0[:, e, e * 8 // wl.E] = m_all[:, e]
+        s_in = torch.from_numpy(S0).to(layer.device)
+        s_out, info = torch.empty_like(s_in), torch.zeros(4 + B.MOE_MAX_BINS, dtype=torch.int32, device=layer.device)
+        for _ in range(3):
+            B.moe_rebalance(s_in, 8, wl.E, 8, layer.q_tokens, s_out, info)
+        s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        s_ev.record()
+        for _ in range(20):
+            B.moe_rebalance(s_in, 8, wl.E, 8, layer.q_tokens, s_out, info)
+        e_ev.record()
+        torch.cuda.synchronize()
+        info_h = info.cpu().numpy()
+        out["alg2_8gpu_schedule"] = {"us_per_call": round(s_ev.elapsed_time(e_ev) / 20 * 1e3, 1), "moves": int(info_h[0]),
+                                     "loads_before": S0.sum(axis=(0, 1)).tolist(), "loads_after": info_h[4:12].tolist(),
+                                     "q_tokens": layer.q_tokens}
     if not args.no_ablation and wl.k == 1:
         # Section 5.1's synthetic router: the first n_hot experts share probability alpha, ids are
         # sampled per token; alpha changes from batch to batch (the dynamic-skew experiment).

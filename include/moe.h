@@ -166,6 +166,29 @@ MOE_API int moe_plan_tiles_subset(const int32_t* counts, const int32_t* offsets,
                    void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Alg. 2 (token rebalancing) as printed, for a group of G GPUs, on the device and without a host
+ * loop (section 4.2; the paper runs it as tensor operations driven by a host loop on every GPU
+ * and reports 20-31 % of the layer's time for it, section 5.3).
+ *
+ *   S[g_from, e, g_to] = tokens that GPU g_from sends to GPU g_to for expert e  (S_initial from
+ *   Alg. 1 step 3: everything goes to the expert's home GPU).
+ *   t_g = sum over g_from, e of S[., ., g];  t_avg = floor(sum S / G).  While some t_g > t_avg:
+ *   g_max = argmax t_g; g_from = the source sending most to g_max; e_max = its largest expert
+ *   block there, t_move its size; stop if t_move < q; g_min = argmin t_g; stop if g_min = g_max
+ *   or t_g[g_min] + q > t_avg; move t_s = min(t_move, t_avg - t_g[g_min]) tokens of that block
+ *   from g_max to g_min.  argmax / argmin take the lowest index among equals.
+ *
+ *   s_initial [G_src, E, G] int32 (device)     s_out [G_src, E, G] int32 (device; may alias s_initial)
+ *   info [4 + MOE_MAX_BINS] int32 (device) or NULL: [0] moves made, [1] t_avg, [2] why the loop
+ *        ended (0 no GPU above the average, 1 block below q, 2 no room on the least loaded GPU,
+ *        3 iteration cap), [4 ..] t_g afterwards
+ * Requires G_src, G <= MOE_MAX_BINS, E <= MOE_MAX_EXPERTS, q_tokens >= 1 and S at most 128 KiB.
+ * Entries must be non-negative with a total below 2^26.
+ */
+MOE_API int moe_rebalance(const int32_t* s_initial, int G_src, int E, int G, int q_tokens,
+                          int32_t* s_out, int32_t* info, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Weight layout of the FFN kernels.  The paper writes an expert as x W1 W2 with W1: d x F and
  * W2: F x d (section 4.4).  The kernels read every weight matrix "output-major": row n holds
  * the d (or F) input coefficients of output feature n, i.e. the transpose, so that the

@@ -29,7 +29,7 @@ MOE_PLAN_HDR_INTS = MOE_PLAN_HDR_CTR + MOE_MAX_BINS + 1
 MOE_OP_PERMUTE = 1
 
 EXPORTS = [
-    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_pack_weights", "moe_pack_w_out",
+    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_rebalance", "moe_pack_weights", "moe_pack_w_out",
     "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_grouped_ffn_top1", "moe_grouped_ffn_top1_phase", "moe_unpermute_combine", "moe_prefetch_create",
     "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_reset", "moe_prefetch_destroy",
     "moe_token_threshold", "moe_workspace_bytes", "moe_copy_bytes", "moe_last_error", "moe_version",
@@ -43,6 +43,7 @@ lib.moe_permute.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _v
 lib.moe_plan_capacity.argtypes = [_i, _i, _i, _i]
 lib.moe_plan_tiles.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp]
 lib.moe_plan_tiles_subset.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), _i, _vp, _i, _vp, _vp, _vp]
+lib.moe_rebalance.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp, _vp]
 lib.moe_pack_weights.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp]
 lib.moe_pack_w_out.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp]
 lib.moe_ffn_tile_m.argtypes = [_i]
@@ -163,6 +164,10 @@ def moe_plan_tiles_subset(counts, offsets, E, A, tile_m, n_bins, q_tokens, polic
     ids = (C.c_int32 * max(n, 1))(*expert_ids)
     _check(lib.moe_plan_tiles_subset(_p(counts), _p(offsets), E, A, tile_m, n_bins, q_tokens, policy, ids, n, _p(tiles),
                                      tile_capacity, _p(plan_hdr), _p(sched), _stream(stream)))
+
+
+def moe_rebalance(s_initial, G_src, E, G, q_tokens, s_out, info=None, stream=None):
+    _check(lib.moe_rebalance(_p(s_initial), G_src, E, G, q_tokens, _p(s_out), _p(info), _stream(stream)))
 
 
 def moe_pack_weights(w_a, w_b, n, K, N, dt, out, stream=None):

@@ -305,6 +305,81 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     if (tid <= MOE_MAX_BINS) hdr[MOE_PLAN_HDR_CTR + tid] = 0;     // work counters of the FFN kernels
 }
 
+
+// moe_rebalance: Alg. 2 as printed, with its three-dimensional schedule S[g_from][e][g_to], for
+// G GPUs.  One work-group; S lives in LDS; the loop runs in one wavefront with the destination
+// GPUs (then the source GPUs, then the experts) across its lanes.
+__global__ __launch_bounds__(NTH) void rebalance_kernel(const int32_t* __restrict__ s_in, int G_src, int E, int G, int q,
+                                                        int32_t* __restrict__ s_out, int32_t* __restrict__ info) {
+    extern __shared__ int Sx[];                              // [G_src][E][G]
+    __shared__ int from_load[MOE_MAX_BINS * MOE_MAX_BINS];   // [g_from][g_to] = sum_e S
+    __shared__ int load[MOE_MAX_BINS];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = G_src * E * G;
+    for (int i = tid; i < n; i += NTH) Sx[i] = s_in[i];
+    __syncthreads();
+    for (int p = tid; p < G_src * G; p += NTH) {
+        const int gf = p / G, g = p % G;
+        int sum = 0;
+        for (int e = 0; e < E; ++e) sum += Sx[(gf * E + e) * G + g];
+        from_load[gf * MOE_MAX_BINS + g] = sum;
+    }
+    __syncthreads();
+    if (tid < G) {
+        int sum = 0;
+        for (int gf = 0; gf < G_src; ++gf) sum += from_load[gf * MOE_MAX_BINS + tid];
+        load[tid] = sum;
+    }
+    __syncthreads();
+    if (tid < 64) {
+        int tg = lane < G ? load[lane] : 0;
+        const int t_avg = (int)(moe_wave_sum_u32((unsigned)tg) / (unsigned)G);
+        int moves = 0, why = 0;                              // why the loop ended: 0 balanced, 1 block < q, 2 no room, 3 cap
+        const int max_iters = n + 16;
+        int it = 0;
+        for (; it < max_iters; ++it) {
+            int g_max, t_max;
+            argmax_bin(tg, lane, G, g_max, t_max);
+            if (t_max <= t_avg) break;
+            // the source GPU that sends most to g_max, then its largest expert block there
+            int g_from, f_max;
+            argmax_bin(lane < G_src ? from_load[lane * MOE_MAX_BINS + g_max] : 0, lane, G_src, g_from, f_max);
+            int best = -1;
+            for (int e = lane; e < E; e += 64) {
+                const int sv = Sx[(g_from * E + e) * G + g_max];
+                best = sv > best ? sv : best;
+            }
+            const int t_move = (int)moe_wave_max_u32((unsigned)(best + 1)) - 1;
+            unsigned first = 0xffffffffu;
+            for (int e = lane; e < E; e += 64)
+                if (Sx[(g_from * E + e) * G + g_max] == t_move) { first = (unsigned)e; break; }
+            const int e_max = (int)moe_wave_min_u32(first);
+            if (t_move < q) { why = 1; break; }
+            int g_min, t_min;
+            argmin_bin(tg, lane, G, g_min, t_min);
+            if (g_min == g_max || t_min + q > t_avg) { why = 2; break; }
+            const int t_s = t_move < t_avg - t_min ? t_move : t_avg - t_min;
+            if (lane == 0) {
+                Sx[(g_from * E + e_max) * G + g_max] -= t_s;
+                Sx[(g_from * E + e_max) * G + g_min] += t_s;
+                from_load[g_from * MOE_MAX_BINS + g_max] -= t_s;
+                from_load[g_from * MOE_MAX_BINS + g_min] += t_s;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            if (lane == g_max) tg -= t_s;
+            if (lane == g_min) tg += t_s;
+            ++moves;
+        }
+        if (it == max_iters) why = 3;
+        if (info) {
+            if (lane == 0) { info[0] = moves; info[1] = t_avg; info[2] = why; }
+            if (lane < G) info[4 + lane] = tg;
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < n; i += NTH) s_out[i] = Sx[i];
+}
+
 }  // namespace
 
 extern "C" int moe_plan_capacity(int A, int E, int tile_m, int n_bins) {
@@ -355,4 +430,24 @@ extern "C" int moe_plan_tiles_subset(const int32_t* counts, const int32_t* offse
     }
     return plan_impl("moe_plan_tiles_subset", counts, offsets, E, A, tile_m, n_bins, q_tokens, policy, m, tiles,
                      tile_capacity, plan_hdr, sched, stream);
+}
+
+extern "C" int moe_rebalance(const int32_t* s_initial, int G_src, int E, int G, int q_tokens, int32_t* s_out, int32_t* info,
+                             void* stream) {
+    MOE_REQUIRE(G_src >= 1 && G_src <= MOE_MAX_BINS && G >= 1 && G <= MOE_MAX_BINS, MOE_ERR_ARG,
+                "moe_rebalance: G_src=%d G=%d outside [1,%d]", G_src, G, MOE_MAX_BINS);
+    MOE_REQUIRE(E >= 1 && q_tokens >= 1, MOE_ERR_ARG, "moe_rebalance: E=%d q_tokens=%d must be >= 1", E, q_tokens);
+    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "moe_rebalance: E=%d > %d", E, MOE_MAX_EXPERTS);
+    const size_t bytes = (size_t)G_src * E * G * sizeof(int32_t);
+    MOE_REQUIRE(bytes <= 128 * 1024, MOE_ERR_UNSUPPORTED, "moe_rebalance: S of %zu bytes does not fit the work-group's memory", bytes);
+    MOE_REQUIRE(s_initial && s_out, MOE_ERR_ARG, "moe_rebalance: null pointer");
+    if (bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(rebalance_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return moe_fail(MOE_ERR_HIP, "moe_rebalance: shared memory attribute: %s", hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(rebalance_kernel, dim3(1), dim3(NTH), bytes, (hipStream_t)stream, s_initial, G_src, E, G, q_tokens,
+                       s_out, info);
+    MOE_CHECK_LAUNCH("moe_rebalance");
+    return MOE_OK;
 }

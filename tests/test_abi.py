@@ -141,6 +141,10 @@ def test_pack_combine_copy_argument_errors():
     assert status(B.moe_pack_weights, FAKE, FAKE, 1, 8, 48, B.MOE_F32, FAKE, 0) == B.MOE_ERR_UNSUPPORTED   # N % 32
     assert status(B.moe_pack_weights, None, None, 1, 8, 8, B.MOE_F32, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_pack_weights, None, None, 0, 8, 8, B.MOE_F32, None, 0) == B.MOE_OK
+    reb = lambda s_in=FAKE, Gs=8, E=128, G=8, q=1, s_out=FAKE: status(B.moe_rebalance, s_in, Gs, E, G, q, s_out, None, 0)
+    assert reb(Gs=0) == B.MOE_ERR_ARG and reb(G=17) == B.MOE_ERR_ARG and reb(q=0) == B.MOE_ERR_ARG
+    assert reb(E=257) == B.MOE_ERR_UNSUPPORTED and reb(Gs=16, E=256, G=16) == B.MOE_ERR_UNSUPPORTED
+    assert reb(s_in=None) == B.MOE_ERR_ARG and reb(s_out=None) == B.MOE_ERR_ARG
     assert status(B.moe_pack_w_out, FAKE, 1, 0, 8, B.MOE_BF16, FAKE, 0) == B.MOE_ERR_ARG
     top1 = lambda dt, F, perm, y: status(B.moe_grouped_ffn_top1, FAKE, 8, 64, F, 2, B.MOE_RELU, dt, FAKE, FAKE, FAKE, FAKE,
                                          128, FAKE, perm, None, y, 0)

@@ -570,3 +570,46 @@ def test_layer_with_sampled_ids_alpha_skew(torch_gpu, alpha, n_hot):
     assert np.array_equal(to_numpy(layer.counts), p["counts"]) and np.array_equal(to_numpy(layer.perm), p["perm"])
     y_o = O.moe_layer(inp["x"], ids.reshape(-1, 1), np.ones((wl.T, 1)), expert_dict(wl, inp), wl.act)
     assert max_err_over_rms(to_numpy(y), y_o) <= TOL[wl.dtype]
+
+
+def test_rebalance_three_dimensional_schedule(torch_gpu):
+    """moe_rebalance (Alg. 2 with S[g_from, e, g_to]) against the oracle's step-by-step loop:
+    the paper's 15-token example with its thresholds, and random Zipf-like count matrices up to
+    8 GPUs x 128 experts."""
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    dev = torch.device("cuda:0")
+
+    def run(S0, q):
+        G_src, E, G = S0.shape
+        s_in = torch.from_numpy(S0.astype(np.int32)).to(dev)
+        s_out = torch.full_like(s_in, -1)
+        info = torch.full((4 + B.MOE_MAX_BINS,), -1, dtype=torch.int32, device=dev)
+        B.moe_rebalance(s_in, G_src, E, G, q, s_out, info)
+        torch.cuda.synchronize()
+        return to_numpy(s_out).astype(np.int64), to_numpy(info)
+
+    m_all = np.array([[1, 1, 3], [1, 2, 2], [0, 1, 4]])                 # tests/golden/alg2_example.txt
+    S0 = O.initial_assign(m_all, [0, 1, 2], 3)
+    for q, loads in ((1, [5, 5, 5]), (3, [5, 4, 6]), (4, [2, 4, 9]), (5, [2, 4, 9])):
+        S, info = run(S0, q)
+        assert np.array_equal(S, O.rebalance(S0, q)) and S.sum(axis=(0, 1)).tolist() == loads
+        assert info[1] == 5 and info[4:7].tolist() == loads
+    r = np.random.default_rng(41)
+    for trial in range(24):
+        G = int(r.choice([1, 2, 3, 5, 8, 16]))
+        G_src = G if trial % 3 else int(r.integers(1, 9))
+        E = int(r.choice([G, 17, 60, 128, 256])) if trial % 2 else int(r.integers(G, 64))
+        if G_src * E * G * 4 > 128 * 1024:
+            E = 64
+        q = int(r.choice([1, 7, 64, 300]))
+        m = (r.zipf(1.4, size=(G_src, E)) * 11 % 900).astype(np.int64)
+        m[r.random((G_src, E)) < 0.15] = 0
+        home = [e * G // E for e in range(E)]
+        S0 = O.initial_assign(m, home, G)
+        _note("rebalance trial %d G_src=%d E=%d G=%d q=%d" % (trial, G_src, E, G, q))
+        S, info = run(S0, q)
+        ref = O.rebalance(S0, q)
+        assert np.array_equal(S, ref), (trial, G_src, E, G, q)
+        assert np.array_equal(info[4:4 + G], ref.sum(axis=(0, 1)))
+        assert np.array_equal(S.sum(axis=2), m)                          # every token still goes to its expert
