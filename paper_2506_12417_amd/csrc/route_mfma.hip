@@ -382,19 +382,25 @@ __global__ __launch_bounds__(NTH) void route_mfma_kernel(const uint16_t* __restr
 
 // =========================================================================================
 // Router with a prepared W_g (moe_pack_router): W_g^T [E,d], so the contraction index is
-// contiguous for both operands and MFMA fragments can be fetched straight from global memory,
-// 16 bytes per lane, with no LDS staging and no barrier in the main loop.
+// contiguous for both operands.  Both are staged through LDS by global -> LDS loads of whole
+// 128-byte lines (a stage = 64 * KSP contraction terms of the 32 tokens and of all experts; three or
+// four stages in flight, one barrier per stage), and the MFMA fragments are read from there.
+// (Fetching the fragments straight from global memory, 16 bytes per lane, touched 32 lines per
+// load for 32 bytes each and left the kernel waiting on the vector cache: 20 us of its 34 on
+// 16384 tokens x 768.)
 //
 // One work-group = 32 tokens.  Its wavefronts split the experts into blocks of 32 (NB blocks)
 // and, when there are fewer than four blocks, also the contraction (KSP parts): wavefront
 // (block, part) takes the 64-term chunks part, part+KSP, ... for its 32 experts.  A wavefront's
 // fp32 MFMA accumulator collects up to KACC terms before it is added into fp64 sums (same error
 // model as above, with KACC-term chunks); the KSP partial sums are added in a fixed order
-// through LDS.  Fragments are prefetched two chunks ahead (three register sets).  A wavefront
-// needs about 180 registers and the work-group at most 64 KB of LDS, so two work-groups share
-// a CU and hide each other's load latency.
+// through LDS.  The staging ring shares its LDS with the buffers of the later phases.
 typedef __attribute__((ext_vector_type(4))) unsigned int frag_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((address_space(3))) void lds_void_t;
+constexpr int ROUTE_RING = 3;          // stages of the prepared-router kernel's staging ring
+// s_waitcnt on vmcnt only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
+#define MOE_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
 // (the body is a __device__ function: buffer-descriptor types exist on the device side only)
 template <int NB, int KSP, int RMAX>   // expert blocks, contraction parts, depth of the top list (>= k + 1)
@@ -407,7 +413,7 @@ __device__ __forceinline__ void route_packed_body(const uint16_t* __restrict__ x
     constexpr int SLAB = KSP > 1 ? KSP * TB * EPT * 8 : 0;
     constexpr int CAND = NWV * (MOE_MAX_EXPERTS + 32) * 12;
     constexpr int REGION0 = SLAB > CAND ? SLAB : CAND;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     // LDS: fp64 slabs [KSP][32][EPT] for the sum over the contraction parts (later the exact path's
     // candidate lists), the fp32 logits [32][PL], partial token norms, flags
     double* slab = reinterpret_cast<double*>(smem);
@@ -425,15 +431,7 @@ __device__ __forceinline__ void route_packed_body(const uint16_t* __restrict__ x
     const int nbi = wave / KSP, ksi = wave % KSP;    // this wavefront's expert block and contraction part
     const int t0 = blockIdx.x * TB;
     const int n_chunks = d / KC;
-    if (tid == 0) *n_flag = 0;
-
     const int rows = T - t0 < TB ? T - t0 : TB;
-    const int e_left = E - nbi * 32;
-    const __amdgpu_buffer_rsrc_t rx =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x + (size_t)t0 * d), 0, rows * d * 2, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t*>(wgt + (size_t)nbi * 32 * d), 0, (e_left < 0 ? 0 : (e_left < 32 ? e_left : 32)) * d * 2, 0x00020000);
-    const unsigned voff = (unsigned)l32 * (unsigned)d * 2u + (unsigned)lhi * 16u;
     float xsq = 0.f;
 
     double acc64[16];
@@ -453,46 +451,95 @@ __device__ __forceinline__ void route_packed_body(const uint16_t* __restrict__ x
     };
     clear_acc();
 
-    constexpr int NSETS = 3;
-    frag_t xa[NSETS][KC / 16], wb[NSETS][KC / 16];
-    auto load_set = [&](auto sc, int c) {            // chunk c of the contraction into register set s
-        constexpr int s = decltype(sc)::value;
-        const unsigned so = (unsigned)c * (KC * 2);
+    // ---- staging.  Stage s holds the chunks s*KSP ... s*KSP+KSP-1: for each, 32 token rows, then
+    // for each EPT expert rows, every row one 128-byte line (64 terms) in eight 16-byte pieces,
+    // piece p of row r at position p ^ ((r / 2) & 7) (conflict-free fragment reads).  A load moves
+    // eight rows (lane = row * 8 + position); the loads of a stage are dealt to the wavefronts,
+    // every wavefront issues the same number (LPW) per stage -- the surplus ones, and all loads
+    // past the last stage, with an empty descriptor -- so the count of outstanding loads that
+    // guarantees a stage is a constant.
+    constexpr int SROWS = (TB + EPT) * KSP, NL = SROWS / 8, LPW = (NL + NWV - 1) / NWV;
+    constexpr int STAGE = SROWS * 128;
+    constexpr int RING = ROUTE_RING;
+    static_assert(LPW * (RING - 1) < 64 && RING * STAGE + 1024 <= 150 * 1024, "staging ring");
+    unsigned char* ring = smem;
+    unsigned char* dump = smem + RING * STAGE;               // 1 KB where the surplus loads' zeros go
+    const int n_stages = (n_chunks + KSP - 1) / KSP;
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x + (size_t)t0 * d), 0, rows * d * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(wgt), 0, E * d * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rnull = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x), 0, 0, 0x00020000);
+    const int ld_r = lane >> 3, ld_p = lane & 7;
+    auto issue_stage = [&](int st) {
+        unsigned char* buf = ring + (st % RING) * STAGE;
 #pragma unroll
-        for (int ks = 0; ks < KC / 16; ++ks) {
-            xa[s][ks] = __builtin_amdgcn_raw_buffer_load_b128(rx, voff, so + ks * 32, 0);
-            wb[s][ks] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, so + ks * 32, 0);
+        for (int i = 0; i < LPW; ++i) {
+            const int L = wave + i * NWV;                    // (wave-uniform)
+            const int R = L * 8;                             // first stage row of this load
+            const int sub = R / (TB + EPT);                  // chunk of the stage
+            const int rr = R - sub * (TB + EPT);             // row inside the chunk: tokens, then experts
+            const int c = st * KSP + sub;
+            const bool live = L < NL && st < n_stages && c < n_chunks;
+            const bool is_x = rr < TB;
+            const int row = (is_x ? rr : rr - TB) + ld_r;    // token of the tile / expert
+            const unsigned voff = (unsigned)row * (unsigned)d * 2u + (unsigned)((ld_p ^ (((rr + ld_r) >> 1) & 7)) << 4);
+            lds_void_t* to = (lds_void_t*)(L < NL ? buf + R * 128 : dump);
+            const unsigned soff = (unsigned)c * 128u;
+            // (three calls under wave-uniform branches: a descriptor chosen by a conditional
+            // expression is kept in memory by the compiler and reloaded, with a full wait, per load)
+            if (live && is_x) __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, to, 16, voff, soff, 0, 0);
+            else if (live) __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, to, 16, voff, soff, 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rnull, to, 16, voff, soff, 0, 0);
         }
     };
-    auto step = [&](auto sc, int c) {                // multiply set s (chunk c), then refill it
-        constexpr int s = decltype(sc)::value;
 #pragma unroll
-        for (int ks = 0; ks < KC / 16; ++ks) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[s][ks]),
-                                                          __builtin_bit_cast(bf16x8, wb[s][ks]), acc, 0, 0, 0);
-            if (nbi == 0) {                          // the token norms, once per contraction part
+    for (int st = 0; st < RING - 1; ++st) issue_stage(st);
+    const int frag_at = l32 * 128;
+    const int frag_sw = (l32 >> 1) & 7;
+    for (int st = 0; st < n_stages; ++st) {
+        // stage st has landed once only the RING-2 younger stages are outstanding
+        if (RING == 4) MOE_WAIT_VMCNT(2 * LPW);
+        else if (RING == 3) MOE_WAIT_VMCNT(LPW);
+        else MOE_WAIT_VMCNT(0);
+        // ... for every wavefront after the barrier; and stage st-1 has been read by all.  (A bare
+        // barrier: __syncthreads would first wait for every load in flight, the prefetched stages too.)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" ::: "memory");
+        issue_stage(st + RING - 1);                          // into the buffer of stage st-1
+        const int c = st * KSP + ksi;
+        if (c < n_chunks) {
+            const unsigned char* xb = ring + (st % RING) * STAGE + ksi * (TB + EPT) * 128;
+            const unsigned char* wb_ = xb + (TB + nbi * 32) * 128;
+            frag_t xa[KC / 16], wb[KC / 16];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const bf16x2 p2 = __builtin_bit_cast(bf16x2, xa[s][ks][i]);
-                    xsq = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, xsq, false);
+            for (int ks = 0; ks < KC / 16; ++ks) {
+                const int pos = ((ks * 2 + lhi) ^ frag_sw) << 4;
+                xa[ks] = *(const frag_t*)(xb + frag_at + pos);
+                wb[ks] = *(const frag_t*)(wb_ + frag_at + pos);
+            }
+#pragma unroll
+            for (int ks = 0; ks < KC / 16; ++ks) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[ks]),
+                                                              __builtin_bit_cast(bf16x8, wb[ks]), acc, 0, 0, 0);
+                if (nbi == 0) {                              // the token norms, once per contraction part
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const bf16x2 p2 = __builtin_bit_cast(bf16x2, xa[ks][i]);
+                        xsq = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, xsq, false);
+                    }
                 }
             }
+            if (++in_acc == KACC / KC) flush_acc();
         }
-        if (c + KSP * NSETS < n_chunks) load_set(sc, c + KSP * NSETS);
-        if (++in_acc == KACC / KC) flush_acc();
-    };
-    using S0 = std::integral_constant<int, 0>;
-    using S1 = std::integral_constant<int, 1>;
-    using S2 = std::integral_constant<int, 2>;
-    if (ksi < n_chunks) load_set(S0{}, ksi);
-    if (ksi + KSP < n_chunks) load_set(S1{}, ksi + KSP);
-    if (ksi + 2 * KSP < n_chunks) load_set(S2{}, ksi + 2 * KSP);
-    for (int c = ksi; c < n_chunks; c += KSP * NSETS) {
-        step(S0{}, c);
-        if (c + KSP < n_chunks) step(S1{}, c + KSP);
-        if (c + 2 * KSP < n_chunks) step(S2{}, c + 2 * KSP);
     }
     if (in_acc) flush_acc();
+    MOE_WAIT_VMCNT(0);                                       // (the trailing empty loads still target this LDS)
+    __syncthreads();                                         // the ring's memory is reused below
+    if (tid == 0) *n_flag = 0;
 
     // ---- logits.  acc64[r]: token 8*(r/4) + 4*lhi + r%4, expert nbi*32 + l32.
     if (KSP > 1) {                                   // the partial sums of the contraction parts, fixed order
@@ -713,7 +760,9 @@ int launch_packed_r(const void* x, const void* wgt, const float* w_norm2, const 
                     int renorm, int32_t* idx, float* w, float* logits, hipStream_t st) {
     constexpr int NWV = NB * KSP, EPT = 32 * NB;
     constexpr size_t slab = KSP > 1 ? (size_t)KSP * 32 * EPT * 8 : 0, cand = (size_t)NWV * (MOE_MAX_EXPERTS + 32) * 12;
-    const size_t smem = (slab > cand ? slab : cand) + (size_t)32 * (EPT + 4) * 4 + KSP * 32 * 4 + 4 * 32 * 4 + 2 * NWV * 4 + 16;
+    const size_t later = (slab > cand ? slab : cand) + (size_t)32 * (EPT + 4) * 4 + KSP * 32 * 4 + 4 * 32 * 4 + 2 * NWV * 4 + 16;
+    const size_t ring = (size_t)ROUTE_RING * (32 + EPT) * KSP * 128 + 1024;       // the staging ring and the later buffers share LDS
+    const size_t smem = ring > later ? ring : later;
     auto kern = route_packed_kernel<NB, KSP, RMAX>;
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
