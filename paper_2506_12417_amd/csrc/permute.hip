@@ -55,12 +55,50 @@ __global__ __launch_bounds__(NTH) void scan_kernel(int32_t* __restrict__ block_h
     }
 }
 
-__global__ __launch_bounds__(NTH) void rank_kernel(const int32_t* __restrict__ idx, int A, int E, int nbits,
+// SCAN: block_hist holds the raw per-block histograms and this kernel does step 2 itself (every
+// work-group sums the histograms of the blocks before it and of all blocks, and scans the totals;
+// the first one also writes counts and offsets): one launch less when the blocks are few.
+template <bool SCAN>
+__global__ __launch_bounds__(NTH) void rank_kernel(const int32_t* __restrict__ idx, int A, int E, int nbits, int nb,
                                                    const int32_t* __restrict__ block_hist,
-                                                   const int32_t* __restrict__ offsets,
+                                                   int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
                                                    int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
     extern __shared__ int chunk_hist[];   // [CHUNKS][E]
+    __shared__ int start_of[MOE_MAX_EXPERTS];      // first position of this work-group's assignments of expert e
+    __shared__ int scan_buf[2][MOE_MAX_EXPERTS];
     for (int i = threadIdx.x; i < CHUNKS * E; i += NTH) chunk_hist[i] = 0;
+    if (SCAN) {
+        static_assert(NTH >= MOE_MAX_EXPERTS, "one thread per expert");
+        const int e = threadIdx.x;
+        int before = 0, total = 0;
+        if (e < E)
+            for (int b = 0; b < nb; ++b) {
+                const int v = block_hist[(size_t)b * E + e];
+                before += b < (int)blockIdx.x ? v : 0;
+                total += v;
+            }
+        // inclusive scan of the totals over the experts (Hillis-Steele, MOE_MAX_EXPERTS entries)
+        scan_buf[0][e] = e < E ? total : 0;
+        __syncthreads();
+        int cur = 0;
+        for (int step = 1; step < MOE_MAX_EXPERTS; step <<= 1) {
+            const int v = scan_buf[cur][e] + (e >= step ? scan_buf[cur][e - step] : 0);
+            scan_buf[cur ^ 1][e] = v;
+            cur ^= 1;
+            __syncthreads();
+        }
+        const int incl = scan_buf[cur][e];
+        if (e < E) {
+            start_of[e] = incl - total + before;
+            if (blockIdx.x == 0) {
+                counts[e] = total;
+                offsets[e] = incl - total;
+                if (e == E - 1) offsets[E] = incl;
+            }
+        }
+    } else {
+        for (int e = threadIdx.x; e < E; e += NTH) start_of[e] = offsets[e] + block_hist[(size_t)blockIdx.x * E + e];
+    }
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int base = blockIdx.x * PB;
@@ -86,7 +124,7 @@ __global__ __launch_bounds__(NTH) void rank_kernel(const int32_t* __restrict__ i
     }
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += NTH) {
-        int run = offsets[e] + block_hist[(size_t)blockIdx.x * E + e];
+        int run = start_of[e];
         for (int c = 0; c < CHUNKS; ++c) {
             int v = chunk_hist[c * E + e];
             chunk_hist[c * E + e] = run;
@@ -141,11 +179,20 @@ extern "C" int moe_permute(const void* x, const int32_t* expert_idx, int T, int 
 
     hipLaunchKernelGGL(hist_kernel, dim3(nb), dim3(NTH), 0, st, expert_idx, A, E, block_hist);
     MOE_CHECK_LAUNCH("moe_permute/hist");
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(NTH), 0, st, block_hist, nb, E, counts, offsets);
-    MOE_CHECK_LAUNCH("moe_permute/scan");
+    // With few blocks every rank work-group repeats the scan itself (one launch less); with many
+    // blocks, or nothing to rank, the scan is a launch of its own.
+    const bool fused_scan = A > 0 && nb <= 64;
+    if (!fused_scan) {
+        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(NTH), 0, st, block_hist, nb, E, counts, offsets);
+        MOE_CHECK_LAUNCH("moe_permute/scan");
+    }
     if (A == 0) return MOE_OK;
-    hipLaunchKernelGGL(rank_kernel, dim3(nb), dim3(NTH), sizeof(int) * CHUNKS * E, st, expert_idx, A, E, nbits,
-                       block_hist, offsets, perm, inv_perm);
+    if (fused_scan)
+        hipLaunchKernelGGL(rank_kernel<true>, dim3(nb), dim3(NTH), sizeof(int) * CHUNKS * E, st, expert_idx, A, E, nbits, nb,
+                           block_hist, counts, offsets, perm, inv_perm);
+    else
+        hipLaunchKernelGGL(rank_kernel<false>, dim3(nb), dim3(NTH), sizeof(int) * CHUNKS * E, st, expert_idx, A, E, nbits, nb,
+                           block_hist, counts, offsets, perm, inv_perm);
     MOE_CHECK_LAUNCH("moe_permute/rank");
     if (x) {
         const int vpr = (int)((size_t)d * moe_elem_size(dt) / 16);

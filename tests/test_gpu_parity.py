@@ -114,7 +114,7 @@ def test_route_near_ties_bf16_both_entry_points(torch_gpu):
 
 
 PERMUTE_CASES = [(1, 1, 1, 8), (256, 2, 8, 64), (1000, 1, 128, 32), (5000, 4, 60, 16), (3, 2, 256, 8),
-                 (4097, 1, 7, 128), (16384, 1, 128, 768)]
+                 (4097, 1, 7, 128), (16384, 1, 128, 768), (35000, 2, 200, 8)]   # the last: more than 64 blocks
 
 
 @pytest.mark.parametrize("T,k,E,d", PERMUTE_CASES)
