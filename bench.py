@@ -337,7 +337,7 @@ def main():
         n_tok = wl.T if args.workload == "c2" else 1024
         tok = None if n_tok == wl.T else np.sort(np.random.default_rng(1).choice(wl.T, n_tok, replace=False))
         passes, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and passes < 5:
+        while t_cpu < 12.0 and passes < 20:
             t1 = time.time()
             idx_o, w_o, _ = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
             O.permute(idx_o, wl.E)
