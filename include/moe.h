@@ -247,7 +247,8 @@ MOE_API int moe_pack_w_out(const void* w, int n, int F, int d, moe_dtype dt, voi
  */
 MOE_API int moe_ffn_tile_m(moe_dtype dt);
 /* bf16 has two tile heights, 128 and 256 rows; this picks one from the mean rows per expert
- * (256 once A/E >= 512).  Plan and FFN must be given the same value. */
+ * (256 once A/E >= 1024: under skewed routing most experts hold far fewer rows than the mean, and
+ * their tiles are mostly empty at 256 rows).  Plan and FFN must be given the same value. */
 MOE_API int moe_ffn_pick_tile_m(moe_dtype dt, int A, int E);
 
 MOE_API int moe_grouped_ffn(const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,

@@ -124,7 +124,7 @@ extern "C" int moe_ffn_tile_m(moe_dtype dt) { return dt == MOE_BF16 ? 128 : FM; 
 // bf16 has two tile heights: 256 rows pay off when the experts hold many rows each
 extern "C" int moe_ffn_pick_tile_m(moe_dtype dt, int A, int E) {
     if (dt != MOE_BF16) return FM;
-    return (E >= 1 && A / E >= 512) ? 256 : 128;
+    return (E >= 1 && A / E >= 1024) ? 256 : 128;
 }
 
 // top1: step 6 folded into the second product (perm: output row of every row; gate_w may be null)

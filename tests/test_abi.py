@@ -90,6 +90,7 @@ def test_workspace_and_capacity_closed_forms():
     assert B.moe_ffn_tile_m(B.MOE_BF16) == 128 and B.moe_ffn_tile_m(B.MOE_F32) == 64
     assert B.moe_ffn_pick_tile_m(B.MOE_BF16, 16384, 128) == 128
     assert B.moe_ffn_pick_tile_m(B.MOE_BF16, 16384, 8) == 256
+    assert B.moe_ffn_pick_tile_m(B.MOE_BF16, 32768, 60) == 128
     assert B.moe_ffn_pick_tile_m(B.MOE_F32, 16384, 8) == 64
 
 
