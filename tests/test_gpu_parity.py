@@ -329,6 +329,12 @@ LAYER_CASES = [
     ("c2", dict(T=2048, d=768, F=3072, E=8)),
     ("c3", dict(T=700, d=256, F=192, E=12, shared_F=320)),
     ("c4", dict(T=900, d=512, F=1024, E=4)),
+    # many tiny experts (most tiles hold a few rows, many stay empty), top-2, the on-demand hand-out at work
+    ("c2", dict(T=1200, d=256, F=512, E=256, k=2)),
+    # one token; a hot expert holding nearly everything (256-row tiles, fixed stride); top-1 with the folded combine
+    ("c2", dict(T=1, d=64, F=512, E=4)),
+    ("c4", dict(T=4200, d=256, F=512, E=2, k=1)),
+    ("c2", dict(T=5000, d=192, F=1024, E=24)),
 ]
 
 
