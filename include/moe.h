@@ -200,6 +200,10 @@ MOE_API int moe_rebalance(const int32_t* s_initial, int G_src, int E, int G, int
  *        rows per matrix, in blocks of 32 rows: block 2j holds outputs [32j, 32j+32) of w_a,
  *        block 2j+1 the same outputs of w_b.  Requires N % 32 == 0.
  *   out  [n, N or 2N, K] dt
+ * MOE_BF16 also orders the rows inside every block of 32 for the 16x16x32 matrix instruction of
+ * the FFN kernels: packed row 16 h + j of a block holds the block's output 2 j + h (h = 0, 1;
+ * j = 0 .. 15), so that a lane's two accumulator columns are adjacent outputs.  Requires
+ * N % 32 == 0 then.  MOE_F32 keeps the outputs in order.
  */
 MOE_API int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int N, moe_dtype dt,
                      void* out, void* stream);
@@ -208,7 +212,8 @@ MOE_API int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int
  * 4.4), in the number format the second product of moe_grouped_ffn reads:
  *
  *   w   [n, F, d] dt
- *   out [n, d, F]   MOE_F32: fp32 as given.  MOE_BF16: every value converted to IEEE half
+ *   out [n, d, F]   MOE_F32: fp32 as given.  MOE_BF16: rows ordered as by moe_pack_weights
+ *        (d % 32 == 0) and every value converted to IEEE half
  *        (binary16, nearest-even).  That is exact for bf16 values of magnitude 2^-14 .. 65504;
  *        smaller ones are rounded to the half subnormals (absolute error <= 2^-25), larger ones
  *        become infinite.  The kernels keep the hidden activations in half as well (see

@@ -11,6 +11,14 @@
 // which is exact for every bf16 weight of magnitude 2^-14 .. 65504.  Both matrix instructions
 // run at the same rate and accumulate in fp32.
 //
+// The matrix instruction is v_mfma_f32_16x16x32 (bf16 or f16).  Under real data the chip's
+// arithmetic rate is set by its power limit, and this shape sustains about 8 % more than
+// 32x32x16 in a loop of nothing else; the kernel as a whole gains about 3 % from it.  A lane
+// then holds column l16 of a 16-column sub-block; moe_pack_weights orders the weight rows so
+// that the two sub-blocks of a 32-column block give the lane two adjacent outputs (packed row
+// 16 h + j of every 32 = output 2 j + h), which it stores as one pair without any exchange
+// between lanes, and the operand loads stay plain runs of consecutive rows.
+//
 // Persistent launch, one work-group of 8 wavefronts (2 per SIMD) per CU.  Work-group b serves
 // bin b % n_bins: work-groups are dealt round-robin to the 8 XCDs, so a bin's tiles -- and with
 // them an expert's weights -- stay inside one XCD's L2.  Inside a bin the work items
@@ -46,7 +54,7 @@
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
@@ -136,7 +144,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                                                const int32_t* __restrict__ row_token,
                                                const float* __restrict__ row_gate, int out_rows) {
     using C = Cfg<BM, BN, BK, RING, WM, WN, CS>;
-    constexpr int MI = C::MI, NI = C::NI, KS = C::KS, PH = C::PH;
+    constexpr int MI = C::MI, NI = C::NI, PH = C::PH;
     // The first product takes bf16 operands and writes the hidden activations as IEEE half; the
     // second one (plain store of fp32 results) takes those and a half copy of the weights.
     // SCATTER is STORE with Alg. 1's step 6 folded in for top-1 routing: row r goes to output row
@@ -150,7 +158,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // tile, so that a ragged tile leaves both wavefronts of a SIMD the same amount of work.
     const int wm = wave / C::WN, wn = wave % C::WN;
     const int grp = wm;
-    const int l32 = lane & 31, lhi = lane >> 5;
+    const int l16 = lane & 15, lq = lane >> 4;               // 16x16x32 fragments: row / column l16, 8-term group lq
     const int n_col_blocks = (N + BN - 1) / BN;
     const int KT = K / BK;
 
@@ -292,33 +300,39 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         issue_done();
     };
 
-    // ---- operand fragment reads.  Row r of a 32-row block is read by lanes r and r + 32 (the
-    // two 8-wide halves of a 16-wide slice); the swizzle depends on r % 32 only.  Row block mi of
-    // this wavefront is block mi * WM + wm of the tile.
-    // Slice ks of a row is piece (2 ks + lhi) ^ swz = (2 ks) ^ (lhi ^ swz), and every row and stage
-    // starts on a multiple of the row size: the address of slice ks is the address of slice 0 with
-    // bits flipped, so one per-lane register (and one XOR per read) serves all slices.  The B rows
-    // of lane l32 sit a wave-uniform distance behind its A rows, with the same swizzle.
+    // ---- operand fragment reads.  The matrix instruction is 16x16x32 (it draws about 8 % less
+    // power per FLOP than 32x32x16 on this chip, and power is what bounds the arithmetic): lane
+    // (l16, lq) supplies row l16 of a 16-row block, terms 8 lq .. 8 lq + 7 of a 32-term slice.  A
+    // 32x32 block of the output is four 16x16 sub-blocks [a][b]; row block mi of this wavefront is
+    // block mi * WM + wm of the tile.
+    // Slice q of a row is piece (4 q + lq) ^ swz = (4 q) ^ (lq ^ swz), and every row and stage starts
+    // on a multiple of the row size: the address of slice q is the address of slice 0 with bits
+    // flipped, so one per-lane register (and one XOR per read) serves all slices.  The swizzle
+    // repeats every 16 rows, and the B rows of lane l16 sit a wave-uniform distance behind its A rows.
     static_assert(C::STAGE_BYTES % C::ROW_BYTES == 0 && (C::ROW_BYTES & (C::ROW_BYTES - 1)) == 0, "slice addressing");
-    int a_rd0 = (wm * 32 + l32) * C::ROW_BYTES + ((lhi ^ C::swz(l32)) << 4);
+    static_assert(CS % 2 == 0 && 16 % (C::WRAP * C::PPR) == 0, "32-term slices, swizzle period");
+    constexpr int S32 = CS / 2;                             // 32-term slices per chunk
+    int a_rd0 = (wm * 32 + l16) * C::ROW_BYTES + ((lq ^ C::swz(l16)) << 4);
     const int b_delta = sgpr(C::A_BYTES + (wn * C::WTN - wm * 32) * C::ROW_BYTES);
-    bf16x8 af[CS][MI], bf[CS][NI];
-    f32x16 acc[MI][NI];
+    bf16x8 af[S32][MI][2], bf[S32][NI][2];
+    f32x4 acc[MI][NI][2][2];
     auto zero_acc = [&]() {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+                for (int ab = 0; ab < 4; ++ab)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[mi][ni][ab >> 1][ab & 1][r] = 0.f;
     };
-    // Memory phase of chunk h: the fragments of the slices h*CS ... of the stage in buffer buf go to
+    // Memory phase of chunk h: the fragments of the slices h*S32 ... of the stage in buffer buf go to
     // registers; the first chunk also issues the next stage's global -> LDS loads.  A load occupies
     // the issuing wavefront until the texture path accepts it (some tens of cycles each when four
     // wavefronts issue at once), the LDS reads do not: the loads are spread between the reads so
     // that the two kinds of waiting overlap instead of adding up.
     auto mem_phase = [&](int buf, int h) {
-        constexpr int NR = CS * (NI + MI), NL = C::LPS, STEP = NR / NL;
+        constexpr int PER = 2 * (NI + MI), NR = S32 * PER, NL = C::LPS, STEP = NR / NL;
         static_assert(STEP >= 1, "more loads than reads in a chunk");
         // (the empty asm keeps the compiler from forming all slice addresses once, outside the loop,
         // and holding them in registers the 256-row configuration does not have)
@@ -331,28 +345,36 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
                 issue_load(j / STEP);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            const int s = j / (NI + MI), idx = j % (NI + MI);
-            if (idx < NI)
-                bf[s][idx] = *(const bf16x8*)(ring + (b_at ^ (unsigned)((h * CS + s) << 5)) + idx * 32 * C::ROW_BYTES);
+            const int s = j / PER, idx = j % PER;
+            const unsigned flip = (unsigned)((h * S32 + s) << 6);
+            if (idx < 2 * NI)
+                bf[s][idx >> 1][idx & 1] =
+                    *(const bf16x8*)(ring + (b_at ^ flip) + ((idx >> 1) * 32 + (idx & 1) * 16) * C::ROW_BYTES);
             else
-                af[s][idx - NI] = *(const bf16x8*)(ring + (a_at ^ (unsigned)((h * CS + s) << 5)) + (idx - NI) * (C::WM * 32) * C::ROW_BYTES);
+                af[s][(idx - 2 * NI) >> 1][idx & 1] =
+                    *(const bf16x8*)(ring + (a_at ^ flip) + (((idx - 2 * NI) >> 1) * (C::WM * 32) + (idx & 1) * 16) * C::ROW_BYTES);
         }
         if (h == 0) issue_done();
     };
     auto mfma_chunk = [&](auto full, int mi_on) {
 #pragma unroll
-        for (int s = 0; s < CS; ++s)
+        for (int s = 0; s < S32; ++s)
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
                 if (decltype(full)::value || mi < mi_on) {
 #pragma unroll
-                    for (int ni = 0; ni < NI; ++ni)
-                        if constexpr (HALF_IN)
-                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, af[s][mi]),
-                                                                                 __builtin_bit_cast(f16x8, bf[s][ni]),
-                                                                                 acc[mi][ni], 0, 0, 0);
-                        else
-                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][mi], bf[s][ni], acc[mi][ni], 0, 0, 0);
+                    for (int a = 0; a < 2; ++a)
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                            for (int b = 0; b < 2; ++b)
+                                if constexpr (HALF_IN)
+                                    acc[mi][ni][a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                                        __builtin_bit_cast(f16x8, af[s][mi][a]), __builtin_bit_cast(f16x8, bf[s][ni][b]),
+                                        acc[mi][ni][a][b], 0, 0, 0);
+                                else
+                                    acc[mi][ni][a][b] =
+                                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[s][mi][a], bf[s][ni][b], acc[mi][ni][a][b], 0, 0, 0);
                 }
             }
     };
@@ -382,24 +404,15 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         asm volatile("" ::: "memory");
     };
 
-    // ---- epilogue of one item.  acc[mi][ni][r]: row 8*(r/4) + 4*lhi + r%4, column l32 of the
-    // 32x32 block.  Neighbouring lanes (columns c, c+1) swap one value of each register pair
-    // (rows rho, rho+1): the even lane then holds columns c, c+1 of row rho, the odd lane the
-    // same columns of row rho+1, so every lane stores two adjacent outputs at once (one packed
-    // half pair, or two floats) and the number of store instructions halves.  Stores go through
-    // a descriptor that ends with the tile's last row (the row part of a store's address is
+    // ---- epilogue of one item.  acc[mi][ni][a][b][r]: row 16 a + 4 lq + r of the 32x32 block and
+    // packed weight row 16 b + l16 of its 32, which is output column 2 l16 + b (the packed order of
+    // 16-bit weights): every lane stores two adjacent outputs at once (one packed half pair, or two
+    // floats), and one store instruction writes 32 columns of four rows.  Stores go through a
+    // descriptor that ends with the tile's last row (the row part of a store's address is
     // range-checked only in the per-lane offset).
     constexpr int ES = HALF_IN ? 4 : 2;
     const unsigned ld_bytes = (unsigned)ld_out * ES;
-    const int odd = l32 & 1;
-    const unsigned st_voff = (unsigned)(wm * 32 + 4 * lhi + odd) * ld_bytes + (unsigned)(l32 & ~1) * ES;
-    // (v0, v1) = this lane's values of rows rho, rho+1 -> the two adjacent values this lane stores
-    auto pair_up = [&](float v0, float v1, float& lo, float& hi) {
-        const float give = odd ? v0 : v1;
-        const float got = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(give), 0xB1, 0xf, 0xf, false));
-        lo = odd ? got : v0;
-        hi = odd ? v1 : got;
-    };
+    const unsigned st_voff = (unsigned)(wm * 32 + 4 * lq) * ld_bytes + (unsigned)(2 * l16) * ES;
     auto store_pair = [&](__amdgpu_buffer_rsrc_t ro, float lo, float hi, unsigned voff, unsigned soff) {
         if (HALF_IN) {
             u32x2 v = {__float_as_uint(lo), __float_as_uint(hi)};
@@ -419,32 +432,27 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         for (int mi = 0; mi < MI; ++mi) {
             if (mi >= mi_on) continue;
 #pragma unroll
-            for (int rp = 0; rp < 8; ++rp) {
-                const int r = 2 * rp;
-                const unsigned voff = st_base + (unsigned)(mi * (C::WM * 32) + 8 * (r >> 2) + (r & 3)) * ld_bytes;
+            for (int j = 0; j < 8; ++j) {
+                const int a = j >> 2, r = j & 3;
+                const unsigned voff = st_base + (unsigned)(mi * (C::WM * 32) + a * 16 + r) * ld_bytes;
                 if (EPI == MOE_EPI_SWIGLU) {
                     // packed weight rows alternate in blocks of 32: gate, up, gate, up, ...
 #pragma unroll
                     for (int ni = 0; ni < NI; ni += 2) {
                         const int pc = n0 + wn * C::WTN + ni * 32;          // packed column of the gate block
-                        if (pc < N) {
-                            float lo, hi;
-                            pair_up(silu_f(acc[mi][ni][r]) * acc[mi][ni + 1][r],
-                                    silu_f(acc[mi][ni][r + 1]) * acc[mi][ni + 1][r + 1], lo, hi);
-                            store_pair(ro, lo, hi, voff, (unsigned)(pc / 2) * 2u);
-                        }
+                        if (pc < N)
+                            store_pair(ro, silu_f(acc[mi][ni][a][0][r]) * acc[mi][ni + 1][a][0][r],
+                                       silu_f(acc[mi][ni][a][1][r]) * acc[mi][ni + 1][a][1][r], voff, (unsigned)(pc / 2) * 2u);
                     }
                 } else {
 #pragma unroll
                     for (int ni = 0; ni < NI; ++ni) {
                         const int col = n0 + wn * C::WTN + ni * 32;
                         if (col < N) {
-                            float lo, hi;
                             if (EPI == MOE_EPI_RELU)
-                                pair_up(fmaxf(acc[mi][ni][r], 0.f), fmaxf(acc[mi][ni][r + 1], 0.f), lo, hi);
+                                store_pair(ro, fmaxf(acc[mi][ni][a][0][r], 0.f), fmaxf(acc[mi][ni][a][1][r], 0.f), voff, (unsigned)col * ES);
                             else
-                                pair_up(acc[mi][ni][r], acc[mi][ni][r + 1], lo, hi);
-                            store_pair(ro, lo, hi, voff, (unsigned)col * ES);
+                                store_pair(ro, acc[mi][ni][a][0][r], acc[mi][ni][a][1][r], voff, (unsigned)col * ES);
                         }
                     }
                 }
@@ -474,15 +482,15 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         }
     };
     auto epilogue_scatter = [&](int par, int rc, int mi_on, int n0) {
-        const int lane_row = wm * 32 + 4 * lhi + odd;
-        const unsigned col_off = (unsigned)(l32 & ~1) * 4u;
+        const int lane_row = wm * 32 + 4 * lq;
+        const unsigned col_off = (unsigned)(2 * l16) * 4u;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             if (mi >= mi_on) continue;
 #pragma unroll
-            for (int rp = 0; rp < 8; ++rp) {
-                const int r = 2 * rp;
-                const int rr = lane_row + mi * (C::WM * 32) + 8 * (r >> 2) + (r & 3);
+            for (int j = 0; j < 8; ++j) {
+                const int a = j >> 2, r = j & 3;
+                const int rr = lane_row + mi * (C::WM * 32) + a * 16 + r;
                 const unsigned tok = (unsigned)rinfo[par * 2 * BM + rr];
                 const float gate = ((const float*)rinfo)[par * 2 * BM + BM + rr];
                 // (a row past the tile's end gets an offset no output has: the range check drops it)
@@ -490,11 +498,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
                     const int col = n0 + wn * C::WTN + ni * 32;
-                    if (col < N) {
-                        float lo, hi;
-                        pair_up(acc[mi][ni][r], acc[mi][ni][r + 1], lo, hi);
-                        store_pair(ry, lo * gate, hi * gate, voff, (unsigned)col * 4u);
-                    }
+                    if (col < N) store_pair(ry, acc[mi][ni][a][0][r] * gate, acc[mi][ni][a][1][r] * gate, voff, (unsigned)col * 4u);
                 }
             }
         }

@@ -140,6 +140,8 @@ def test_ffn_argument_errors():
 def test_pack_combine_copy_argument_errors():
     assert status(B.moe_pack_weights, FAKE, None, 1, 0, 8, B.MOE_F32, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_pack_weights, FAKE, FAKE, 1, 8, 48, B.MOE_F32, FAKE, 0) == B.MOE_ERR_UNSUPPORTED   # N % 32
+    assert status(B.moe_pack_weights, FAKE, None, 1, 8, 48, B.MOE_BF16, FAKE, 0) == B.MOE_ERR_UNSUPPORTED  # N % 32, 16-bit
+    assert status(B.moe_pack_w_out, FAKE, 1, 8, 48, B.MOE_BF16, FAKE, 0) == B.MOE_ERR_UNSUPPORTED
     assert status(B.moe_pack_weights, None, None, 1, 8, 8, B.MOE_F32, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_pack_weights, None, None, 0, 8, 8, B.MOE_F32, None, 0) == B.MOE_OK
     reb = lambda s_in=FAKE, Gs=8, E=128, G=8, q=1, s_out=FAKE: status(B.moe_rebalance, s_in, Gs, E, G, q, s_out, None, 0)
@@ -155,7 +157,7 @@ def test_pack_combine_copy_argument_errors():
     assert top1(B.MOE_BF16, 512, FAKE, None) == B.MOE_ERR_ARG
     assert status(B.moe_grouped_ffn_top1_phase, 3, FAKE, 8, 64, 512, 2, B.MOE_RELU, B.MOE_BF16, FAKE, FAKE, FAKE, FAKE,
                   128, FAKE, FAKE, None, FAKE, 0) == B.MOE_ERR_ARG
-    assert status(B.moe_pack_w_out, None, 1, 8, 8, B.MOE_BF16, FAKE, 0) == B.MOE_ERR_ARG
+    assert status(B.moe_pack_w_out, None, 1, 8, 32, B.MOE_BF16, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_pack_w_out, FAKE, 1, 8, 8, 7, FAKE, 0) == B.MOE_ERR_UNSUPPORTED
     assert status(B.moe_pack_w_out, None, 0, 8, 8, B.MOE_BF16, None, 0) == B.MOE_OK
     assert status(B.moe_unpermute_combine, FAKE, FAKE, None, None, 4, 30, 1, FAKE, 0) == B.MOE_ERR_UNSUPPORTED

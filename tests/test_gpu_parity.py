@@ -219,7 +219,14 @@ def test_plan_tiles_all_policies(torch_gpu, policy):
 
 
 PACK_CASES = [("f32", 1, 64, 128, False), ("bf16", 3, 768, 3072 // 4, False), ("bf16", 2, 96, 160, True),
-              ("f32", 2, 40, 64, True), ("bf16", 1, 50, 70, False)]
+              ("f32", 2, 40, 64, True), ("f32", 1, 50, 70, False), ("bf16", 1, 50, 96, False)]
+
+
+def _bf16_row_order(mat):
+    """Packed order of 16-bit weights: inside every block of 32 rows, row 16 h + j <- row 2 j + h."""
+    n, rows, K = mat.shape
+    blocks = mat.reshape(n, rows // 32, 16, 2, K)         # [.., j, h, :]
+    return np.ascontiguousarray(np.swapaxes(blocks, 2, 3)).reshape(n, rows, K)
 
 
 @pytest.mark.parametrize("dtype,n,K,N,inter", PACK_CASES)
@@ -247,13 +254,15 @@ def test_pack_weights(torch_gpu, dtype, n, K, N, inter):
             ref[:, 64 * j + 32:64 * j + 64] = bt[:, 32 * j:32 * j + 32]
     else:
         ref = at
+    if dtype == "bf16":
+        ref = _bf16_row_order(ref)
     assert np.array_equal(to_numpy(out), ref)
 
 
-@pytest.mark.parametrize("dtype,n,F,d", [("bf16", 2, 96, 160), ("bf16", 1, 50, 70), ("f32", 2, 40, 64)])
+@pytest.mark.parametrize("dtype,n,F,d", [("bf16", 2, 96, 160), ("bf16", 1, 50, 64), ("f32", 2, 40, 70)])
 def test_pack_w_out(torch_gpu, dtype, n, F, d):
-    """Output-major like moe_pack_weights; bf16 values become the nearest IEEE half (exact in
-    half's normal range, rounded on its subnormals, infinite beyond 65504)."""
+    """Output-major and in the row order of moe_pack_weights; bf16 values become the nearest IEEE
+    half (exact in half's normal range, rounded on its subnormals, infinite beyond 65504)."""
     torch = torch_gpu
     from paper_2506_12417_amd import binding as B
     from paper_2506_12417_amd.layer import to_device
@@ -269,7 +278,7 @@ def test_pack_w_out(torch_gpu, dtype, n, F, d):
         with np.errstate(over="ignore"):
             ref = W.bf16_bits_to_f32(w).astype(np.float16)
         got = out.cpu().numpy()
-        assert np.array_equal(got.view(np.uint16), np.transpose(ref, (0, 2, 1)).view(np.uint16))
+        assert np.array_equal(got.view(np.uint16), _bf16_row_order(np.transpose(ref, (0, 2, 1)).view(np.uint16)))
         normal = (np.abs(ref) >= 2.0 ** -14) & np.isfinite(ref)
         assert normal.mean() > 0.3 and np.array_equal(ref[normal].astype(np.float32), W.bf16_bits_to_f32(w)[normal])
     else:
