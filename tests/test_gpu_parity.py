@@ -288,9 +288,9 @@ def test_pack_w_out(torch_gpu, dtype, n, F, d):
         assert np.array_equal(to_numpy(out).view(np.uint32), np.transpose(w32, (0, 2, 1)).view(np.uint32))
 
 
-def _stage_check(torch, wl, inp, tol_scale=1.0):
+def _stage_check(torch, wl, inp, tol_scale=1.0, flip_tol=1e-3, **layer_kw):
     """Runs route -> permute -> plan -> ffn -> combine on the GPU and checks every stage."""
-    layer = make_layer(wl, inp)
+    layer = make_layer(wl, inp, **layer_kw)
     x = layer_x(layer, inp)
     y = layer.forward(x)
     torch.cuda.synchronize()
@@ -326,7 +326,7 @@ def _stage_check(torch, wl, inp, tol_scale=1.0):
         yp_m = O.grouped_ffn(xp, p["offsets"], ew, wl.act, h_round="f16")
         e_m = max_err_over_rms(to_numpy(layer.y_perm), yp_m)
         print("   ffn err/rms vs half-hidden oracle %.3e" % e_m, flush=True)
-        assert e_m <= 1e-3
+        assert e_m <= flip_tol
     return layer
 
 
@@ -353,6 +353,19 @@ def test_layer_stage_by_stage(torch_gpu, name, over):
     _note("layer %s %s" % (name, over))
     inp = W.make_inputs(wl)
     _stage_check(torch_gpu, wl, inp)
+
+
+def test_layer_with_more_tiles_in_a_bin_than_the_kernel_lists(torch_gpu):
+    """400 000 rows on ONE bin in 128-row tiles: more than 3 100 tiles, beyond the per-bin block table
+    the GEMM kernel keeps in LDS, so its items are taken in plain column-block-major order."""
+    wl = W.WORKLOADS["c2"].scaled(T=400000, d=64, F=64, E=4)
+    _note("layer, one bin, %d rows" % wl.T)
+    inp = W.make_inputs(wl)
+    # (F = 64: a single hidden activation whose half rounding falls the other way is a larger share
+    # of an output than with the long contractions of the other cases, and the maximum is over
+    # 25 million outputs: 1.2e-3 observed)
+    layer = _stage_check(torch_gpu, wl, inp, flip_tol=2e-3, n_bins=1, tile_m=128)
+    assert int(to_numpy(layer.plan_hdr)[0]) > 3068
 
 
 def test_combine_identity_and_error_paths(torch_gpu):
