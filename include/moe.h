@@ -128,8 +128,15 @@ MOE_API int moe_permute(const void* x, const int32_t* expert_idx, int T, int d, 
  *   MOE_PLAN_EVEN_SPLIT every expert's rows are divided evenly over all bins (section 5.3.2).
  *
  * Output: a table of tiles, bin after bin.  A tile is at most tile_m consecutive rows of one
- * expert; the tiles cover rows [0,A) exactly once.  Inside a bin the blocks are ordered by
- * falling row count (then expert id), a block's tiles by rising row_begin.
+ * expert; the tiles cover rows [0,A) exactly once.  A block = the rows of one expert on one
+ * bin; its tiles are listed together, by rising row_begin.  The order of a bin's blocks is the
+ * order in which moe_grouped_ffn takes them (the paper leaves the order inside a GPU open):
+ * blocks of more than one tile and blocks of one tile are each ordered by falling row count,
+ * then expert id; if the first kind outnumbers the second (or one is missing) it comes first,
+ * otherwise the two lists are merged evenly (the i-th of L has the key (2i+1)/L, rising keys,
+ * the multi-tile block first among equals), so that work bound by arithmetic (tiles that share
+ * an expert's weights) and work bound by memory (one-tile experts, each streaming its own
+ * weights) run side by side.
  *
  *   counts [E], offsets [E+1] int32 (device, e.g. from moe_permute)
  *   tiles  [tile_capacity] out;  tile_capacity >= moe_plan_capacity(A, E, tile_m, n_bins)

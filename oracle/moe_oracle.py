@@ -34,6 +34,8 @@ from __future__ import annotations
 
 from typing import Dict, Optional, Sequence, Tuple
 
+from fractions import Fraction
+
 import numpy as np
 
 
@@ -388,18 +390,35 @@ def schedule_balanced(counts, G: int, q: int, tile_m: int, by_cost: bool = True)
     return S
 
 
+def block_order(rows_of: dict, tile_m: int):
+    """The order in which one bin lists its blocks (rows_of: expert -> rows of that expert on
+    the bin, all positive).  The paper does not order the work inside a GPU (Alg. 1 step 5 just
+    runs the experts); this is the library's launch order.  Blocks of more than one tile
+    ("long") and the others ("short") are each ordered by falling row count, then expert id.
+    If the long ones outnumber the short ones, or one kind is missing, the long ones come first.
+    Otherwise the two lists are merged evenly: the i-th of L long blocks has the key (2i+1)/L,
+    the j-th of M short ones (2j+1)/M; rising key, a long block first among equal keys."""
+    by_size = sorted(rows_of, key=lambda e: (-rows_of[e], e))
+    long_ = [e for e in by_size if rows_of[e] > tile_m]
+    short = [e for e in by_size if rows_of[e] <= tile_m]
+    if not long_ or not short or len(long_) > len(short):
+        return long_ + short
+    keyed = [(Fraction(2 * i + 1, len(long_)), 0, e) for i, e in enumerate(long_)]
+    keyed += [(Fraction(2 * j + 1, len(short)), 1, e) for j, e in enumerate(short)]
+    return [e for _, _, e in sorted(keyed)]
+
+
 def tiles_from_schedule(S: np.ndarray, offsets, tile_m: int):
     """The tile table a schedule S [E, n_bins] stands for: bin after bin; inside a bin the
-    blocks by falling row count (then expert id); a block's rows are the expert's rows after
-    those of lower-numbered bins, cut into tiles of at most tile_m rows.
+    blocks in block_order(); a block's rows are the expert's rows after those of
+    lower-numbered bins, cut into tiles of at most tile_m rows.
     Returns (tiles [n,4] int32 = expert,row_begin,row_count,bin ; bin_start [G+1])."""
     S = np.asarray(S, dtype=np.int64)
     E, G = S.shape
     before = np.concatenate([np.zeros((E, 1), dtype=np.int64), np.cumsum(S, axis=1)[:, :-1]], axis=1)
     tiles, bin_start = [], [0]
     for g in range(G):
-        blocks = sorted((e for e in range(E) if S[e, g] > 0), key=lambda e: (-S[e, g], e))
-        for e in blocks:
+        for e in block_order({e: int(S[e, g]) for e in range(E) if S[e, g] > 0}, tile_m):
             row, left = int(offsets[e] + before[e, g]), int(S[e, g])
             while left > 0:
                 rc = min(tile_m, left)

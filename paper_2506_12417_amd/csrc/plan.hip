@@ -53,6 +53,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     __shared__ int blk_n[MOE_MAX_EXPERTS * MOE_MAX_BINS];
     __shared__ unsigned char blk_e[MOE_MAX_EXPERTS * MOE_MAX_BINS];
     __shared__ int blk_t[MOE_MAX_EXPERTS * MOE_MAX_BINS];               // tiles of the block
+    __shared__ short blk_key[MOE_MAX_EXPERTS * MOE_MAX_BINS];           // rank of the block among its kind in its bin
     __shared__ int load[MOE_MAX_BINS], bin_blocks[MOE_MAX_BINS + 1], bin_cursor[MOE_MAX_BINS], bin_tiles[MOE_MAX_BINS + 1];
     __shared__ int s_tavg, s_moves;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -259,8 +260,30 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     }
     __syncthreads();
 
-    // ---- tiles: inside a bin the blocks by falling row count, then expert id; one block per thread
+    // ---- tiles; one block per thread.  Inside a bin the blocks of several tiles ("long": their
+    // tiles share the expert's weights through the XCD's L2, the arithmetic bounds them) are
+    // spread evenly among the blocks of one tile ("short": each streams its expert's weights
+    // from HBM), so that the work-groups of an XCD, which take the blocks in this order, mix the
+    // two kinds at all times instead of first computing with the memory idle and then waiting
+    // for the memory.  Each kind is ordered by falling row count, then expert id; the i-th of
+    // n_long long blocks has the key (2i+1)/n_long, the j-th short one (2j+1)/n_short, and the
+    // blocks are listed by rising key, a long one first among equals.  Where the long blocks
+    // outnumber the short ones the bin is bound by arithmetic anyway, and the plain order by
+    // falling row count (then expert id) is kept: it leaves the smallest blocks for the end,
+    // where they even out the finishing times of the work-groups.
     const int n_blocks = bin_blocks[G];
+    for (int b = tid; b < n_blocks; b += NTH) {
+        int g = 0;
+        while (b >= bin_blocks[g + 1]) ++g;
+        const int n = blk_n[b], e = blk_e[b];
+        const bool is_long = n > tile_m;
+        int rank = 0;
+        for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o) {
+            const int n2 = blk_n[o], e2 = blk_e[o];
+            if ((n2 > tile_m) == is_long && (n2 > n || (n2 == n && e2 < e))) ++rank;
+        }
+        blk_key[b] = rank;
+    }
     if (tid == 0) {
         int run = 0;
         for (int g = 0; g < G; ++g) {
@@ -281,10 +304,19 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         int g = 0;
         while (b >= bin_blocks[g + 1]) ++g;
         const int n = blk_n[b], e = blk_e[b];
+        const bool is_long = n > tile_m;
+        int n_long = 0;
+        for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o) n_long += blk_n[o] > tile_m;
+        const int n_short = bin_blocks[g + 1] - bin_blocks[g] - n_long;
+        const int key = (2 * blk_key[b] + 1) * (is_long ? n_short : n_long);
         int before = 0;
         for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o) {
-            const int n2 = blk_n[o], e2 = blk_e[o];
-            if (n2 > n || (n2 == n && e2 < e)) before += blk_t[o];
+            const bool long2 = blk_n[o] > tile_m;
+            const int key2 = (2 * blk_key[o] + 1) * (long2 ? n_short : n_long);
+            const bool first = long2 == is_long ? blk_key[o] < blk_key[b]
+                               : n_long > n_short ? long2
+                                                  : (key2 < key || (key2 == key && long2));
+            if (first) before += blk_t[o];
         }
         int row = row0[e];
         for (int g2 = 0; g2 < g; ++g2) row += S[e * G + g2];

@@ -442,6 +442,30 @@ def test_schedule_policies_invariants():
         assert np.all(Se.max(axis=1) - Se.min(axis=1) <= 1)
 
 
+def test_block_order_spreads_long_blocks_among_short_ones():
+    """Hand-worked listings (tile_m = 128: a block of more than 128 rows is long)."""
+    # L = 2 long (keys 1/2, 3/2), M = 4 short (keys 1/4, 3/4, 5/4, 7/4)
+    assert O.block_order({0: 300, 1: 200, 2: 50, 3: 40, 4: 30, 5: 20}, 128) == [2, 0, 3, 4, 1, 5]
+    # equal keys: the long block first
+    assert O.block_order({0: 5, 1: 200}, 128) == [1, 0]
+    assert O.block_order({7: 129, 3: 500, 1: 128, 2: 128}, 128) == [3, 1, 7, 2]
+    # long blocks outnumber the short ones, or one kind is missing: falling rows, then expert id
+    assert O.block_order({0: 300, 1: 300, 2: 10}, 128) == [0, 1, 2]
+    assert O.block_order({4: 20, 2: 20, 9: 128}, 128) == [9, 2, 4]
+    assert O.block_order({4: 200, 2: 2000}, 128) == [2, 4]
+    assert O.block_order({}, 128) == []
+    # any input: a permutation that keeps each kind in its own order
+    r = np.random.default_rng(12)
+    for _ in range(200):
+        tile_m = int(r.choice([16, 128, 256]))
+        rows = {int(e): int(n) for e, n in zip(r.permutation(40)[:r.integers(1, 30)], r.integers(1, 4 * tile_m, 30))}
+        order = O.block_order(rows, tile_m)
+        assert sorted(order) == sorted(rows)
+        for kind in (True, False):
+            sub = [e for e in order if (rows[e] > tile_m) == kind]
+            assert sub == sorted(sub, key=lambda e: (-rows[e], e))
+
+
 def test_schedule_balanced_splits_hot_expert_and_balances():
     # one expert with half of all rows, 8 bins: its rows must be spread, tile counts equal
     counts = np.array([8192, 2600, 1500, 1100, 900, 800, 700, 592])
