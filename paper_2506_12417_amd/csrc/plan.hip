@@ -54,7 +54,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     __shared__ unsigned char blk_e[MOE_MAX_EXPERTS * MOE_MAX_BINS];
     __shared__ int blk_t[MOE_MAX_EXPERTS * MOE_MAX_BINS];               // tiles of the block
     __shared__ short blk_key[MOE_MAX_EXPERTS * MOE_MAX_BINS];           // rank of the block among its kind in its bin
-    __shared__ int load[MOE_MAX_BINS], bin_blocks[MOE_MAX_BINS + 1], bin_cursor[MOE_MAX_BINS], bin_tiles[MOE_MAX_BINS + 1];
+    __shared__ int load[MOE_MAX_BINS], bin_blocks[MOE_MAX_BINS + 1], bin_cursor[MOE_MAX_BINS], bin_tiles[MOE_MAX_BINS + 1], bin_long[MOE_MAX_BINS];
     __shared__ int s_tavg, s_moves;
     const int tid = threadIdx.x, lane = tid & 63;
     const bool by_cost = (policy == MOE_PLAN_BALANCED);
@@ -277,12 +277,15 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         while (b >= bin_blocks[g + 1]) ++g;
         const int n = blk_n[b], e = blk_e[b];
         const bool is_long = n > tile_m;
-        int rank = 0;
+        int rank = 0, n_long = 0;
         for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o) {
             const int n2 = blk_n[o], e2 = blk_e[o];
-            if ((n2 > tile_m) == is_long && (n2 > n || (n2 == n && e2 < e))) ++rank;
+            const bool long2 = n2 > tile_m;
+            n_long += long2;
+            if (long2 == is_long && (n2 > n || (n2 == n && e2 < e))) ++rank;
         }
-        blk_key[b] = rank;
+        blk_key[b] = (short)(rank | (is_long ? 0x4000 : 0));
+        bin_long[g] = n_long;                      // (every block of the bin writes the same number)
     }
     if (tid == 0) {
         int run = 0;
@@ -305,19 +308,20 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         while (b >= bin_blocks[g + 1]) ++g;
         const int n = blk_n[b], e = blk_e[b];
         const bool is_long = n > tile_m;
-        int n_long = 0;
-        for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o) n_long += blk_n[o] > tile_m;
+        const int n_long = bin_long[g];
         const int n_short = bin_blocks[g + 1] - bin_blocks[g] - n_long;
-        const int key = (2 * blk_key[b] + 1) * (is_long ? n_short : n_long);
+        // one number per block that rises along the listing: long blocks first, or the merged keys
+        // (doubled, a short block's one higher, so that a long one precedes a short one of equal key)
+        const bool merged = n_long > 0 && n_long <= n_short;
+        auto place = [&](int k) {
+            const bool lng = (k & 0x4000) != 0;
+            const int rank = k & 0x3fff;
+            return merged ? 2 * (2 * rank + 1) * (lng ? n_short : n_long) + (lng ? 0 : 1) : (lng ? rank : 0x4000 + rank);
+        };
+        const int mine = place(blk_key[b]);
         int before = 0;
-        for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o) {
-            const bool long2 = blk_n[o] > tile_m;
-            const int key2 = (2 * blk_key[o] + 1) * (long2 ? n_short : n_long);
-            const bool first = long2 == is_long ? blk_key[o] < blk_key[b]
-                               : n_long > n_short ? long2
-                                                  : (key2 < key || (key2 == key && long2));
-            if (first) before += blk_t[o];
-        }
+        for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o)
+            if (place(blk_key[o]) < mine) before += blk_t[o];
         int row = row0[e];
         for (int g2 = 0; g2 < g; ++g2) row += S[e * G + g2];
         const int nt = blk_t[b];
