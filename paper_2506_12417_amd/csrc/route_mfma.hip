@@ -594,20 +594,32 @@ __device__ __forceinline__ void route_packed_body(const uint16_t* __restrict__ x
     const int rounds = (k + 1 < E) ? k + 1 : E;
     const float u = 5.9604645e-8f;   // 2^-24
 
-    // ---- selection: TPT threads per token (the first four wavefronts), thread `sub` scans experts sub, sub+TPT, ...
+    // ---- selection: TPT threads per token (the first four wavefronts); thread `sub` takes the CPT
+    // consecutive experts from sub * CPT on, fetched with four-float reads before the scan (a read
+    // per expert inside the scan made it wait for LDS at every step)
     if (tid < TB * TPT) {
+        constexpr int CPT = EPT / TPT;
+        static_assert(CPT % 4 == 0 && PL % 4 == 0, "four-float reads of a logit row");
         const int tok = tid / TPT, sub = tid % TPT, t = t0 + tok;
         const float* row = ls + tok * PL;
+        float mine[CPT];
+#pragma unroll
+        for (int j = 0; j < CPT; j += 4) {
+            const float4 q = *reinterpret_cast<const float4*>(row + sub * CPT + j);
+            mine[j] = q.x; mine[j + 1] = q.y; mine[j + 2] = q.z; mine[j + 3] = q.w;
+        }
         float lv[RMAX];
         int le[RMAX];
 #pragma unroll
         for (int r = 0; r < RMAX; ++r) { lv[r] = NEG_INF; le[r] = INT_MAX; }
         float m = NEG_INF;
-        for (int e = sub; e < E; e += TPT) {
-            float v = row[e];
-            int ve = e;
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) {
+            int ve = sub * CPT + j;
+            float v = ve < E ? mine[j] : NEG_INF;                // (columns past E hold nothing)
+            mine[j] = v;
             m = fmaxf(m, v);
-            if (beats(v, ve, lv[RMAX - 1], le[RMAX - 1])) {     // sorted insertion, static indices
+            if (ve < E && beats(v, ve, lv[RMAX - 1], le[RMAX - 1])) {     // sorted insertion, static indices
 #pragma unroll
                 for (int r = 0; r < RMAX; ++r) {
                     if (beats(v, ve, lv[r], le[r])) {
@@ -620,7 +632,8 @@ __device__ __forceinline__ void route_packed_body(const uint16_t* __restrict__ x
         }
         m = group_max<TPT>(m);
         float s = 0.f;
-        for (int e = sub; e < E; e += TPT) s += __expf(row[e] - m);
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) s += sub * CPT + j < E ? __expf(mine[j] - m) : 0.f;
         const float denom = group_sum<TPT>(s);
         float sel_v[RMAX];
         int sel_e[RMAX];
