@@ -305,6 +305,35 @@ MOE_API int moe_grouped_ffn_top1_phase(int phase, const void* x_perm, int T, int
                                        void* h_scratch, const int32_t* perm, const float* gate_w, float* y,
                                        void* stream);
 
+/* Steps 4 (the row gather), 5 and, for top-1 routing, 6 in one call: the first product fetches
+ * its rows from x itself,
+ *
+ *   row r of expert e's group = x[perm[r] / k]                (what moe_permute writes to x_perm[r])
+ *
+ * so moe_permute can be called without x / x_perm (it then only sorts), and x_perm is neither
+ * written nor read.  The results are those of the separate calls, bit for bit.
+ *
+ *   x      [T,d] dt
+ *   perm   [T*k] int32 : from moe_permute
+ *   k == 1 : y_out = y [T,d] fp32, y[perm[r]] = gate_w[perm[r]] * FFN_e(x[perm[r]]) as in
+ *            moe_grouped_ffn_top1 (gate_w [T] fp32 or NULL; F >= 512)
+ *   k  > 1 : y_out = y_perm [T*k,d] fp32 as in moe_grouped_ffn (gate_w is not used); the caller
+ *            combines with moe_unpermute_combine
+ * other arguments as moe_grouped_ffn.  MOE_BF16 only, tile_m = 128, d >= 256, x smaller than
+ * 4 GiB (MOE_ERR_UNSUPPORTED otherwise: use the separate calls).
+ */
+MOE_API int moe_grouped_ffn_fused(const void* x, int T, int d, int F, int E, int k, moe_act act, moe_dtype dt,
+                                  const void* const* w_in, const void* const* w_out,
+                                  const moe_tile* tiles, int32_t* plan_hdr, int tile_m,
+                                  void* h_scratch, const int32_t* perm, const float* gate_w, float* y_out,
+                                  void* stream);
+/* One of its two products on its own, like moe_grouped_ffn_phase (phase 2 does not read x). */
+MOE_API int moe_grouped_ffn_fused_phase(int phase, const void* x, int T, int d, int F, int E, int k, moe_act act,
+                                        moe_dtype dt, const void* const* w_in, const void* const* w_out,
+                                        const moe_tile* tiles, int32_t* plan_hdr, int tile_m,
+                                        void* h_scratch, const int32_t* perm, const float* gate_w,
+                                        float* y_out, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Step 6 (Alg. 1 "reconstruct"; section 2: the experts' outputs are weighted by the router's
  * values and combined):

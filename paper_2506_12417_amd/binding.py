@@ -30,7 +30,7 @@ MOE_OP_PERMUTE = 1
 
 EXPORTS = [
     "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_rebalance", "moe_pack_weights", "moe_pack_w_out",
-    "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_grouped_ffn_top1", "moe_grouped_ffn_top1_phase", "moe_unpermute_combine", "moe_prefetch_create",
+    "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_grouped_ffn_top1", "moe_grouped_ffn_top1_phase", "moe_grouped_ffn_fused", "moe_grouped_ffn_fused_phase", "moe_unpermute_combine", "moe_prefetch_create",
     "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_reset", "moe_prefetch_destroy",
     "moe_token_threshold", "moe_workspace_bytes", "moe_copy_bytes", "moe_last_error", "moe_version",
 ]
@@ -52,6 +52,8 @@ lib.moe_grouped_ffn.argtypes = [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp,
 lib.moe_grouped_ffn_phase.argtypes = [_i, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp]
 lib.moe_grouped_ffn_top1.argtypes = [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]
 lib.moe_grouped_ffn_top1_phase.argtypes = [_i, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]
+lib.moe_grouped_ffn_fused.argtypes = [_vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]
+lib.moe_grouped_ffn_fused_phase.argtypes = [_i, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]
 lib.moe_unpermute_combine.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp]
 lib.moe_prefetch_create.argtypes = [C.POINTER(_vp), _i, _sz, _vp]
 lib.moe_prefetch_experts.argtypes = [_vp, C.POINTER(C.c_int32), _i, C.POINTER(_vp), _sz, C.POINTER(_vp)]
@@ -194,6 +196,19 @@ def moe_grouped_ffn_top1_phase(phase, x_perm, T, d, F, E, act, dt, w_in, w_out, 
                                gate_w, y, stream=None):
     _check(lib.moe_grouped_ffn_top1_phase(phase, _p(x_perm), T, d, F, E, act, dt, _p(w_in), _p(w_out), _p(tiles),
                                           _p(plan_hdr), tile_m, _p(h_scratch), _p(perm), _p(gate_w), _p(y), _stream(stream)))
+
+
+def moe_grouped_ffn_fused(x, T, d, F, E, k, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, perm, gate_w, y_out,
+                          stream=None):
+    _check(lib.moe_grouped_ffn_fused(_p(x), T, d, F, E, k, act, dt, _p(w_in), _p(w_out), _p(tiles), _p(plan_hdr),
+                                     tile_m, _p(h_scratch), _p(perm), _p(gate_w), _p(y_out), _stream(stream)))
+
+
+def moe_grouped_ffn_fused_phase(phase, x, T, d, F, E, k, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, perm,
+                                gate_w, y_out, stream=None):
+    _check(lib.moe_grouped_ffn_fused_phase(phase, _p(x), T, d, F, E, k, act, dt, _p(w_in), _p(w_out), _p(tiles),
+                                           _p(plan_hdr), tile_m, _p(h_scratch), _p(perm), _p(gate_w), _p(y_out),
+                                           _stream(stream)))
 
 
 def moe_grouped_ffn_phase(phase, x_perm, A, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch,

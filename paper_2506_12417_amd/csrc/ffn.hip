@@ -133,11 +133,17 @@ struct Top1 {
     const float* gate_w = nullptr;
     bool on = false;
 };
+// gather: step 4's row gather folded into the first product (x [x_rows, d]; row r is x[perm[r] / k])
+struct Gather {
+    const int32_t* perm = nullptr;
+    int x_rows = 0, k = 1;
+    bool on = false;
+};
 
 static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,
                             const void* const* w_in, const void* const* w_out, const moe_tile* tiles,
                             int32_t* plan_hdr, int tile_m, void* h_scratch, float* y_perm, void* stream,
-                            const Top1& top1 = Top1()) {
+                            const Top1& top1 = Top1(), const Gather& gather = Gather()) {
     MOE_REQUIRE(moe_dtype_ok(dt), MOE_ERR_UNSUPPORTED, "moe_grouped_ffn: dtype %d", (int)dt);
     MOE_REQUIRE(act == MOE_RELU || act == MOE_SWIGLU, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn: activation %d", (int)act);
     MOE_REQUIRE(A >= 0 && d >= 1 && F >= 1 && E >= 1, MOE_ERR_ARG, "moe_grouped_ffn: A=%d d=%d F=%d E=%d", A, d, F, E);
@@ -164,8 +170,12 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
         const long long tiles_est = (A + tile_m - 1) / tile_m + E / 2;
         auto narrow = [&](int N) { return tile_m == 128 && tiles_est * ((N + 255) / 256) < 2 * MOE_GEMM_GRID; };
         if (phases & 1) {
-            rc = moe_launch_gemm_bf16(act == MOE_SWIGLU ? MOE_EPI_SWIGLU : MOE_EPI_RELU, tile_m, narrow(n1), x_perm, d, n1,
-                                      w_in, tiles, plan_hdr, h_scratch, F, st);
+            if (gather.on)
+                rc = moe_launch_gemm_bf16_gather(act == MOE_SWIGLU ? MOE_EPI_SWIGLU : MOE_EPI_RELU, x_perm, gather.x_rows, d, n1,
+                                                 w_in, tiles, plan_hdr, h_scratch, F, st, gather.perm, gather.k);
+            else
+                rc = moe_launch_gemm_bf16(act == MOE_SWIGLU ? MOE_EPI_SWIGLU : MOE_EPI_RELU, tile_m, narrow(n1), x_perm, d, n1,
+                                          w_in, tiles, plan_hdr, h_scratch, F, st);
             if (rc != MOE_OK) return rc;
         }
         if (phases & 2) {
@@ -237,4 +247,47 @@ extern "C" int moe_grouped_ffn_top1_phase(int phase, const void* x_perm, int T, 
                                           const int32_t* perm, const float* gate_w, float* y, void* stream) {
     MOE_REQUIRE(phase == 1 || phase == 2, MOE_ERR_ARG, "moe_grouped_ffn_top1_phase: phase %d", phase);
     return top1_impl(phase, x_perm, T, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, perm, gate_w, y, stream);
+}
+
+static int fused_impl(int phases, const void* x, int T, int d, int F, int E, int k, moe_act act, moe_dtype dt,
+                      const void* const* w_in, const void* const* w_out, const moe_tile* tiles, int32_t* plan_hdr,
+                      int tile_m, void* h_scratch, const int32_t* perm, const float* gate_w, float* y_out, void* stream) {
+    MOE_REQUIRE(dt == MOE_BF16, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: MOE_BF16 only (dtype %d)", (int)dt);
+    MOE_REQUIRE(T >= 0 && k >= 1, MOE_ERR_ARG, "moe_grouped_ffn_fused: T=%d k=%d", T, k);
+    MOE_REQUIRE((long long)T * k < (1ll << 30), MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: T*k too large");
+    MOE_REQUIRE(tile_m == 128, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: needs 128-row tiles (tile_m=%d)", tile_m);
+    MOE_REQUIRE(d >= 256, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: needs d >= 256 (d=%d)", d);
+    MOE_REQUIRE((long long)T * d * 2 < (1ll << 32), MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: x must be smaller than 4 GiB (T=%d d=%d)", T, d);
+    MOE_REQUIRE(T == 0 || perm, MOE_ERR_ARG, "moe_grouped_ffn_fused: null pointer");
+    Gather g;
+    g.perm = perm;
+    g.x_rows = T;
+    g.k = k;
+    g.on = true;
+    if (k == 1) {
+        MOE_REQUIRE(F >= 512, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: top-1 needs F >= 512 (F=%d)", F);
+        MOE_REQUIRE(T == 0 || !(phases & 2) || y_out, MOE_ERR_ARG, "moe_grouped_ffn_fused: null pointer");
+        MOE_REQUIRE((long long)T * d * 4 < (1ll << 31), MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: y must be smaller than 2 GiB (T=%d d=%d)", T, d);
+        Top1 t;
+        t.perm = perm;
+        t.gate_w = gate_w;
+        t.on = true;
+        return grouped_ffn_impl(phases, x, T, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, y_out, stream, t, g);
+    }
+    return grouped_ffn_impl(phases, x, T * k, d, F, E, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, y_out, stream, Top1(), g);
+}
+
+extern "C" int moe_grouped_ffn_fused(const void* x, int T, int d, int F, int E, int k, moe_act act, moe_dtype dt,
+                                     const void* const* w_in, const void* const* w_out, const moe_tile* tiles,
+                                     int32_t* plan_hdr, int tile_m, void* h_scratch, const int32_t* perm,
+                                     const float* gate_w, float* y_out, void* stream) {
+    return fused_impl(3, x, T, d, F, E, k, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, perm, gate_w, y_out, stream);
+}
+
+extern "C" int moe_grouped_ffn_fused_phase(int phase, const void* x, int T, int d, int F, int E, int k, moe_act act,
+                                           moe_dtype dt, const void* const* w_in, const void* const* w_out,
+                                           const moe_tile* tiles, int32_t* plan_hdr, int tile_m, void* h_scratch,
+                                           const int32_t* perm, const float* gate_w, float* y_out, void* stream) {
+    MOE_REQUIRE(phase == 1 || phase == 2, MOE_ERR_ARG, "moe_grouped_ffn_fused_phase: phase %d", phase);
+    return fused_impl(phase, x, T, d, F, E, k, act, dt, w_in, w_out, tiles, plan_hdr, tile_m, h_scratch, perm, gate_w, y_out, stream);
 }

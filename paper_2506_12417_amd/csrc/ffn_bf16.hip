@@ -136,14 +136,18 @@ struct Cfg {
 
 // (The body is a __device__ function: it uses buffer-descriptor types that exist only on the
 // device side, and the host pass must still be able to instantiate the kernel's stub.)
-template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS>
+template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS, bool GATHER>
 __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_mat, int K, int N,
                                                const void* const* __restrict__ w_ptrs,
                                                const moe_tile* __restrict__ tiles, int32_t* __restrict__ hdr,
                                                void* __restrict__ out, int ld_out,
                                                const int32_t* __restrict__ row_token,
-                                               const float* __restrict__ row_gate, int out_rows) {
+                                               const float* __restrict__ row_gate, int out_rows, int a_div) {
     using C = Cfg<BM, BN, BK, RING, WM, WN, CS>;
+    // GATHER (first product only): row r of the table's row space is row row_token[r] / a_div of
+    // a_mat, which has out_rows rows -- Alg. 1's step 4 (the rows of x brought into expert order)
+    // done by the operand loads themselves, whose per-lane addresses are free to choose.
+    static_assert(!GATHER || (EPI != MOE_EPI_SCATTER && RING >= 3), "gather: first product, on-demand hand-out");
     constexpr int MI = C::MI, NI = C::NI, PH = C::PH;
     // The first product takes bf16 operands and writes the hidden activations as IEEE half; the
     // second one (plain store of fp32 results) takes those and a half copy of the weights.
@@ -241,6 +245,8 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         }
     };
 
+    int* rinfo = (int*)(ring + C::SMEM - C::ROWINFO_BYTES);   // per-row tables of two items (scatter epilogue, gather)
+
     // ---- loader.  Piece id = i * NTH + tid of an operand tile: row id / PPR, position id % PPR;
     // the swizzle does not depend on i, so one per-lane offset serves every load of a stage.
     const int ld_row = tid / C::PPR;
@@ -251,6 +257,33 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     __amdgpu_buffer_rsrc_t l_ra, l_rb;
     int l_item = first, l_seq = 0, l_kt = 0, l_buf = 0, issued = 0;
     int g = 0, c_buf = 0;                                   // K-step counter of the stream, its stage
+    // GATHER: the source rows of an item's rows wait in LDS (rinfo[parity of the item's sequence
+    // number][row]): wavefront 0 fetches them there with a global -> LDS load as soon as it knows
+    // the item's id, one item ahead (see publish()).  When the loader turns to the item, every
+    // lane reads the rows of its NA passes and keeps their byte offsets.
+    unsigned voff_a[GATHER ? C::NA : 1];
+    auto fetch_rows = [&](int par, int id) {               // (wavefront 0)
+        int cb, ti;
+        locate(id, ti, cb);
+        const moe_tile t = tiles[bin_start + ti];
+        const int rc = t.row_count < BM ? t.row_count : BM;
+        const __amdgpu_buffer_rsrc_t rt = make_rsrc(row_token + t.row_begin, (unsigned)(rc > 0 ? rc : 0) * 4u);
+#pragma unroll
+        for (int i = 0; i < BM / 64; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rt, (lds_void_t*)(rinfo + par * 2 * BM + i * 64), 4,
+                                                     (unsigned)(i * 64 + lane) * 4u, 0, 0, 0);
+    };
+    auto rows_to_offsets = [&](int par, int rc) {
+        const unsigned piece = (unsigned)(((tid % C::PPR) ^ C::swz(ld_row)) << 4);
+#pragma unroll
+        for (int q = 0; q < C::NA; ++q) {
+            const int row = q * C::ROWS_PER_PASS + ld_row;
+            unsigned src = (unsigned)rinfo[par * 2 * BM + row];
+            if (a_div != 1) src /= (unsigned)a_div;
+            // (a row past the tile's end gets an offset beyond the matrix: the range check reads zeros)
+            voff_a[q] = row < rc ? src * (unsigned)K * 2u + piece : 0xFFFFFFF0u;
+        }
+    };
     auto load_item = [&](int it) {
         int cb, ti;
         locate(it, ti, cb);
@@ -259,7 +292,12 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         const int n0 = cb * BN;
         const int nr = N - n0 < BN ? N - n0 : BN;
         const uint16_t* wmat = (const uint16_t*)w_ptrs[t.expert];
-        l_ra = make_rsrc(a_mat + (size_t)t.row_begin * K, (unsigned)(rc > 0 ? rc : 0) * (unsigned)K * 2u);
+        if constexpr (GATHER) {
+            l_ra = make_rsrc(a_mat, (unsigned)out_rows * (unsigned)K * 2u);
+            rows_to_offsets(l_seq & 1, rc);
+        } else {
+            l_ra = make_rsrc(a_mat + (size_t)t.row_begin * K, (unsigned)(rc > 0 ? rc : 0) * (unsigned)K * 2u);
+        }
         l_rb = make_rsrc(wmat + (size_t)n0 * K, (unsigned)nr * (unsigned)K * 2u);
     };
     // load q of a stage (the A passes first, then the B passes), and the bookkeeping once all are out
@@ -267,7 +305,8 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         unsigned char* st = ring + l_buf * C::STAGE_BYTES + wave * 1024;
         const unsigned k_off = (unsigned)l_kt * (BK * 2);
         if (q < C::NA)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(l_ra, (lds_void_t*)(st + q * (C::NW * 1024)), 16, ld_voff0 + (unsigned)q * ld_pass, k_off, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(l_ra, (lds_void_t*)(st + q * (C::NW * 1024)), 16,
+                                                     GATHER ? voff_a[GATHER ? q : 0] : ld_voff0 + (unsigned)q * ld_pass, k_off, 0, 0);
         else
             __builtin_amdgcn_raw_ptr_buffer_load_lds(l_rb, (lds_void_t*)(st + C::A_BYTES + (q - C::NA) * (C::NW * 1024)), 16,
                                                      ld_voff0 + (unsigned)(q - C::NA) * ld_pass, k_off, 0, 0);
@@ -391,6 +430,9 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         if (dyn && wave == 0 && f_seq >= 0 && g >= f_ready) {
             const int id = stride + read_ticket();
             if (lane == 0) ids[f_seq & 3] = id;
+            // (gather: the next K-step's wait of this wavefront covers these loads, the barrier
+            // after it shows them to the others; the loader turns to the item K-steps later)
+            if constexpr (GATHER) { if (id < n_items) fetch_rows(f_seq & 1, sgpr(id)); }
             f_seq = -1;
             MOE_WAIT_LGKMCNT(0);
         }
@@ -464,7 +506,6 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // (rinfo[parity of the item][0: tokens, 1: gates][row]); they were fetched there by two small
     // global -> LDS loads during the item's first K-steps: first the tokens of the tile's rows,
     // then, indexed by them, the gate values.
-    int* rinfo = (int*)(ring + C::SMEM - C::ROWINFO_BYTES);
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(out, (unsigned)out_rows * ld_bytes);
     auto fetch_tokens = [&](int par, int row_begin, int rc) {
         if (wave < BM / 64) {
@@ -512,6 +553,15 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     };
 
     // ---- prologue: RING-1 stages on their way, the first one landed
+    if constexpr (GATHER) {                                 // source rows of the first two items: fetched and waited for
+        if (wave == 0) {
+            fetch_rows(0, first);
+            const int second = sgpr(ids[1]);
+            if (second < n_items) fetch_rows(1, second);
+        }
+        MOE_WAIT_VMCNT(0);
+        __syncthreads();
+    }
     load_item(first);
 #pragma unroll
     for (int s = 0; s < RING - 1; ++s) issue();
@@ -617,33 +667,35 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     MOE_WAIT_VMCNT(0);                                      // (the trailing empty loads still target this LDS)
 }
 
-template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS>
+template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS, bool GATHER>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(const uint16_t* __restrict__ a_mat, int K, int N,
                                                                   const void* const* __restrict__ w_ptrs,
                                                                   const moe_tile* __restrict__ tiles,
                                                                   int32_t* __restrict__ hdr, void* __restrict__ out,
                                                                   int ld_out, const int32_t* __restrict__ row_token,
-                                                                  const float* __restrict__ row_gate, int out_rows) {
-    gemm_bf16_body<EPI, BM, BN, BK, RING, WM, WN, CS>(a_mat, K, N, w_ptrs, tiles, hdr, out, ld_out, row_token, row_gate,
-                                                      out_rows);
+                                                                  const float* __restrict__ row_gate, int out_rows,
+                                                                  int a_div) {
+    gemm_bf16_body<EPI, BM, BN, BK, RING, WM, WN, CS, GATHER>(a_mat, K, N, w_ptrs, tiles, hdr, out, ld_out, row_token,
+                                                              row_gate, out_rows, a_div);
 }
 
-struct ScatterArgs {             // MOE_EPI_SCATTER only
-    const int32_t* row_token = nullptr;
+struct ScatterArgs {             // MOE_EPI_SCATTER: output row and gate value of every row, rows of the output
+    const int32_t* row_token = nullptr;      // gather: source row (times a_div) of every row, rows of the source
     const float* row_gate = nullptr;
     int out_rows = 0;
+    int a_div = 1;
 };
 
-template <int EPI, class C>
+template <int EPI, class C, bool GATHER = false>
 int launch(const void* a, int K, int N, const void* const* w, const moe_tile* tiles, int32_t* hdr, void* out,
            int ld_out, const ScatterArgs& sc, hipStream_t st) {
     static_assert(C::SMEM <= 160 * 1024, "LDS ring too large");
-    auto kern = gemm_bf16_kernel<EPI, C::BM, C::BN, C::BK, C::RING, C::WM, C::WN, C::CS>;
+    auto kern = gemm_bf16_kernel<EPI, C::BM, C::BN, C::BK, C::RING, C::WM, C::WN, C::CS, GATHER>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)C::SMEM);
     if (e != hipSuccess) return moe_fail(MOE_ERR_HIP, "moe_grouped_ffn: shared memory attribute: %s", hipGetErrorString(e));
     hipLaunchKernelGGL(kern, dim3(MOE_GEMM_GRID), dim3(C::NTH), C::SMEM, st, (const uint16_t*)a, K, N, w, tiles, hdr, out,
-                       ld_out, sc.row_token, sc.row_gate, sc.out_rows);
+                       ld_out, sc.row_token, sc.row_gate, sc.out_rows, sc.a_div);
     MOE_CHECK_LAUNCH("moe_grouped_ffn (bf16 GEMM)");
     return MOE_OK;
 }
@@ -678,4 +730,15 @@ int moe_launch_gemm_bf16(int epi, int tile_m, int narrow, const void* a, int K, 
         return launch_tile<MOE_EPI_SCATTER>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, sc, st);
     }
     return launch_tile<MOE_EPI_STORE>(tile_m, narrow, a, K, N, w, tiles, hdr, out, ld_out, sc, st);
+}
+
+int moe_launch_gemm_bf16_gather(int epi, const void* x, int x_rows, int K, int N, const void* const* w,
+                                const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st,
+                                const int32_t* row_src, int src_div) {
+    ScatterArgs sc;
+    sc.row_token = row_src;
+    sc.out_rows = x_rows;
+    sc.a_div = src_div;
+    if (epi == MOE_EPI_SWIGLU) return launch<MOE_EPI_SWIGLU, Short, true>(x, K, N, w, tiles, hdr, out, ld_out, sc, st);
+    return launch<MOE_EPI_RELU, Short, true>(x, K, N, w, tiles, hdr, out, ld_out, sc, st);
 }

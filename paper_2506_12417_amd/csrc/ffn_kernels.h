@@ -15,3 +15,9 @@ constexpr int MOE_GEMM_GRID = 256;
 int moe_launch_gemm_bf16(int epi, int tile_m, int narrow, const void* a, int K, int N, const void* const* w,
                          const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st,
                          const int32_t* row_token = nullptr, const float* row_gate = nullptr, int out_rows = 0);
+
+// The first product with the row gather folded in (128-row tiles, RELU or SWIGLU; K / 64 >= 4):
+// row r of the table's row space is row row_src[r] / src_div of x [x_rows, K].
+int moe_launch_gemm_bf16_gather(int epi, const void* x, int x_rows, int K, int N, const void* const* w,
+                                const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st,
+                                const int32_t* row_src, int src_div);

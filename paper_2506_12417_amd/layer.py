@@ -68,7 +68,8 @@ class ExpertGroup:
 class MoELayer:
     def __init__(self, T: int, d: int, F: int, E: int, k: int, act: str, dtype: str, renorm: int,
                  shared_F: int = 0, n_bins: int = XCDS, q_tokens: Optional[int] = None,
-                 policy: int = B.MOE_PLAN_HARMOENY, tile_m: Optional[int] = None, device="cuda:0"):
+                 policy: int = B.MOE_PLAN_HARMOENY, tile_m: Optional[int] = None, device="cuda:0",
+                 fuse_gather: Optional[bool] = None):
         self.T, self.d, self.F, self.E, self.k, self.renorm = T, d, F, E, k, renorm
         self.A = T * k
         self.act = B.MOE_SWIGLU if act == "swiglu" else B.MOE_RELU
@@ -104,6 +105,10 @@ class MoELayer:
         # top-1 routing without a shared expert: step 6 is folded into the second GEMM (128-row tiles;
         # the 256-row kernel has no registers left for it)
         self.fold_combine = (k == 1 and self.dt == B.MOE_BF16 and not shared_F and self.tile_m == 128 and F >= 512)
+        # the row gather inside the first product (moe_grouped_ffn_fused): where the library offers it
+        can_fuse = (self.dt == B.MOE_BF16 and self.tile_m == 128 and d >= 256 and d % 64 == 0 and F % 64 == 0
+                    and T * d * 2 < 2 ** 32 and (k > 1 or self.fold_combine))
+        self.fuse_gather = can_fuse if fuse_gather is None else (fuse_gather and can_fuse)
         if shared_F:
             # the always-on shared expert is one more group: E = 1, every token, rows in place
             self.shared = ExpertGroup(1, d, shared_F, B.MOE_SWIGLU, self.dt, dev)
@@ -150,8 +155,9 @@ class MoELayer:
                          self.expert_idx, self.gate_w, logits_out, stream)
 
     def permute(self, x, stream=None):
+        """x = None: only the sort (counts, offsets, perm, inv_perm); x_perm is left alone."""
         B.moe_permute(x, self.expert_idx, self.T, self.d, self.E, self.k, self.dt, self.counts, self.offsets,
-                      self.perm, self.inv_perm, self.x_perm, self.ws, self.ws_bytes, stream)
+                      self.perm, self.inv_perm, None if x is None else self.x_perm, self.ws, self.ws_bytes, stream)
 
     def plan(self, stream=None):
         B.moe_plan_tiles(self.counts, self.offsets, self.E, self.A, self.tile_m, self.n_bins, self.q_tokens,
@@ -183,6 +189,29 @@ class MoELayer:
         (a router that samples ids, section 5.1's synthetic skew): step 1 is skipped."""
         if not routed:
             self.route(x, None, stream)
+        if self.fuse_gather:
+            # the first product gathers its rows from x itself (no x_perm); for top-1 the second one
+            # also writes y directly
+            self.permute(None, stream)
+            self.plan(stream)
+            g = self.experts
+            args = (x, self.T, self.d, self.F, self.E, self.k, self.act, self.dt, g.in_ptrs, g.out_ptrs, self.tiles,
+                    self.plan_hdr, self.tile_m, self.h, self.perm, self.gate_w, self.y if self.k == 1 else self.y_perm,
+                    stream)
+            if marks is None:
+                B.moe_grouped_ffn_fused(*args)
+            else:
+                marks[0].record()
+                B.moe_grouped_ffn_fused_phase(1, *args)
+                marks[1].record()
+                B.moe_grouped_ffn_fused_phase(2, *args)
+                marks[2].record()
+            if self.k == 1:
+                return self.y
+            if self.shared_F:
+                self.shared_ffn(x, stream)
+            self.combine(True, stream)
+            return self.y
         self.permute(x, stream)
         self.plan(stream)
         if self.fold_combine:

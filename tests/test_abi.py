@@ -157,6 +157,15 @@ def test_pack_combine_copy_argument_errors():
     assert top1(B.MOE_BF16, 512, FAKE, None) == B.MOE_ERR_ARG
     assert status(B.moe_grouped_ffn_top1_phase, 3, FAKE, 8, 64, 512, 2, B.MOE_RELU, B.MOE_BF16, FAKE, FAKE, FAKE, FAKE,
                   128, FAKE, FAKE, None, FAKE, 0) == B.MOE_ERR_ARG
+    fused = lambda dt=B.MOE_BF16, T=8, d=256, F=512, k=1, tile_m=128, perm=FAKE, y=FAKE: status(
+        B.moe_grouped_ffn_fused, FAKE, T, d, F, 2, k, B.MOE_RELU, dt, FAKE, FAKE, FAKE, FAKE, tile_m, FAKE, perm, None, y, 0)
+    assert fused(dt=B.MOE_F32) == B.MOE_ERR_UNSUPPORTED and fused(tile_m=256) == B.MOE_ERR_UNSUPPORTED
+    assert fused(d=192) == B.MOE_ERR_UNSUPPORTED and fused(F=448) == B.MOE_ERR_UNSUPPORTED       # top-1 needs F >= 512
+    assert fused(T=2 ** 24, d=256) == B.MOE_ERR_UNSUPPORTED                                        # x of 8 GiB
+    assert fused(k=0) == B.MOE_ERR_ARG and fused(perm=None) == B.MOE_ERR_ARG and fused(y=None) == B.MOE_ERR_ARG
+    assert fused(T=0, perm=None, y=None) == B.MOE_OK
+    assert status(B.moe_grouped_ffn_fused_phase, 0, FAKE, 8, 256, 512, 2, 1, B.MOE_RELU, B.MOE_BF16, FAKE, FAKE, FAKE, FAKE,
+                  128, FAKE, FAKE, None, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_pack_w_out, None, 1, 8, 32, B.MOE_BF16, FAKE, 0) == B.MOE_ERR_ARG
     assert status(B.moe_pack_w_out, FAKE, 1, 8, 8, 7, FAKE, 0) == B.MOE_ERR_UNSUPPORTED
     assert status(B.moe_pack_w_out, None, 0, 8, 8, B.MOE_BF16, None, 0) == B.MOE_OK

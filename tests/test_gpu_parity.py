@@ -294,13 +294,17 @@ def _stage_check(torch, wl, inp, tol_scale=1.0, flip_tol=1e-3, **layer_kw):
     x = layer_x(layer, inp)
     y = layer.forward(x)
     torch.cuda.synchronize()
-    if layer.fold_combine:
-        # forward() took the top-1 entry point (no y_perm); the separate calls must give the same bits
-        y_folded = y.clone()
+    if layer.fold_combine or layer.fuse_gather:
+        # forward() took a fused entry point (no x_perm and / or no y_perm); the separate calls
+        # must give the same bits
+        y_fused = y.clone()
+        layer.permute(x)
         layer.ffn()
+        if layer.shared_F:
+            layer.shared_ffn(x)
         layer.combine(True)
         torch.cuda.synchronize()
-        assert torch.equal(y_folded, layer.y)
+        assert torch.equal(y_fused, layer.y)
     idx_o, w_o, _ = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
     assert np.array_equal(to_numpy(layer.expert_idx), idx_o)
     p = O.permute(idx_o, wl.E)
@@ -561,6 +565,53 @@ def test_ffn_top1_is_ffn_then_combine(torch_gpu, T, d, F, E, gate, skew):
                                L.h, L.perm, L.gate_w if gate else None, L.y)
         torch.cuda.synchronize()
         assert torch.equal(L.y, y_sep), rep
+    assert int(L.plan_hdr[B.MOE_PLAN_HDR_CTR:].abs().sum()) == 0      # the work counters are back at zero
+
+
+@pytest.mark.parametrize("T,d,F,E,k,act,skew", [(1500, 256, 512, 16, 1, "relu", "zipf"), (1500, 256, 512, 16, 2, "swiglu", "zipf"),
+                                                 (4096, 768, 3072, 128, 1, "relu", "zipf"), (777, 320, 640, 5, 3, "relu", "hot"),
+                                                 (300, 1024, 1024, 40, 1, "swiglu", "uniform"), (1, 256, 512, 4, 4, "relu", "uniform")])
+def test_ffn_fused_is_gather_then_ffn(torch_gpu, T, d, F, E, k, act, skew):
+    """moe_grouped_ffn_fused reads the rows moe_permute would have gathered and writes what the
+    separate calls write, bit for bit (H, and y_perm or -- top-1 -- y): ragged tiles, empty
+    experts, the shortest contraction it accepts, and twice in a row on one plan."""
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    from paper_2506_12417_amd.layer import MoELayer
+    dev = torch.device("cuda:0")
+    r = np.random.default_rng(T + F + k)
+    if skew == "zipf":
+        p_e = 1.0 / np.arange(1, E + 1)
+    elif skew == "hot":
+        p_e = np.array([0.9] + [0.1 / (E - 1)] * (E - 1))
+    else:
+        p_e = np.ones(E)
+    if E > k + 1:
+        p_e[E // 2] = 0.0                                 # one expert stays empty
+    ids = np.stack([r.choice(E, size=k, replace=False, p=p_e / p_e.sum()) for _ in range(T)]).astype(np.int32)
+    L = MoELayer(T, d, F, E, k, act, "bf16", 0, tile_m=128, fuse_gather=False)
+    L.experts.w_in.normal_(0, d ** -0.5)
+    B.moe_pack_w_out(torch.randn(E, F, d, device=dev).mul_(F ** -0.5).to(torch.bfloat16), E, F, d, B.MOE_BF16, L.experts.w_out)
+    L.expert_idx.copy_(torch.from_numpy(ids))
+    L.gate_w.copy_(torch.rand(T, k, device=dev) + 0.05)
+    x = torch.randn(T, d, device=dev).to(torch.bfloat16)
+    L.permute(x)
+    L.plan()
+    L.ffn()
+    L.combine(True)
+    torch.cuda.synchronize()
+    h_sep, yp_sep, y_sep = L.h.clone(), L.y_perm.clone(), L.y.clone()
+    g = L.experts
+    for rep in range(2):
+        L.x_perm.fill_(float("nan"))                      # the fused call must not need it
+        L.h.fill_(float("nan"))
+        out = L.y if k == 1 else L.y_perm
+        out.fill_(float("nan"))
+        B.moe_grouped_ffn_fused(x, T, d, F, E, k, L.act, L.dt, g.in_ptrs, g.out_ptrs, L.tiles, L.plan_hdr, L.tile_m,
+                                L.h, L.perm, L.gate_w, out)
+        torch.cuda.synchronize()
+        assert torch.equal(L.h.view(torch.int16), h_sep.view(torch.int16)), rep
+        assert torch.equal(out, y_sep if k == 1 else yp_sep), rep
     assert int(L.plan_hdr[B.MOE_PLAN_HDR_CTR:].abs().sum()) == 0      # the work counters are back at zero
 
 
