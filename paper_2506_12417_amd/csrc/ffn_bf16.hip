@@ -22,7 +22,9 @@
 // Persistent launch, one work-group of 8 wavefronts (2 per SIMD) per CU.  Work-group b serves
 // bin b % n_bins: work-groups are dealt round-robin to the 8 XCDs, so a bin's tiles -- and with
 // them an expert's weights -- stay inside one XCD's L2.  Inside a bin the work items
-// (tile, column block) are taken expert after expert with a fixed stride.
+// (tile, column block) are taken block after block in the order of the plan's table: the first
+// round with a fixed stride, the later ones on demand (a counter per bin), except by the
+// 256-row configuration, which keeps the stride.
 //
 // A work-group's items form ONE stream of K-steps: the operand loads run RING-1 steps ahead of
 // the arithmetic and cross item boundaries, so the next item's first tiles are already on their
