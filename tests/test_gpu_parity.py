@@ -376,6 +376,26 @@ def test_layer_with_very_many_tiles_in_a_bin(torch_gpu, T):
     assert (n_tiles > 3068) == (T == 400000) and int(to_numpy(layer.counts).max()) > 4 * 256 * 128
 
 
+@pytest.mark.parametrize("name,over", [("c2", dict(T=3000, d=256, F=512, E=24)), ("c3", dict(T=700, d=256, F=192, E=12, shared_F=320)),
+                                       ("c4", dict(T=4200, d=256, F=512, E=2, k=1)), ("c1", {})])
+def test_forward_in_two_timed_halves_gives_the_same_output(torch_gpu, name, over):
+    """forward(marks=...) runs the two grouped GEMMs through the *_phase entry points with events
+    between them (what bench.py times); the output is that of the single call, bit for bit."""
+    torch = torch_gpu
+    wl = W.WORKLOADS[name].scaled(**over)
+    inp = W.make_inputs(wl)
+    layer = make_layer(wl, inp)
+    x = layer_x(layer, inp)
+    ref = layer.forward(x).clone()
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    layer.y.fill_(float("nan"))
+    y = layer.forward(x, marks=marks)
+    torch.cuda.synchronize()
+    assert torch.equal(y, ref)
+    assert marks[0].elapsed_time(marks[1]) > 0 and marks[1].elapsed_time(marks[2]) > 0
+
+
 def test_combine_identity_and_error_paths(torch_gpu):
     torch = torch_gpu
     from paper_2506_12417_amd import binding as B

@@ -70,3 +70,14 @@ def test_pre_routed_ids_and_alpha_skew():
     assert abs(float(np.mean(a < 10)) - 0.9) < 0.01
     u = W.alpha_skew_ids(20000, 16, 0.0, 1, 1)
     assert np.bincount(u, minlength=16)[0] == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits without touching a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
