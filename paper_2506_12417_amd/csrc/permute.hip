@@ -22,13 +22,15 @@ __global__ __launch_bounds__(NTH) void hist_kernel(const int32_t* __restrict__ i
     for (int e = threadIdx.x; e < E; e += NTH) h[e] = 0;
     __syncthreads();
     const int base = blockIdx.x * PB;
-    for (int i = threadIdx.x; i < PB; i += NTH) {
-        int a = base + i;
-        if (a < A) {
-            int e = idx[a];
-            if ((unsigned)e < (unsigned)E) atomicAdd(&h[e], 1);
-        }
+    int mine[PB / NTH];                                     // (all loads first: one memory latency, not PB / NTH)
+#pragma unroll
+    for (int j = 0; j < PB / NTH; ++j) {
+        const int a = base + j * NTH + threadIdx.x;
+        mine[j] = a < A ? idx[a] : -1;
     }
+#pragma unroll
+    for (int j = 0; j < PB / NTH; ++j)
+        if ((unsigned)mine[j] < (unsigned)E) atomicAdd(&h[mine[j]], 1);
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += NTH) block_hist[(size_t)blockIdx.x * E + e] = h[e];
 }
@@ -39,10 +41,16 @@ __global__ __launch_bounds__(NTH) void scan_kernel(int32_t* __restrict__ block_h
     __shared__ int tot[MOE_MAX_EXPERTS];
     for (int e = threadIdx.x; e < E; e += NTH) {
         int run = 0;
-        for (int b = 0; b < nb; ++b) {
-            int v = block_hist[(size_t)b * E + e];
-            block_hist[(size_t)b * E + e] = run;
-            run += v;
+        for (int b0 = 0; b0 < nb; b0 += 8) {               // eight loads in flight at a time
+            int v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = b0 + j < nb ? block_hist[(size_t)(b0 + j) * E + e] : 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (b0 + j < nb) {
+                    block_hist[(size_t)(b0 + j) * E + e] = run;
+                    run += v[j];
+                }
         }
         tot[e] = run;
         counts[e] = run;
@@ -67,15 +75,29 @@ __global__ __launch_bounds__(NTH) void rank_kernel(const int32_t* __restrict__ i
     __shared__ int start_of[MOE_MAX_EXPERTS];      // first position of this work-group's assignments of expert e
     __shared__ int scan_buf[2][MOE_MAX_EXPERTS];
     for (int i = threadIdx.x; i < CHUNKS * E; i += NTH) chunk_hist[i] = 0;
+    // this thread's assignments: fetched first, all at once, so that their latency passes under the scan
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int base = blockIdx.x * PB;
+    int my_e[CHUNKS / 4], my_rank[CHUNKS / 4];
+#pragma unroll
+    for (int ci = 0; ci < CHUNKS / 4; ++ci) {
+        const int a = base + (ci * 4 + wave) * 64 + lane;
+        my_e[ci] = a < A ? idx[a] : -1;
+    }
     if (SCAN) {
         static_assert(NTH >= MOE_MAX_EXPERTS, "one thread per expert");
         const int e = threadIdx.x;
         int before = 0, total = 0;
         if (e < E)
-            for (int b = 0; b < nb; ++b) {
-                const int v = block_hist[(size_t)b * E + e];
-                before += b < (int)blockIdx.x ? v : 0;
-                total += v;
+            for (int b0 = 0; b0 < nb; b0 += 8) {           // eight loads in flight at a time
+                int v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = b0 + j < nb ? block_hist[(size_t)(b0 + j) * E + e] : 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    before += b0 + j < (int)blockIdx.x ? v[j] : 0;
+                    total += v[j];
+                }
             }
         // inclusive scan of the totals over the experts (Hillis-Steele, MOE_MAX_EXPERTS entries)
         scan_buf[0][e] = e < E ? total : 0;
@@ -100,18 +122,11 @@ __global__ __launch_bounds__(NTH) void rank_kernel(const int32_t* __restrict__ i
         for (int e = threadIdx.x; e < E; e += NTH) start_of[e] = offsets[e] + block_hist[(size_t)blockIdx.x * E + e];
     }
     __syncthreads();
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int base = blockIdx.x * PB;
-    int my_e[CHUNKS / 4], my_rank[CHUNKS / 4];
 #pragma unroll
     for (int ci = 0; ci < CHUNKS / 4; ++ci) {
         const int c = ci * 4 + wave;
-        const int a = base + c * 64 + lane;
-        int e = -1;
-        if (a < A) {
-            e = idx[a];
-            if ((unsigned)e >= (unsigned)E) e = -1;
-        }
+        int e = my_e[ci];
+        if ((unsigned)e >= (unsigned)E) e = -1;
         unsigned long long peers = __ballot(e >= 0);
         for (int b = 0; b < nbits; ++b) {
             unsigned long long m = __ballot((e >> b) & 1);
