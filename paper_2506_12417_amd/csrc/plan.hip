@@ -278,11 +278,12 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         const int n = blk_n[b], e = blk_e[b];
         const bool is_long = n > tile_m;
         int rank = 0, n_long = 0;
+        // (bitwise, not short-circuit logic: both reads go out together and the loop has no branches)
         for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o) {
             const int n2 = blk_n[o], e2 = blk_e[o];
-            const bool long2 = n2 > tile_m;
+            const int long2 = n2 > tile_m;
             n_long += long2;
-            if (long2 == is_long && (n2 > n || (n2 == n && e2 < e))) ++rank;
+            rank += (long2 == (int)is_long) & ((n2 > n) | ((n2 == n) & (e2 < e)));
         }
         blk_key[b] = (short)(rank | (is_long ? 0x4000 : 0));
         bin_long[g] = n_long;                      // (every block of the bin writes the same number)
@@ -320,8 +321,10 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         };
         const int mine = place(blk_key[b]);
         int before = 0;
-        for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o)
-            if (place(blk_key[o]) < mine) before += blk_t[o];
+        for (int o = bin_blocks[g]; o < bin_blocks[g + 1]; ++o) {
+            const int k2 = blk_key[o], t2 = blk_t[o];
+            before += place(k2) < mine ? t2 : 0;
+        }
         int row = row0[e];
         for (int g2 = 0; g2 < g; ++g2) row += S[e * G + g2];
         const int nt = blk_t[b];
