@@ -21,6 +21,13 @@ What follows which passage:
   combine           Alg. 1 step 6 on already-permuted expert outputs.
   rebalance         Alg. 2 (token rebalancing), taken step by step in the paper's notation.
   token_threshold_q section 4.4, Eq. 1-4 and appendix B.
+  schedule_*        the schedules a plan is made from: Alg. 2 with bins for GPUs (harmoeny), its
+                    starting placement (static), section 5.3.2's even split.
+  schedule_balanced, block_order, tiles_from_schedule
+                    PARITY UNPINNED to the paper: the tile-equalising variant of Alg. 2 and the
+                    order in which a bin lists its work are this library's own choices (the paper
+                    leaves the order inside a GPU open).  They are pinned to Alg. 2 where they
+                    coincide with it, to hand-worked cases and to invariants only.
 
 Readings where the paper is silent (each listed in the design notes): the gate is a softmax over
 all E logits; selection is on the logits, descending, ties to the lower expert index; with
