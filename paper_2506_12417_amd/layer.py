@@ -251,7 +251,8 @@ class PreRoutedShare:
     original order (the gate is applied later, at the rows' source GPU: weights are 1 here).
 
     Experts run in groups: the resident ones first, then the fetched ones `group` at a time, in
-    fetch order; each group is one moe_plan_tiles_subset + moe_grouped_ffn over the same rows."""
+    fetch order; each group is one moe_plan_tiles_subset + moe_grouped_ffn (or its fused form) over
+    the same rows."""
 
     def __init__(self, T: int, d: int, F: int, E: int, n_local: int, n_slots: int, act: str = "relu",
                  dtype: str = "bf16", n_bins: int = XCDS, q_tokens: Optional[int] = None, group: Optional[int] = None,
@@ -268,6 +269,11 @@ class PreRoutedShare:
         self.tile_m = B.moe_ffn_pick_tile_m(self.dt, T, E)
         # a group of fetched experts runs while the next group's copies are in flight
         self.group = group if group is not None else max(1, min(4, n_slots // 2))
+        # one row per expert (k = 1): where the library offers it, the first product gathers its rows
+        # from x and the second one writes every row to its place in y (moe_grouped_ffn_fused), so
+        # that no gather precedes the groups and no combine follows the last one
+        self.fused = (self.dt == B.MOE_BF16 and self.tile_m == 128 and d >= 256 and d % 64 == 0 and F >= 512
+                      and F % 64 == 0 and T * d * 4 < 2 ** 31)
         dev, i32, f32 = self.device, torch.int32, torch.float32
         es = 2 if dtype == "bf16" else 4
         self.rows_in = 2 * F if self.act == B.MOE_SWIGLU else F
@@ -351,8 +357,8 @@ class PreRoutedShare:
             self._host_ptr = {e: self.host_w[e - self.n_local].data_ptr() for e in order}
         B.moe_prefetch_reset(self.engine)
         self.expert_idx.view(-1).copy_(ids)
-        B.moe_permute(x, self.expert_idx, T, self.d, E, 1, self.dt, self.counts, self.offsets, self.perm,
-                      self.inv_perm, self.x_perm, self.ws, self.ws_bytes, stream)
+        B.moe_permute(None if self.fused else x, self.expert_idx, T, self.d, E, 1, self.dt, self.counts, self.offsets,
+                      self.perm, self.inv_perm, None if self.fused else self.x_perm, self.ws, self.ws_bytes, stream)
 
         def fetch(chunk):
             if not chunk:
@@ -366,8 +372,12 @@ class PreRoutedShare:
             B.moe_plan_tiles_subset(self.counts, self.offsets, E, T, self.tile_m, self.n_bins, self.q_tokens,
                                     B.MOE_PLAN_HARMOENY, group_ids, self.tiles, self.tile_capacity, self.plan_hdr,
                                     None, stream)
-            B.moe_grouped_ffn(self.x_perm, T, self.d, self.F, E, self.act, self.dt, self.ptr_dev[0], self.ptr_dev[1],
-                              self.tiles, self.plan_hdr, self.tile_m, self.h, self.y_perm, stream)
+            if self.fused:
+                B.moe_grouped_ffn_fused(x, T, self.d, self.F, E, 1, self.act, self.dt, self.ptr_dev[0], self.ptr_dev[1],
+                                        self.tiles, self.plan_hdr, self.tile_m, self.h, self.perm, None, self.y, stream)
+            else:
+                B.moe_grouped_ffn(self.x_perm, T, self.d, self.F, E, self.act, self.dt, self.ptr_dev[0],
+                                  self.ptr_dev[1], self.tiles, self.plan_hdr, self.tile_m, self.h, self.y_perm, stream)
 
         next_fetch = min(self.n_slots, len(order))
         fetch(order[:next_fetch])                       # fills every slot; copies run while the resident experts compute
@@ -375,7 +385,11 @@ class PreRoutedShare:
             run(list(range(self.n_local)))
         done = 0
         while done < len(order):
-            grp = order[done:done + self.group]
+            # the last expert runs as a group of its own: what follows the last copy -- and nothing
+            # hides it -- is then one expert's work, not a whole group's
+            left = len(order) - done
+            take = self.group if left > self.group or self.group == 1 else max(1, left - 1)
+            grp = order[done:done + take]
             # copies complete in the order they were enqueued: waiting for the group's last one covers the others
             # (a chain of event waits on the compute stream costs far more than one)
             B.moe_prefetch_wait(self.engine, grp[-1], stream)
@@ -386,7 +400,8 @@ class PreRoutedShare:
             nxt = order[next_fetch:next_fetch + len(grp)]  # into the slots just released
             fetch(nxt)
             next_fetch += len(nxt)
-        B.moe_unpermute_combine(self.y_perm, self.inv_perm, None, None, T, self.d, 1, self.y, stream)
+        if not self.fused:
+            B.moe_unpermute_combine(self.y_perm, self.inv_perm, None, None, T, self.d, 1, self.y, stream)
         if self._done is None:
             self._done = torch.cuda.Event()
         self._done.record()

@@ -426,17 +426,20 @@ def _share(torch, wl, inp, n_local, n_slots, group=None):
     return sh
 
 
-@pytest.mark.parametrize("n_slots,group", [(7, None), (3, None), (2, 1), (1, 1)])
-def test_prefetch_overwrite_matches_all_resident(torch_gpu, n_slots, group):
+@pytest.mark.parametrize("n_slots,group,d,F", [(7, None, 128, 256), (3, None, 128, 256), (2, 1, 128, 256), (1, 1, 128, 256),
+                                               (7, None, 256, 512), (2, None, 256, 512)])
+def test_prefetch_overwrite_matches_all_resident(torch_gpu, n_slots, group, d, F):
     """The pre-routed share (rows arrive with their expert ids, some experts live in pinned host
     memory): with every expert resident, with a slot per host expert, and with fewer slots than
     host experts (slots are overwritten while later groups compute) the output must be the same
     bits, and equal to the oracle's per-row FFN within the bf16 tolerance.  Slots are poisoned
-    first, so an expert used before its copy landed, or a slot overwritten too early, shows."""
+    first, so an expert used before its copy landed, or a slot overwritten too early, shows.
+    (d = 256, F = 512: the groups run through moe_grouped_ffn_fused -- no gather before them, no
+    combine after them; the output buffer is poisoned too, every row must be written.)"""
     torch = torch_gpu
     from paper_2506_12417_amd.layer import to_device
-    wl = W.WORKLOADS["c5"].scaled(T=3000, d=128, F=256, E=12, n_local=5)
-    _note("prefetch n_slots=%d group=%s" % (n_slots, group))
+    wl = W.WORKLOADS["c5"].scaled(T=3000, d=d, F=F, E=12, n_local=5)
+    _note("prefetch n_slots=%d group=%s d=%d F=%d" % (n_slots, group, d, F))
     inp = W.make_inputs(wl)
     ids = inp["ids"]
     x = to_device(inp["x"], "cuda:0")
@@ -451,8 +454,10 @@ def test_prefetch_overwrite_matches_all_resident(torch_gpu, n_slots, group):
     counts = np.bincount(ids, minlength=wl.E)
     heavy_first = sorted(range(wl.n_local, wl.E), key=lambda e: (-counts[e], e))
     for order in (None, heavy_first, None):                                # three passes over the same engine
+        assert sh.fused == (d >= 256)
         sh.slots.fill_(0x7f)
         sh.y_perm.fill_(float("nan"))
+        sh.y.fill_(float("nan"))
         torch.cuda.synchronize()
         y = to_numpy(sh.forward(x, ids_d, fetch_order=order))
         torch.cuda.synchronize()
