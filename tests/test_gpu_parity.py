@@ -553,12 +553,14 @@ def test_full_size_workloads_sampled(torch_gpu, name, n_sample):
     assert np.isfinite(y_h).all()
 
 
-@pytest.mark.parametrize("T,d,F,E,gate,skew", [(1500, 128, 512, 16, True, "zipf"), (1500, 128, 512, 16, False, "zipf"),
-                                               (4096, 768, 3072, 128, True, "zipf"), (777, 192, 640, 5, True, "hot"),
-                                               (300, 64, 1024, 40, True, "uniform")])
-def test_ffn_top1_is_ffn_then_combine(torch_gpu, T, d, F, E, gate, skew):
+@pytest.mark.parametrize("T,d,F,E,gate,skew,tile_m", [(1500, 128, 512, 16, True, "zipf", 128), (1500, 128, 512, 16, False, "zipf", 128),
+                                                      (4096, 768, 3072, 128, True, "zipf", 128), (777, 192, 640, 5, True, "hot", 128),
+                                                      (300, 64, 1024, 40, True, "uniform", 128),
+                                                      (5000, 256, 512, 3, True, "hot", 256)])
+def test_ffn_top1_is_ffn_then_combine(torch_gpu, T, d, F, E, gate, skew, tile_m):
     """moe_grouped_ffn_top1 writes what moe_grouped_ffn + moe_unpermute_combine write, bit for bit:
-    ragged tiles, empty experts, with and without gate values, and twice in a row on one plan."""
+    ragged tiles, empty experts, with and without gate values, 256-row tiles, and twice in a row
+    on one plan."""
     torch = torch_gpu
     from paper_2506_12417_amd import binding as B
     from paper_2506_12417_amd.layer import MoELayer
@@ -572,7 +574,7 @@ def test_ffn_top1_is_ffn_then_combine(torch_gpu, T, d, F, E, gate, skew):
         p_e = np.ones(E)
     p_e[E // 2] = 0.0                                     # one expert stays empty
     ids = r.choice(E, size=T, p=p_e / p_e.sum()).astype(np.int32)
-    L = MoELayer(T, d, F, E, 1, "relu", "bf16", 0, tile_m=128)
+    L = MoELayer(T, d, F, E, 1, "relu", "bf16", 0, tile_m=tile_m)
     L.experts.w_in.normal_(0, d ** -0.5)
     B.moe_pack_w_out(torch.randn(E, F, d, device=dev).mul_(F ** -0.5).to(torch.bfloat16), E, F, d, B.MOE_BF16, L.experts.w_out)
     L.expert_idx.copy_(torch.from_numpy(ids).view(T, 1))
