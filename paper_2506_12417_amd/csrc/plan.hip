@@ -58,7 +58,6 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     __shared__ int s_tavg, s_moves;
     const int tid = threadIdx.x, lane = tid & 63;
     const bool by_cost = (policy == MOE_PLAN_BALANCED);
-    (void)A;
 
     for (int i = tid; i < E * G; i += NTH) S[i] = 0;
     if (tid < G) { load[tid] = 0; bin_blocks[tid] = 0; bin_cursor[tid] = 0; bin_tiles[tid] = 0; }
@@ -166,6 +165,18 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         int moves = 0;
         // the largest block of bin g (most rows, lowest expert among equals)
         auto largest_block = [&](int g, int& e_max, int& rows) {
+            if (A < (1 << 24)) {
+                // rows and expert in one key (rows << 8 | 255 - expert): one pass, one reduction
+                unsigned key = 0;
+                for (int e = lane; e < E; e += 64) {
+                    const unsigned k2 = ((unsigned)S[e * G + g] << 8) | (unsigned)(255 - e);
+                    key = k2 > key ? k2 : key;
+                }
+                key = moe_wave_max_u32(key);
+                rows = (int)(key >> 8);
+                e_max = 255 - (int)(key & 255u);
+                return;
+            }
             int best = -1;
             for (int e = lane; e < E; e += 64) {
                 const int sv = S[e * G + g];
