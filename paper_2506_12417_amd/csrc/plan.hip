@@ -245,11 +245,18 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     __syncthreads();
 
     // ---- the non-empty blocks of every bin, gathered into per-bin segments (any order)
-    for (int p = tid; p < E * G; p += NTH) {
-        const int n = S[p];
-        if (sched) sched[p] = n;
-        if (n > 0) atomicAdd(&bin_blocks[p % G], 1);
-    }
+    // Thread t serves bin t % G and the experts t / G, t / G + NTH / G, ...: it counts its blocks
+    // and reserves their places with ONE atomic per pass (an atomic per block made 32 lanes of a
+    // wavefront queue up on each of the few bin counters).
+    if (sched)
+        for (int p = tid; p < E * G; p += NTH) sched[p] = S[p];
+    const int per_bin = NTH / G;                             // threads per bin
+    const int my_g = tid % G, my_j = tid / G;
+    const bool serving = my_j < per_bin;
+    int my_blocks = 0;
+    if (serving)
+        for (int e = my_j; e < E; e += per_bin) my_blocks += S[e * G + my_g] > 0;
+    if (my_blocks) atomicAdd(&bin_blocks[my_g], my_blocks);
     __syncthreads();
     if (tid == 0) {
         int run = 0;
@@ -257,17 +264,21 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         bin_blocks[G] = run;
     }
     __syncthreads();
-    for (int p = tid; p < E * G; p += NTH) {
-        const int n = S[p];
-        if (n > 0) {
-            const int g = p % G;
-            const int at = bin_blocks[g] + atomicAdd(&bin_cursor[g], 1);
-            const int nt = (n + tile_m - 1) / tile_m;
-            blk_n[at] = n;
-            blk_e[at] = (unsigned char)(p / G);
-            blk_t[at] = nt;
-            atomicAdd(&bin_tiles[g], nt);
+    if (my_blocks) {
+        int at = bin_blocks[my_g] + atomicAdd(&bin_cursor[my_g], my_blocks), my_tiles = 0;
+        for (int e = my_j; e < E; e += per_bin) {
+            const int n = S[e * G + my_g];
+            if (n > 0) {
+                const int nt = (n + tile_m - 1) / tile_m;
+                blk_n[at] = n;
+                blk_e[at] = (unsigned char)e;
+                blk_t[at] = nt;
+                blk_key[at] = (short)my_g;                   // (the bin, until the block's rank replaces it)
+                my_tiles += nt;
+                ++at;
+            }
         }
+        atomicAdd(&bin_tiles[my_g], my_tiles);
     }
     __syncthreads();
 
@@ -284,8 +295,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     // where they even out the finishing times of the work-groups.
     const int n_blocks = bin_blocks[G];
     for (int b = tid; b < n_blocks; b += NTH) {
-        int g = 0;
-        while (b >= bin_blocks[g + 1]) ++g;
+        const int g = blk_key[b];
         const int n = blk_n[b], e = blk_e[b];
         const bool is_long = n > tile_m;
         int rank = 0, n_long = 0;
@@ -296,7 +306,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
             n_long += long2;
             rank += (long2 == (int)is_long) & ((n2 > n) | ((n2 == n) & (e2 < e)));
         }
-        blk_key[b] = (short)(rank | (is_long ? 0x4000 : 0));
+        blk_key[b] = (short)(rank | (g << 9) | (is_long ? 0x4000 : 0));
         bin_long[g] = n_long;                      // (every block of the bin writes the same number)
     }
     if (tid == 0) {
@@ -316,8 +326,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
     }
     __syncthreads();
     for (int b = tid; b < n_blocks; b += NTH) {
-        int g = 0;
-        while (b >= bin_blocks[g + 1]) ++g;
+        const int g = (blk_key[b] >> 9) & (MOE_MAX_BINS - 1);
         const int n = blk_n[b], e = blk_e[b];
         const bool is_long = n > tile_m;
         const int n_long = bin_long[g];
@@ -327,7 +336,7 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
         const bool merged = n_long > 0 && n_long <= n_short;
         auto place = [&](int k) {
             const bool lng = (k & 0x4000) != 0;
-            const int rank = k & 0x3fff;
+            const int rank = k & 0x1ff;
             return merged ? 2 * (2 * rank + 1) * (lng ? n_short : n_long) + (lng ? 0 : 1) : (lng ? rank : 0x4000 + rank);
         };
         const int mine = place(blk_key[b]);
