@@ -19,10 +19,12 @@ What follows which passage:
                     order (step 6, "reconstruct").  Computed per token straight from the
                     definition, without the permutation, so a permutation mistake cannot cancel.
   combine           Alg. 1 step 6 on already-permuted expert outputs.
-  rebalance         Alg. 2 (token rebalancing), taken step by step in the paper's notation.
+  rebalance         Alg. 2 / section 4.2 (token rebalancing): pick_move() takes one decision of
+                    the greedy loop, rebalance() applies decisions until none is left.
   token_threshold_q section 4.4, Eq. 1-4 and appendix B.
   schedule_*        the schedules a plan is made from: Alg. 2 with bins for GPUs (harmoeny), its
-                    starting placement (static), section 5.3.2's even split.
+                    starting placement (static), section 5.3.2's round-robin placement and
+                    even split.
   schedule_balanced, block_order, tiles_from_schedule
                     PARITY UNPINNED to the paper: the tile-equalising variant of Alg. 2 and the
                     order in which a bin lists its work are this library's own choices (the paper
@@ -246,33 +248,83 @@ def initial_assign(m_all: np.ndarray, home: Sequence[int], G: int) -> np.ndarray
     return S
 
 
-def rebalance(S_initial: np.ndarray, q: int, max_iters: int = 1_000_000) -> np.ndarray:
-    """Token rebalancing, Alg. 2.  S[g_from, e, g_to] int64; q >= 1 is the transfer threshold.
-    argmax/argmin take the lowest index among equals (numpy's and the usual tensor-library
-    convention)."""
+class _NoMove(Exception):
+    """Why the greedy loop of Alg. 2 ends: `reason` is one of "balanced" (no destination above the
+    floor average), "small" (the chosen block holds fewer than q tokens) and "no_room" (the
+    emptiest destination is the donor itself, or cannot take q tokens and stay at the average)."""
+
+    def __init__(self, reason: str):
+        super().__init__(reason)
+        self.reason = reason
+
+
+def _first_largest(values) -> int:
+    """Index of the largest value, the lowest index among equals."""
+    best = 0
+    for i, v in enumerate(values):
+        if v > values[best]:
+            best = i
+    return best
+
+
+def _first_smallest(values) -> int:
+    best = 0
+    for i, v in enumerate(values):
+        if v < values[best]:
+            best = i
+    return best
+
+
+def pick_move(S: np.ndarray, load, average: int, q: int):
+    """One decision of Alg. 2 on the state (S, load), with load[g] = tokens bound for GPU g.
+    Returns (source, expert, donor, receiver, tokens) or raises _NoMove.
+
+    The donor is the fullest destination.  Of the sources feeding it, the one whose tokens for
+    the donor, summed over ALL experts, are the most is taken; of that source's experts, the one
+    with the most tokens for the donor.  That single (source, expert) block is the candidate: it
+    must hold q tokens.  The receiver is the emptiest destination and must be able to take q
+    tokens without passing the average; it takes the block, or as much of it as brings it to the
+    average (section 4.2)."""
+    G_src, E, G = S.shape
+    if not any(t > average for t in load):
+        raise _NoMove("balanced")
+    donor = _first_largest(load)
+    per_source = [sum(int(S[s, e, donor]) for e in range(E)) for s in range(G_src)]
+    source = _first_largest(per_source)
+    expert = _first_largest([int(S[source, e, donor]) for e in range(E)])
+    block = int(S[source, expert, donor])
+    if block < q:
+        raise _NoMove("small")
+    receiver = _first_smallest(load)
+    room = average - load[receiver]
+    if receiver == donor or room < q:
+        raise _NoMove("no_room")
+    return source, expert, donor, receiver, min(block, room)
+
+
+def rebalance(S_initial: np.ndarray, q: int, max_iters: int = 1_000_000, moves: Optional[list] = None
+              ) -> np.ndarray:
+    """Token rebalancing, Alg. 2 / section 4.2.  S[g_from, e, g_to] int64; q >= 1 is the transfer
+    threshold.  The average is the floor of total / |G|.  Every "most" / "least" takes the lowest
+    index among equals.  `moves`, if given, receives every transfer as
+    (source, expert, donor, receiver, tokens) in the order they are made."""
     if q < 1:
         raise ValueError("q must be >= 1 (with q = 0 the loop can move zero tokens forever)")
     S = np.array(S_initial, dtype=np.int64, copy=True)
     G = S.shape[2]
-    t_avg = int(S.sum()) // G
-    t_g = S.sum(axis=(0, 1))
+    load = [int(S[:, :, g].sum()) for g in range(G)]
+    average = sum(load) // G
     for _ in range(max_iters):
-        if not np.any(t_g > t_avg):
+        try:
+            source, expert, donor, receiver, n = pick_move(S, load, average, q)
+        except _NoMove:
             break
-        g_max = int(np.argmax(t_g))
-        g_from = int(np.argmax(S[:, :, g_max].sum(axis=1)))
-        e_max = int(np.argmax(S[g_from, :, g_max]))
-        t_move = int(S[g_from, e_max, g_max])
-        if t_move < q:
-            return S
-        g_min = int(np.argmin(t_g))
-        if g_min == g_max or t_g[g_min] + q > t_avg:
-            return S
-        t_s = min(t_move, t_avg - int(t_g[g_min]))
-        S[g_from, e_max, g_max] -= t_s
-        S[g_from, e_max, g_min] += t_s
-        t_g[g_max] -= t_s
-        t_g[g_min] += t_s
+        S[source, expert, donor] -= n
+        S[source, expert, receiver] += n
+        load[donor] -= n
+        load[receiver] += n
+        if moves is not None:
+            moves.append((source, expert, donor, receiver, n))
     return S
 
 
@@ -311,9 +363,21 @@ def contiguous_home(E: int, G: int):
     return [(e * G) // E for e in range(E)]
 
 
+def round_robin_home(E: int, G: int):
+    """Experts dealt to the GPUs in turn (section 5.3.2, policy 1): expert e lives on GPU e mod G."""
+    return [e % G for e in range(E)]
+
+
 def schedule_static(counts, G: int) -> np.ndarray:
     counts = np.asarray(counts, dtype=np.int64)
     return initial_assign(counts[None, :], contiguous_home(len(counts), G), G)[0]
+
+
+def schedule_round_robin(counts, G: int) -> np.ndarray:
+    """Round-robin policy (section 5.3.2, policy 1): experts dealt to the GPUs in turn, every
+    token goes to the GPU that houses its expert, whatever the imbalance."""
+    counts = np.asarray(counts, dtype=np.int64)
+    return initial_assign(counts[None, :], round_robin_home(len(counts), G), G)[0]
 
 
 def schedule_harmoeny(counts, G: int, q: int) -> np.ndarray:
@@ -347,8 +411,7 @@ def schedule_balanced(counts, G: int, q: int, tile_m: int, by_cost: bool = True)
        block, floor(difference / 2)) tiles of the largest block (most rows, lowest expert among
        equals) of the most loaded bin to the least loaded one: the whole block if m covers it,
        else m * tile_m rows.  q is not used.
-    by_cost=False: weights are row counts, the granule is one row, the stop rules are those of
-    the printed loop (a move needs q rows, the receiver stays below the average): step 2 IS Alg. 2."""
+    by_cost=False: weights are row counts and step 2 is rebalance() itself (one source)."""
     counts = np.asarray(counts, dtype=np.int64)
     E = len(counts)
     tiles_of = lambda n: (int(n) + tile_m - 1) // tile_m
@@ -377,24 +440,7 @@ def schedule_balanced(counts, G: int, q: int, tile_m: int, by_cost: bool = True)
             S[e_max, g_max] = n_from - t_s
             S[e_max, g_min] = n_to + t_s
         return S
-    t_avg = int(t_g.sum()) // G
-    for _ in range(E * G + 16):
-        if not np.any(t_g > t_avg):
-            break
-        g_max = int(np.argmax(t_g))
-        e_max = int(np.argmax(S[:, g_max]))
-        t_move = int(S[e_max, g_max])
-        if t_move < q:
-            break
-        g_min = int(np.argmin(t_g))
-        if g_min == g_max or t_g[g_min] + q > t_avg:
-            break
-        t_s = min(t_move, t_avg - int(t_g[g_min]))
-        t_g[g_max] -= t_s
-        t_g[g_min] += t_s
-        S[e_max, g_max] -= t_s
-        S[e_max, g_min] += t_s
-    return S
+    return rebalance(S[None, :, :], q)[0]
 
 
 def block_order(rows_of: dict, tile_m: int):

@@ -371,11 +371,123 @@ def test_rebalance_invariants_random():
         t_avg = m_all.sum() // G
         assert t1.max() <= t0.max()
         assert np.all(t1[t0 <= t_avg] <= t_avg)               # a receiver is never pushed above the average
-        moved = S - S0
-        assert np.all((moved == 0) | (np.abs(moved) >= 1))
-        # a GPU only ever gains tokens in blocks of at least q
-        gains = moved[moved > 0]
-        assert gains.size == 0 or gains.min() >= 1
+        # Receivers never pass the average, so they never become donors: an entry of S that grew
+        # only ever grew, by whole moves, and every move carries at least q tokens
+        # (t_s = min(t_move, room) with t_move >= q and room >= q).
+        moves = []
+        assert np.array_equal(O.rebalance(S0, q, moves=moves), S)
+        assert all(n >= q for *_, n in moves)
+        gains = (S - S0)[(S - S0) > 0]
+        assert gains.size == 0 or gains.min() >= q
+        replay = S0.copy()
+        for s_, e_, donor, recv, n in moves:
+            assert home[e_] == donor or replay[s_, e_, donor] > 0
+            replay[s_, e_, donor] -= n
+            replay[s_, e_, recv] += n
+        assert np.array_equal(replay, S)
+        # stopping: balanced, or the next candidate is too small, or the emptiest GPU has no room for q
+        if t1.max() > t_avg:
+            with pytest.raises(O._NoMove) as why:
+                O.pick_move(S, [int(v) for v in t1], int(t_avg), q)
+            assert why.value.reason in ("small", "no_room")
+
+
+def _schedule(G_src, E, G, entries):
+    S = np.zeros((G_src, E, G), dtype=np.int64)
+    for (s_, e_, g_), n in entries.items():
+        S[s_, e_, g_] = n
+    return S
+
+
+def test_rebalance_source_is_chosen_by_its_sum_over_experts():
+    """Hand-worked, Alg. 2: the source GPU is the one that sends the most tokens to the fullest
+    GPU summed over all experts, NOT the one holding the largest single block.
+    3 sources, 4 experts, 3 GPUs; experts 2 and 3 both live on GPU 2.  q = 1.
+        tokens per (source, expert):  source 0: 1 1 4 6 | source 1: 1 1 7 0 | source 2: 0 1 1 1
+    Loads 2, 3, 19; total 24, average 8.
+    Move 1: fullest GPU 2.  Sources send it 10, 7, 2 -> source 0 (its largest block is 6, while
+            source 1 holds a block of 7).  Expert 3 (6 tokens).  Emptiest GPU 0 has room 8-2 = 6
+            -> all 6 go.  Loads 8, 3, 13.
+    Move 2: fullest GPU 2.  Sources send it 4, 7, 2 -> source 1, expert 2 (7 tokens).  Emptiest
+            GPU 1 has room 5 -> 5 go.  Loads 8, 8, 8: balanced."""
+    m_all = np.array([[1, 1, 4, 6], [1, 1, 7, 0], [0, 1, 1, 1]])
+    home = [0, 1, 2, 2]
+    S0 = O.initial_assign(m_all, home, 3)
+    assert S0.sum(axis=(0, 1)).tolist() == [2, 3, 19]
+    expected = _schedule(3, 4, 3, {
+        (0, 0, 0): 1, (0, 1, 1): 1, (0, 2, 2): 4, (0, 3, 0): 6,
+        (1, 0, 0): 1, (1, 1, 1): 1, (1, 2, 1): 5, (1, 2, 2): 2,
+        (2, 1, 1): 1, (2, 2, 2): 1, (2, 3, 2): 1})
+    moves = []
+    S = O.rebalance(S0, 1, moves=moves)
+    assert np.array_equal(S, expected)
+    assert moves == [(0, 3, 2, 0, 6), (1, 2, 2, 1, 5)]
+    assert S.sum(axis=(0, 1)).tolist() == [8, 8, 8]
+
+
+def test_rebalance_equal_values_go_to_the_lowest_index():
+    """Hand-worked tables for the reading "among equals, the lowest index" (the paper's argmax /
+    argmin say nothing about ties), one case per choice of Alg. 2."""
+    # (a) two equally full GPUs: GPU 0 gives first.  One source, expert e on GPU e, counts 6 6 0,
+    #     average 4.  Move 1: donor 0 (6 = 6), receiver 2 (empty), min(6, 4) = 4 of expert 0.
+    #     Loads 2 6 4.  Move 2: donor 1, receiver 0 (2), room 2: 2 of expert 1.  Loads 4 4 4.
+    S0 = O.initial_assign(np.array([[6, 6, 0]]), [0, 1, 2], 3)
+    moves = []
+    S = O.rebalance(S0, 1, moves=moves)
+    assert S[0].tolist() == [[2, 0, 4], [2, 4, 0], [0, 0, 0]]
+    assert moves == [(0, 0, 0, 2, 4), (0, 1, 1, 0, 2)]
+    # (b) two equally empty GPUs: GPU 1 receives first.  Experts 0 (5 tokens) and 1 (4 tokens) on
+    #     GPU 0, nothing elsewhere; average 3.  Move 1: expert 0's block of 5, receiver 1 (0 = 0),
+    #     room 3 -> 3 tokens.  Loads 6 3 0.  Move 2: blocks left on GPU 0 are 2 and 4 -> expert 1,
+    #     receiver 2, room 3 -> 3 tokens.  Loads 3 3 3.
+    S0 = O.initial_assign(np.array([[5, 4]]), [0, 0], 3)
+    moves = []
+    S = O.rebalance(S0, 1, moves=moves)
+    assert S[0].tolist() == [[2, 3, 0], [1, 0, 3]]
+    assert moves == [(0, 0, 0, 1, 3), (0, 1, 0, 2, 3)]
+    # (c) two equally large blocks: the lower expert moves.  Experts 0 and 1, 4 tokens each, both on
+    #     GPU 0 of 2; average 4.  One move: expert 0, all 4 tokens, to GPU 1.
+    S0 = O.initial_assign(np.array([[4, 4]]), [0, 0], 2)
+    assert O.rebalance(S0, 1)[0].tolist() == [[0, 4], [4, 0]]
+    # (d) two sources sending equally much: the lower source.  Both send 3 tokens of expert 0 to
+    #     GPU 0 of 2; average 3.  One move: source 0's block, 3 tokens, to GPU 1.
+    S0 = O.initial_assign(np.array([[3], [3]]), [0], 2)
+    S = O.rebalance(S0, 1)
+    assert S[0].tolist() == [[0, 3]] and S[1].tolist() == [[3, 0]]
+
+
+def test_rebalance_floor_average_and_stop_reasons():
+    # total 14 on 3 GPUs: the average is floor(14/3) = 4; counts 9 3 2 with expert e on GPU e.
+    # Move 1: 9 -> receiver 2 (2), room 2: loads 7 3 4.  Move 2: receiver 1 (3), room 1: 6 4 4.
+    # GPU 0 is still above 4 but the emptiest GPU (1, with 4) has no room: stop.
+    S0 = O.initial_assign(np.array([[9, 3, 2]]), [0, 1, 2], 3)
+    moves = []
+    S = O.rebalance(S0, 1, moves=moves)
+    assert S[0].tolist() == [[6, 1, 2], [0, 3, 0], [0, 0, 2]]
+    assert moves == [(0, 0, 0, 2, 2), (0, 0, 0, 1, 1)]
+    for load, S_, q, reason in (([4, 4, 4], S, 1, "balanced"), ([6, 4, 4], S, 1, "no_room"),
+                                ([9, 3, 2], S0, 10, "small"), ([9, 3, 2], S0, 3, "no_room")):
+        with pytest.raises(O._NoMove) as why:
+            O.pick_move(S_, load, 4, q)
+        assert why.value.reason == reason, (load, q)
+    # the amount is the block when the block is the smaller one: loads 3 0 with average 1 and a
+    # block of 1 -> only that block moves even though there is room for one... and exactly one
+    S0 = O.initial_assign(np.array([[1, 1, 1]]), [0, 0, 0], 2)          # average floor(3/2) = 1
+    assert O.pick_move(S0, [3, 0], 1, 1) == (0, 0, 0, 1, 1)
+
+
+def test_even_split_and_round_robin_hand_tables():
+    """Section 5.3.2.  Even Split: a tokens of an expert over four GPUs -> a/4 each; the remainder
+    (which the paper's example leaves open) one token each to the lowest-numbered GPUs.
+    Round-robin: experts dealt to the GPUs in turn, no rebalancing."""
+    S = O.schedule_even_split([7, 3, 0, 8, 1], 4)
+    assert S.tolist() == [[2, 2, 2, 1], [1, 1, 1, 0], [0, 0, 0, 0], [2, 2, 2, 2], [1, 0, 0, 0]]
+    assert O.round_robin_home(7, 3) == [0, 1, 2, 0, 1, 2, 0]
+    S = O.schedule_round_robin([5, 0, 2, 9, 1, 4, 3], 3)
+    assert S.tolist() == [[5, 0, 0], [0, 0, 0], [0, 0, 2], [9, 0, 0], [0, 1, 0], [0, 0, 4], [3, 0, 0]]
+    assert S.sum(axis=0).tolist() == [17, 1, 6]
+    # contiguous placement of the same counts, for contrast (Fig. 2: neighbours share a GPU)
+    assert O.schedule_static([5, 0, 2, 9, 1, 4, 3], 3).sum(axis=0).tolist() == [7, 10, 7]
 
 
 # ------------------------------------------------------------------------------------ threshold q
