@@ -172,22 +172,27 @@ __global__ __launch_bounds__(NTH) void gather_rows_kernel(const uint4* __restric
 
 }  // namespace
 
-extern "C" int moe_permute(const void* x, const int32_t* expert_idx, int T, int d, int E, int k, moe_dtype dt,
-                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
-                           void* ws, size_t ws_bytes, void* stream) {
-    MOE_REQUIRE(moe_dtype_ok(dt), MOE_ERR_UNSUPPORTED, "moe_permute: dtype %d", (int)dt);
-    MOE_REQUIRE(T >= 0 && E >= 1 && k >= 1 && d >= 1, MOE_ERR_ARG, "moe_permute: T=%d d=%d E=%d k=%d", T, d, E, k);
-    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "moe_permute: E=%d > %d", E, MOE_MAX_EXPERTS);
-    MOE_REQUIRE((long long)T * k < (1ll << 30), MOE_ERR_UNSUPPORTED, "moe_permute: T*k too large");
-    MOE_REQUIRE((x == nullptr) == (x_perm == nullptr), MOE_ERR_ARG, "moe_permute: x and x_perm must both be given or both be null");
-    MOE_REQUIRE(((size_t)d * moe_elem_size(dt)) % 16 == 0, MOE_ERR_UNSUPPORTED, "moe_permute: row of %d elements is not a multiple of 16 bytes", d);
-    MOE_REQUIRE(counts && offsets && ws, MOE_ERR_ARG, "moe_permute: null pointer");
-    MOE_REQUIRE(ws_bytes >= moe_workspace_bytes(MOE_OP_PERMUTE, T, d, 0, E, k, dt), MOE_ERR_WORKSPACE,
-                "moe_permute: workspace %zu < %zu bytes", ws_bytes, moe_workspace_bytes(MOE_OP_PERMUTE, T, d, 0, E, k, dt));
+// Argument checks shared by the two entry points (nothing is enqueued on an error).
+static int permute_check(const char* who, const void* x, const int32_t* expert_idx, int T, int d, int E, int k,
+                         moe_dtype dt, const int32_t* counts, const int32_t* offsets, const int32_t* perm,
+                         const int32_t* inv_perm, const void* x_perm) {
+    MOE_REQUIRE(moe_dtype_ok(dt), MOE_ERR_UNSUPPORTED, "%s: dtype %d", who, (int)dt);
+    MOE_REQUIRE(T >= 0 && E >= 1 && k >= 1 && d >= 1, MOE_ERR_ARG, "%s: T=%d d=%d E=%d k=%d", who, T, d, E, k);
+    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "%s: E=%d > %d", who, E, MOE_MAX_EXPERTS);
+    MOE_REQUIRE((long long)T * k < (1ll << 30), MOE_ERR_UNSUPPORTED, "%s: T*k too large", who);
+    MOE_REQUIRE((x == nullptr) == (x_perm == nullptr), MOE_ERR_ARG, "%s: x and x_perm must both be given or both be null", who);
+    MOE_REQUIRE(((size_t)d * moe_elem_size(dt)) % 16 == 0, MOE_ERR_UNSUPPORTED, "%s: row of %d elements is not a multiple of 16 bytes", who, d);
+    MOE_REQUIRE(counts && offsets, MOE_ERR_ARG, "%s: null pointer", who);
+    MOE_REQUIRE((long long)T * k == 0 || (expert_idx && perm && inv_perm), MOE_ERR_ARG, "%s: null pointer", who);
+    return MOE_OK;
+}
+
+// The launches of the sort; block_hist holds one histogram of E counters per block of PB
+// assignments (every entry is written by hist_kernel before anything reads it).
+static int permute_launch(const void* x, const int32_t* expert_idx, int T, int d, int E, int k, moe_dtype dt,
+                          int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
+                          int32_t* block_hist, hipStream_t st) {
     const int A = T * k;
-    MOE_REQUIRE(A == 0 || (expert_idx && perm && inv_perm), MOE_ERR_ARG, "moe_permute: null pointer");
-    hipStream_t st = (hipStream_t)stream;
-    int32_t* block_hist = (int32_t*)ws;
     const int nb = A == 0 ? 1 : (A + PB - 1) / PB;
     int nbits = 0;
     while ((1 << nbits) < E) ++nbits;
@@ -219,4 +224,16 @@ extern "C" int moe_permute(const void* x, const int32_t* expert_idx, int T, int 
         MOE_CHECK_LAUNCH("moe_permute/gather");
     }
     return MOE_OK;
+}
+
+extern "C" int moe_permute(const void* x, const int32_t* expert_idx, int T, int d, int E, int k, moe_dtype dt,
+                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
+                           void* ws, size_t ws_bytes, void* stream) {
+    const int rc = permute_check("moe_permute", x, expert_idx, T, d, E, k, dt, counts, offsets, perm, inv_perm, x_perm);
+    if (rc != MOE_OK) return rc;
+    MOE_REQUIRE(ws, MOE_ERR_ARG, "moe_permute: null pointer");
+    MOE_REQUIRE(ws_bytes >= moe_workspace_bytes(MOE_OP_PERMUTE, T, d, 0, E, k, dt), MOE_ERR_WORKSPACE,
+                "moe_permute: workspace %zu < %zu bytes", ws_bytes, moe_workspace_bytes(MOE_OP_PERMUTE, T, d, 0, E, k, dt));
+    return permute_launch(x, expert_idx, T, d, E, k, dt, counts, offsets, perm, inv_perm, x_perm, (int32_t*)ws,
+                          (hipStream_t)stream);
 }
