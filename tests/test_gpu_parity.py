@@ -216,6 +216,41 @@ def test_plan_tiles_all_policies(torch_gpu, policy):
             assert np.array_equal(hdr_h[4:4 + G + 1], bin_start_o)
             assert np.array_equal(tiles_h[:n], tiles_o)
             O.validate_tiles(tiles_h[:n], hdr_h[4:4 + G + 1], counts, offsets, tile_m, G)
+            if policy == B.MOE_PLAN_HARMOENY:
+                _check_alg2_end_state(tiles_h[:n], counts, G, q, tile_m)
+
+
+def _check_alg2_end_state(tiles, counts, G, q, tile_m):
+    """What section 4.2 promises of the schedule, read off the GPU's tile table alone (one source,
+    so a block is the rows of one expert on one bin).
+    - The greedy loop has nothing left to do: no bin is above the floor average, or the largest
+      block of the fullest bin is below q, or the emptiest bin cannot take q rows.
+    - The balance that follows when it did not stop on a small block: every bin is within
+      (G-1)(q-1) + (A mod G) rows of the average -- the slack q allows; with q = 1 the bins differ
+      by the remainder only -- hence an expert with more rows than that bound is split over bins.
+    - An expert with at least 2 tile_m rows is cut into at least two tiles."""
+    E, A = len(counts), int(counts.sum())
+    block = np.zeros((E, G), dtype=np.int64)
+    n_tiles = np.zeros(E, dtype=np.int64)
+    for e, _, rc, g in tiles:
+        block[e, g] += rc
+        n_tiles[e] += 1
+    load = block.sum(axis=0)
+    avg = A // G
+    g_max, g_min = int(np.argmax(load)), int(np.argmin(load))
+    balanced = load.max() <= avg
+    small = block[:, g_max].max() < q
+    no_room = g_min == g_max or load[g_min] + q > avg
+    assert balanced or small or no_room, "a feasible move was left: loads %s" % load.tolist()
+    if balanced or no_room:
+        bound = avg + (G - 1) * (q - 1) + A % G
+        assert load.max() <= bound
+        for e in range(E):
+            if counts[e] > bound:
+                assert (block[e] > 0).sum() >= 2
+    for e in range(E):
+        if counts[e] >= 2 * tile_m:
+            assert n_tiles[e] >= 2
 
 
 PACK_CASES = [("f32", 1, 64, 128, False), ("bf16", 3, 768, 3072 // 4, False), ("bf16", 2, 96, 160, True),
@@ -551,6 +586,76 @@ def test_full_size_workloads_sampled(torch_gpu, name, n_sample):
     print("   %s: %d tokens, max err / rms = %.3e (tol %.0e)" % (name, tok.size, err, TOL[wl.dtype]), flush=True)
     assert err <= TOL[wl.dtype]
     assert np.isfinite(y_h).all()
+
+
+def test_full_size_prerouted_share_with_host_experts(torch_gpu):
+    """c5 at its stated size (32768 rows, 16 resident + 16 host-resident experts, d = 768,
+    F = 3072), in the launch configuration bench.py times: all experts resident, then the
+    section 4.3 flow with a slot per host expert and with 4 slots (overwrite), by id and
+    heaviest first.  Integer stages in full; the output bit-identical between the flows, and on a
+    seeded sample of rows plus the first and last row of every expert's group against the
+    oracle's per-row definition (weights 1: the gate is applied at the rows' source GPU)."""
+    torch = torch_gpu
+    from paper_2506_12417_amd.layer import to_device
+    wl = W.WORKLOADS["c5"]
+    _note("full size c5: drawing inputs")
+    inp = W.make_inputs(wl)
+    ids = inp["ids"]
+    x = to_device(inp["x"], "cuda:0")
+    ids_d = torch.from_numpy(ids).to("cuda:0")
+    counts = np.bincount(ids, minlength=wl.E)
+    offsets = np.concatenate([[0], np.cumsum(counts)])
+    perm_o = np.argsort(ids, kind="stable")
+    inv_o = np.empty_like(perm_o)
+    inv_o[perm_o] = np.arange(perm_o.size)
+    assert abs(counts[wl.n_local:].sum() / wl.T - 0.30) < 0.02          # the workload's stated foreign share
+
+    _note("full size c5: all experts resident")
+    ref_layer = _share(torch, wl, inp, n_local=wl.E, n_slots=1)
+    ref_layer.y.fill_(float("nan"))
+    y_res = to_numpy(ref_layer.forward(x, ids_d)).copy()
+    torch.cuda.synchronize()
+    for n, ref in (("counts", counts), ("offsets", offsets), ("perm", perm_o), ("inv_perm", inv_o)):
+        assert np.array_equal(to_numpy(getattr(ref_layer, n)), ref), n
+    tile_m = ref_layer.tile_m
+    ref_layer.close()
+    del ref_layer
+    assert np.isfinite(y_res).all()
+
+    r = np.random.default_rng(55)
+    rows = set(r.choice(wl.T, 256, replace=False).tolist())
+    for e in range(wl.E):
+        if counts[e]:
+            rows.add(int(perm_o[offsets[e]]))
+            rows.add(int(perm_o[offsets[e + 1] - 1]))
+            # the last row of every full tile and the row after it (tile seams)
+            for b in range(tile_m, int(counts[e]), tile_m):
+                if len(rows) < 700:
+                    rows.update((int(perm_o[offsets[e] + b - 1]), int(perm_o[offsets[e] + b])))
+    rows = np.array(sorted(rows))
+    _note("full size c5: oracle on %d rows (tile_m %d)" % (rows.size, tile_m))
+    y_o = O.moe_layer(inp["x"], ids.reshape(-1, 1), np.ones((wl.T, 1)), {n: inp[n] for n in ("W1", "W2")}, wl.act, tokens=rows)
+    err = float(np.abs(y_res[rows].astype(np.float64) - y_o).max()) / float(np.sqrt(np.mean(y_o ** 2)))
+    print("   c5: %d rows, max err / rms = %.3e (tol %.0e)" % (rows.size, err, TOL["bf16"]), flush=True)
+    assert err <= TOL["bf16"]
+
+    heavy_first = sorted(range(wl.n_local, wl.E), key=lambda e: (-counts[e], e))
+    for n_slots in (16, 4):
+        _note("full size c5: %d slots" % n_slots)
+        sh = _share(torch, wl, inp, n_local=wl.n_local, n_slots=n_slots)
+        assert sh.tile_m == tile_m
+        for order in (None, heavy_first):
+            sh.slots.fill_(0x7f)
+            sh.y_perm.fill_(float("nan"))
+            sh.y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            y = to_numpy(sh.forward(x, ids_d, fetch_order=order))
+            torch.cuda.synchronize()
+            assert np.array_equal(y, y_res), "n_slots=%d order=%s" % (n_slots, "by id" if order is None else "heavy first")
+        assert np.array_equal(to_numpy(sh.perm), perm_o) and np.array_equal(to_numpy(sh.counts), counts)
+        assert sh.bytes_fetched == 2 * (wl.E - wl.n_local) * sh.bytes_each
+        sh.close()
+        del sh
 
 
 @pytest.mark.parametrize("T,d,F,E,gate,skew,tile_m", [(1500, 128, 512, 16, True, "zipf", 128), (1500, 128, 512, 16, False, "zipf", 128),
