@@ -108,6 +108,20 @@ MOE_API int moe_permute(const void* x, const int32_t* expert_idx, int T, int d, 
                 int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
                 void* ws, size_t ws_bytes, void* stream);
 
+/* moe_permute for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * kernels, same results; the block histograms go to an array of MOE_PERMUTE_STATIC_BYTES
+ * bytes (1 MiB) that is part of the library's device image, so nothing is allocated, neither
+ * here nor by the caller.  MOE_ERR_CAPACITY if moe_workspace_bytes(MOE_OP_PERMUTE, ...) exceeds
+ * that size (ceil(T*k / 1024) * E * 4 bytes: T*k up to 2 Mi assignments at E = 128); nothing is
+ * enqueued then.  The stream must belong to the current device.  Every call on a GPU uses that
+ * GPU's one array: calls that may run at the same time on one GPU (two streams) race; calls
+ * on one stream are safe, nothing has to be cleared between them. */
+#define MOE_PERMUTE_STATIC_BYTES (1u << 20)
+MOE_API int moe_permute_static(const void* x, const int32_t* expert_idx, int T, int d, int E, int k, moe_dtype dt,
+                int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
+                void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Step 3 on one GPU: the load-aware token schedule (section 4.2, Alg. 2) with the GPU's
  * n_bins XCDs in the role of the paper's GPUs.  S[e,g] = rows of expert e processed by bin g.

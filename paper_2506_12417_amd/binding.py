@@ -27,9 +27,10 @@ MOE_MAX_EXPERTS, MOE_MAX_TOPK, MOE_MAX_BINS = 256, 8, 16
 MOE_PLAN_HDR_CTR = 4 + 2 * (MOE_MAX_BINS + 1)
 MOE_PLAN_HDR_INTS = MOE_PLAN_HDR_CTR + MOE_MAX_BINS + 1
 MOE_OP_PERMUTE = 1
+MOE_PERMUTE_STATIC_BYTES = 1 << 20
 
 EXPORTS = [
-    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_rebalance", "moe_pack_weights", "moe_pack_w_out",
+    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_permute_static", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_rebalance", "moe_pack_weights", "moe_pack_w_out",
     "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_grouped_ffn_top1", "moe_grouped_ffn_top1_phase", "moe_grouped_ffn_fused", "moe_grouped_ffn_fused_phase", "moe_unpermute_combine", "moe_prefetch_create",
     "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_reset", "moe_prefetch_destroy",
     "moe_token_threshold", "moe_workspace_bytes", "moe_copy_bytes", "moe_last_error", "moe_version",
@@ -40,6 +41,7 @@ lib.moe_route_topk.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, 
 lib.moe_pack_router.argtypes = [_vp, _i, _i, _i, _vp, _vp, _vp]
 lib.moe_route_topk_packed.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
 lib.moe_permute.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.moe_permute_static.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.moe_plan_capacity.argtypes = [_i, _i, _i, _i]
 lib.moe_plan_tiles.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp]
 lib.moe_plan_tiles_subset.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), _i, _vp, _i, _vp, _vp, _vp]
@@ -151,6 +153,11 @@ def moe_route_topk_packed(x, w_gate_t, w_norm2, bias, T, d, E, k, renorm, dt, ex
 def moe_permute(x, expert_idx, T, d, E, k, dt, counts, offsets, perm, inv_perm, x_perm, ws, ws_bytes, stream=None):
     _check(lib.moe_permute(_p(x), _p(expert_idx), T, d, E, k, dt, _p(counts), _p(offsets), _p(perm), _p(inv_perm),
                            _p(x_perm), _p(ws), ws_bytes, _stream(stream)))
+
+
+def moe_permute_static(x, expert_idx, T, d, E, k, dt, counts, offsets, perm, inv_perm, x_perm, stream=None):
+    _check(lib.moe_permute_static(_p(x), _p(expert_idx), T, d, E, k, dt, _p(counts), _p(offsets), _p(perm),
+                                  _p(inv_perm), _p(x_perm), _stream(stream)))
 
 
 def moe_plan_tiles(counts, offsets, E, A, tile_m, n_bins, q_tokens, policy, tiles, tile_capacity, plan_hdr,

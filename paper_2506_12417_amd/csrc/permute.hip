@@ -9,6 +9,7 @@
 //      per-64-chunk counts are prefix-summed in LDS -> perm, inv_perm
 //   4. row gather x_perm[r] = x[perm[r] / k], 16 bytes per lane, fully coalesced
 #include "common.h"
+#include <mutex>
 
 namespace {
 
@@ -172,6 +173,30 @@ __global__ __launch_bounds__(NTH) void gather_rows_kernel(const uint4* __restric
 
 }  // namespace
 
+// Scratch of moe_permute_static: the block histograms, in the library's own device memory (each
+// GPU the library runs on holds a copy of this array until the process ends).  Host code never
+// passes the array's name to a kernel: it asks the runtime for the array's address on the
+// current device, once per device, and uses that pointer.
+static __device__ __align__(256) unsigned char scratch[MOE_PERMUTE_STATIC_BYTES];
+
+static int32_t* g_scratch_ptr[64] = {};          // per device, set on first use
+static std::mutex g_scratch_mutex;
+
+static int scratch_on_current_device(int32_t** out) {
+    int dev = -1;
+    MOE_CHECK_HIP(hipGetDevice(&dev));
+    MOE_REQUIRE(dev >= 0 && dev < 64, MOE_ERR_UNSUPPORTED, "moe_permute_static: device %d", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        MOE_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        MOE_REQUIRE(p != nullptr, MOE_ERR_HIP, "moe_permute_static: no address for the scratch array");
+        g_scratch_ptr[dev] = (int32_t*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+
 // Argument checks shared by the two entry points (nothing is enqueued on an error).
 static int permute_check(const char* who, const void* x, const int32_t* expert_idx, int T, int d, int E, int k,
                          moe_dtype dt, const int32_t* counts, const int32_t* offsets, const int32_t* perm,
@@ -235,5 +260,21 @@ extern "C" int moe_permute(const void* x, const int32_t* expert_idx, int T, int 
     MOE_REQUIRE(ws_bytes >= moe_workspace_bytes(MOE_OP_PERMUTE, T, d, 0, E, k, dt), MOE_ERR_WORKSPACE,
                 "moe_permute: workspace %zu < %zu bytes", ws_bytes, moe_workspace_bytes(MOE_OP_PERMUTE, T, d, 0, E, k, dt));
     return permute_launch(x, expert_idx, T, d, E, k, dt, counts, offsets, perm, inv_perm, x_perm, (int32_t*)ws,
+                          (hipStream_t)stream);
+}
+
+extern "C" int moe_permute_static(const void* x, const int32_t* expert_idx, int T, int d, int E, int k, moe_dtype dt,
+                                  int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
+                                  void* stream) {
+    const int rc = permute_check("moe_permute_static", x, expert_idx, T, d, E, k, dt, counts, offsets, perm, inv_perm, x_perm);
+    if (rc != MOE_OK) return rc;
+    const size_t need = moe_workspace_bytes(MOE_OP_PERMUTE, T, d, 0, E, k, dt);
+    MOE_REQUIRE(need <= MOE_PERMUTE_STATIC_BYTES, MOE_ERR_CAPACITY,
+                "moe_permute_static: T*k = %lld with E = %d needs %zu bytes of scratch, the built-in array holds %u "
+                "(use moe_permute with a workspace)", (long long)T * k, E, need, MOE_PERMUTE_STATIC_BYTES);
+    int32_t* block_hist = nullptr;
+    const int rs = scratch_on_current_device(&block_hist);
+    if (rs != MOE_OK) return rs;
+    return permute_launch(x, expert_idx, T, d, E, k, dt, counts, offsets, perm, inv_perm, x_perm, block_hist,
                           (hipStream_t)stream);
 }

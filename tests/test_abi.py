@@ -77,6 +77,21 @@ def test_permute_argument_errors():
     assert call(T=1 << 29, k=4) == B.MOE_ERR_UNSUPPORTED
 
 
+def test_permute_static_argument_errors():
+    def call(x=FAKE, idx=FAKE, T=8, d=64, E=4, k=2, dt=B.MOE_BF16, counts=FAKE, offsets=FAKE, perm=FAKE, inv=FAKE, xp=FAKE):
+        return status(B.moe_permute_static, x, idx, T, d, E, k, dt, counts, offsets, perm, inv, xp, 0)
+
+    assert call(E=0) == B.MOE_ERR_ARG
+    assert call(dt=5) == B.MOE_ERR_UNSUPPORTED
+    assert call(x=None) == B.MOE_ERR_ARG
+    assert call(counts=None) == B.MOE_ERR_ARG
+    # the built-in array holds 1 MiB of block histograms: ceil(T*k / 1024) * E * 4 bytes must fit
+    fits = (B.MOE_PERMUTE_STATIC_BYTES // (4 * 128)) * 1024
+    assert B.moe_workspace_bytes(B.MOE_OP_PERMUTE, fits, 64, 0, 128, 1, B.MOE_BF16) == B.MOE_PERMUTE_STATIC_BYTES
+    assert call(T=fits + 1, k=1, E=128) == B.MOE_ERR_CAPACITY
+    assert "moe_permute" in B.moe_last_error()
+
+
 def test_workspace_and_capacity_closed_forms():
     # one histogram of E int32 counters per block of 1024 assignments
     for T, k, E in ((1, 1, 1), (1024, 1, 8), (1025, 1, 8), (16384, 4, 60), (0, 2, 5)):
