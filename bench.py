@@ -151,48 +151,50 @@ def bench_prerouted(args):
     print(json.dumps(out))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-uniform", action="store_true")
-    ap.add_argument("--no-ablation", action="store_true", help="skip the plan-policy and alpha-skew legs")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain device copy of 256 MiB a few times (reference for scaling "
-                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
-              % args.gpus, file=sys.stderr)
-        sys.exit(2)
+def stage_bytes(wl, name, fused_gather):
+    """Algorithmic HBM bytes of one launch of a stage (s = bytes per activation element):
+    route:   x once + W_g + indices and gate values written
+    permute: the indices twice (histogram, rank) + perm and inv_perm written; with the row gather
+             also x read and x_perm written
+    combine: y_perm, inv_perm and gate values read (+ the shared expert's output), y written"""
+    s = 2 if wl.dtype == "bf16" else 4
+    A = wl.T * wl.k
+    if name == "route":
+        return wl.T * wl.d * s + wl.d * wl.E * s + A * 8
+    if name == "permute":
+        b = 2 * A * 4 + A * 8
+        return b if fused_gather else b + wl.T * wl.d * s + A * wl.d * s
+    if name == "combine":
+        return A * wl.d * 4 + A * 12 + wl.T * wl.d * 4 + (wl.T * wl.d * 4 if wl.shared_F else 0)
+    return None
 
-    import numpy as np
-    import torch
-    import moe_workloads as W
-    from paper_2506_12417_amd import binding as B
-    from paper_2506_12417_amd.layer import MoELayer, to_device
 
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
-    if args.workload == "c5":
-        return bench_prerouted(args)
-    wl = W.WORKLOADS[args.workload]
-    t0 = time.time()
-    inp = W.make_inputs(wl)
-    t_gen = time.time() - t0
-    names = ("W1", "W2") if wl.act == "relu" else ("Wg", "Wu", "Wd")
-    layer = MoELayer(wl.T, wl.d, wl.F, wl.E, wl.k, wl.act, wl.dtype, wl.renorm, shared_F=wl.shared_F)
-    layer.load_router(inp["W_g"], inp["b"])
-    layer.load_experts({n: inp[n] for n in names})
-    if wl.shared_F:
-        layer.load_shared({"Wg": inp["sWg"], "Wu": inp["sWu"], "Wd": inp["sWd"]})
-    x = to_device(inp["x"], layer.device)
-    torch.cuda.synchronize()
-    print("[bench] %s: inputs drawn in %.1fs, weights packed on device" % (wl.name, t_gen), file=sys.stderr, flush=True)
+class Leg:
+    """One workload on the device: inputs drawn, weights packed, the layer ready to step."""
 
-    def timed(steps, warmup, marks_on=True):
+    def __init__(self, name):
+        import torch
+        import moe_workloads as W
+        from paper_2506_12417_amd.layer import MoELayer, to_device
+        self.torch = torch
+        self.wl = wl = W.WORKLOADS[name]
+        t0 = time.time()
+        self.inp = inp = W.make_inputs(wl)
+        t_gen = time.time() - t0
+        self.names = ("W1", "W2") if wl.act == "relu" else ("Wg", "Wu", "Wd")
+        self.layer = layer = MoELayer(wl.T, wl.d, wl.F, wl.E, wl.k, wl.act, wl.dtype, wl.renorm, shared_F=wl.shared_F)
+        layer.load_router(inp["W_g"], inp["b"])
+        layer.load_experts({n: inp[n] for n in self.names})
+        if wl.shared_F:
+            layer.load_shared({"Wg": inp["sWg"], "Wu": inp["sWu"], "Wd": inp["sWd"]})
+        self.x = to_device(inp["x"], layer.device)
+        torch.cuda.synchronize()
+        print("[bench] %s: inputs drawn in %.1fs, weights packed on device" % (wl.name, t_gen), file=sys.stderr, flush=True)
+
+    def timed(self, steps, warmup, marks_on=True):
+        """Mean step time over `steps` steps (HIP events on the launch stream around all of them)
+        and, with marks_on, the mean launch times of the two grouped GEMMs."""
+        torch, layer, x = self.torch, self.layer, self.x
         for _ in range(warmup):
             layer.forward(x)
         torch.cuda.synchronize()
@@ -210,6 +212,106 @@ def main():
             g1 = sum(m[0].elapsed_time(m[1]) for m in marks) / steps
             g2 = sum(m[1].elapsed_time(m[2]) for m in marks) / steps
         return ms, g1, g2
+
+    def stage_times(self, steps):
+        """Mean time of every stage, from events recorded after each stage of the same step
+        sequence (so every stage finds its inputs as cold or warm as in a real step)."""
+        torch, layer, x = self.torch, self.layer, self.x
+        runs = []
+        for _ in range(steps):
+            st = []
+            layer.forward(x, stages=st)
+            runs.append(st)
+        torch.cuda.synchronize()
+        names = [n for n, _ in runs[0][1:]]
+        return {n: sum(r[i][1].elapsed_time(r[i + 1][1]) for r in runs) / steps * 1e3 for i, n in enumerate(names)}
+
+    def stage_hbm(self, steps):
+        us = self.stage_times(steps)
+        out = {}
+        for n in ("route", "permute", "combine"):
+            if n in us:
+                b = stage_bytes(self.wl, n, self.layer.fuse_gather)
+                gbs = b / (us[n] * 1e-6) / 1e9
+                out[n] = {"us": round(us[n], 2), "algorithmic_bytes": int(b), "GBs": round(gbs, 1),
+                          "frac_of_8TBs": round(gbs / HBM_PEAK_GBS, 4)}
+        out["plan_us"] = round(us["plan"], 2)
+        if self.wl.k == 1 and "combine" not in us:
+            out["combine"] = "folded into the second grouped GEMM (top-1): no kernel of its own"
+        if self.layer.fuse_gather:
+            out["permute_note"] = "sort only: the row gather is done by the first grouped GEMM's loads"
+        return out
+
+    def gemm_rates(self, g1_ms, g2_ms):
+        """TFLOP/s of the routed experts' two grouped GEMMs from their mean launch times."""
+        wl = self.wl
+        A = wl.T * wl.k
+        Fp = 2 * wl.F if wl.act == "swiglu" else wl.F
+        f1, f2 = 2.0 * A * wl.d * Fp, 2.0 * A * wl.F * wl.d
+        r = lambda f, ms: f / (ms * 1e-3) / 1e12
+        return {"g1_ms": round(g1_ms, 4), "g2_ms": round(g2_ms, 4),
+                "g1_tflops": round(r(f1, g1_ms), 1), "g2_tflops": round(r(f2, g2_ms), 1),
+                "both_tflops": round(r(f1 + f2, g1_ms + g2_ms), 1),
+                "g1_frac": round(r(f1, g1_ms) / MFMA_BF16_PEAK_TFLOPS, 4), "g2_frac": round(r(f2, g2_ms) / MFMA_BF16_PEAK_TFLOPS, 4),
+                "both_frac": round(r(f1 + f2, g1_ms + g2_ms) / MFMA_BF16_PEAK_TFLOPS, 4)}
+
+    def free(self):
+        self.layer = self.x = self.inp = None
+        self.torch.cuda.empty_cache()
+
+
+def device_copy_rate():
+    """A plain device-to-device copy of 256 MiB (moe_copy_bytes): what this chip's HBM delivers to
+    the simplest streaming kernel, beside the nominal 8 TB/s.  GB/s of bytes read + bytes written."""
+    import torch
+    from paper_2506_12417_amd import binding as B
+    n = 256 << 20
+    src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        B.moe_copy_bytes(src, dst, n)
+    s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    s_ev.record()
+    for _ in range(10):
+        B.moe_copy_bytes(src, dst, n)
+    e_ev.record()
+    torch.cuda.synchronize()
+    ms = s_ev.elapsed_time(e_ev) / 10
+    return {"kernel": "copy_bytes_kernel", "bytes_read_plus_written": 2 * n, "ms": round(ms, 4),
+            "GBs": round(2 * n / (ms * 1e-3) / 1e9, 1), "frac_of_8TBs": round(2 * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-uniform", action="store_true")
+    ap.add_argument("--no-ablation", action="store_true", help="skip the plan-policy and alpha-skew legs")
+    ap.add_argument("--no-mfma-leg", action="store_true",
+                    help="skip the arithmetic-bound workloads (c4, c3) that the default run times after c2")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of 256 MiB a few times (reference for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import moe_workloads as W
+    from paper_2506_12417_amd import binding as B
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.workload == "c5":
+        return bench_prerouted(args)
+    leg = Leg(args.workload)
+    wl, inp, layer, x, names, timed = leg.wl, leg.inp, leg.layer, leg.x, leg.names, leg.timed
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=layer.device).fill_(1)
@@ -261,6 +363,10 @@ def main():
         "roofline": roofline,
     }
 
+    out["gemms"] = leg.gemm_rates(g1_ms, g2_ms)
+    out["stage_hbm"] = leg.stage_hbm(max(5, args.steps // 5))
+    out["device_copy"] = device_copy_rate()
+
     if args.workload == "c2" and not args.no_uniform:
         layer.load_router(inp["W_g"], np.zeros(wl.E, dtype=np.float32))     # same data, router bias 0
         ms_u, _, _ = timed(args.steps, max(3, args.warmup // 2), marks_on=False)
@@ -273,7 +379,8 @@ def main():
         # (same rows, same kernels, bit-identical outputs; only the tile schedule differs).
         # (timed without the event records between the kernels, which cost a few microseconds a step)
         abl = {"alg2": round(timed(max(10, args.steps // 2), 3, marks_on=False)[0], 4)}   # the default: Alg. 2 as printed
-        for name, pol in (("balanced_tiles", B.MOE_PLAN_BALANCED), ("static", B.MOE_PLAN_STATIC), ("even_split", B.MOE_PLAN_EVEN_SPLIT)):
+        for name, pol in (("balanced_tiles", B.MOE_PLAN_BALANCED), ("static", B.MOE_PLAN_STATIC), ("round_robin", B.MOE_PLAN_ROUND_ROBIN),
+                          ("even_split", B.MOE_PLAN_EVEN_SPLIT)):
             layer.policy = pol
             abl[name] = round(timed(max(10, args.steps // 2), 3, marks_on=False)[0], 4)
         layer.policy = B.MOE_PLAN_HARMOENY
@@ -328,6 +435,28 @@ def main():
                              "tokens_per_s_mean": round(float(wl.T / (t.mean() * 1e-3)), 1),
                              "ms_min": round(float(t.min()), 4), "ms_max": round(float(t.max()), 4),
                              "ms_std": round(float(t.std()), 4), "batches": batches}
+
+    if args.workload == "c2" and not args.no_mfma_leg:
+        # The second half of the metric: the grouped FFN's fraction of the bf16 matrix-core peak on
+        # the workloads that are bound by arithmetic (c2 is bound by its weights' bytes).  Same code
+        # path, same launch configuration as `--workload c4` / `--workload c3`, fewer steps.
+        leg.free()
+        out["mfma_leg"] = {"peak_tflops": MFMA_BF16_PEAK_TFLOPS}
+        for name in ("c4", "c3"):
+            ml = Leg(name)
+            steps = max(5, args.steps // 5)
+            ms_m, g1_m, g2_m = ml.timed(steps, 3)
+            r = ml.gemm_rates(g1_m, g2_m)
+            r.update({"workload": "%s: T=%d d=%d F=%d E=%d top-%d %s%s" % (
+                          name, ml.wl.T, ml.wl.d, ml.wl.F, ml.wl.E, ml.wl.k, ml.wl.act,
+                          (" + shared F=%d" % ml.wl.shared_F) if ml.wl.shared_F else ""),
+                      "tile_m": ml.layer.tile_m, "steps": steps, "ms_per_step": round(ms_m, 4),
+                      "tokens_per_s": round(ml.wl.T / (ms_m * 1e-3), 1),
+                      "layer_ffn_tflops": round(ffn_flops(ml.wl, ml.wl.T * ml.wl.k) / (ms_m * 1e-3) / 1e12, 1),
+                      "stage_hbm": ml.stage_hbm(steps)})
+            out["mfma_leg"][name] = r
+            ml.free()
+            del ml
 
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as O       # the CPU oracle, timed as it stands

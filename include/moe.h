@@ -139,7 +139,10 @@ MOE_API int moe_permute_static(const void* x, const int32_t* expert_idx, int T, 
  *                      blocks of experts), loads are row counts, any number of rows may move,
  *                      a move needs at least q_tokens rows.
  *   MOE_PLAN_STATIC    the starting placement of MOE_PLAN_HARMOENY, no rebalancing.
- *   MOE_PLAN_EVEN_SPLIT every expert's rows are divided evenly over all bins (section 5.3.2).
+ *   MOE_PLAN_EVEN_SPLIT every expert's rows are divided evenly over all bins (section 5.3.2,
+ *                      policy 3); the remainder goes one row each to the lowest bins.
+ *   MOE_PLAN_ROUND_ROBIN experts dealt to the bins in turn (expert e on bin e mod n_bins), every
+ *                      row goes to its expert's bin, no rebalancing (section 5.3.2, policy 1).
  *
  * Output: a table of tiles, bin after bin.  A tile is at most tile_m consecutive rows of one
  * expert; the tiles cover rows [0,A) exactly once.  A block = the rows of one expert on one
@@ -165,7 +168,8 @@ MOE_API int moe_permute_static(const void* x, const int32_t* expert_idx, int T, 
  */
 typedef struct { int32_t expert, row_begin, row_count, bin; } moe_tile;
 
-enum { MOE_PLAN_BALANCED = 0, MOE_PLAN_HARMOENY = 1, MOE_PLAN_STATIC = 2, MOE_PLAN_EVEN_SPLIT = 3 };
+enum { MOE_PLAN_BALANCED = 0, MOE_PLAN_HARMOENY = 1, MOE_PLAN_STATIC = 2, MOE_PLAN_EVEN_SPLIT = 3,
+       MOE_PLAN_ROUND_ROBIN = 4 };
 #define MOE_PLAN_HDR_CTR (4 + 2 * (MOE_MAX_BINS + 1))
 #define MOE_PLAN_HDR_INTS (MOE_PLAN_HDR_CTR + MOE_MAX_BINS + 1)
 
@@ -238,7 +242,7 @@ MOE_API int moe_pack_weights(const void* w_a, const void* w_b, int n, int K, int
  *        (binary16, nearest-even).  That is exact for bf16 values of magnitude 2^-14 .. 65504;
  *        smaller ones are rounded to the half subnormals (absolute error <= 2^-25), larger ones
  *        become infinite.  The kernels keep the hidden activations in half as well (see
- *        moe_grouped_ffn).
+ *        moe_grouped_ffn), saturated at +-65504.
  */
 MOE_API int moe_pack_w_out(const void* w, int n, int F, int d, moe_dtype dt, void* out, void* stream);
 
@@ -268,8 +272,10 @@ MOE_API int moe_pack_w_out(const void* w, int n, int F, int d, moe_dtype dt, voi
  * Requires d % 64 == 0 and F % 64 == 0 for MOE_BF16 (d % 4, F % 4 for MOE_F32).  MOE_BF16
  * accumulates both products in fp32 and rounds the hidden activations once, to IEEE half: 11
  * significant bits, so the result is within about 1e-3 of the output's RMS of the exact one
- * (bf16 activations would be eight times coarser); a hidden activation beyond +-65504 becomes
- * infinite and shows as inf/NaN in y_perm.
+ * (bf16 activations would be eight times coarser); a hidden activation beyond +-65504 (the
+ * largest half value) is stored as +-65504: it saturates, y_perm stays finite.  The bf16 kernels
+ * are persistent launches laid out for the whole MI355X (256 compute units in 8 XCDs):
+ * MOE_ERR_UNSUPPORTED on a device that reports another count.
  */
 MOE_API int moe_ffn_tile_m(moe_dtype dt);
 /* bf16 has two tile heights, 128 and 256 rows; this picks one from the mean rows per expert

@@ -153,8 +153,9 @@ def expert_ffn(x_rows: np.ndarray, weights: Dict[str, np.ndarray], act: str,
     """One expert on a block of rows, float64 (section 4.4: x W1 W2, activation between).
     act="relu":   y = max(0, x W1) W2           weights: W1 [d,F], W2 [F,d]
     act="swiglu": y = (silu(x Wg) * (x Wu)) Wd  weights: Wg, Wu [d,F], Wd [F,d]
-    h_round="bf16" / "f16" rounds the hidden activations to bfloat16 / IEEE half before the second
-    product; that is a diagnostic that mimics a 16-bit intermediate, not the definition."""
+    h_round="bf16" / "f16" rounds the hidden activations to bfloat16 / IEEE half (saturating at
+    +-65504) before the second product; that is a diagnostic that mimics a 16-bit intermediate,
+    not the definition."""
     x = to_f64(x_rows)
     if act == "relu":
         h = np.maximum(x @ to_f64(weights["W1"]), 0.0)
@@ -167,7 +168,8 @@ def expert_ffn(x_rows: np.ndarray, weights: Dict[str, np.ndarray], act: str,
     if h_round == "bf16":
         h = round_to_bf16(h)
     elif h_round == "f16":
-        h = h.astype(np.float16).astype(np.float64)      # numpy rounds float64 -> half directly, ties to even
+        # half with saturation: values beyond the largest half (65504) are kept at +-65504
+        h = np.clip(h, -65504.0, 65504.0).astype(np.float16).astype(np.float64)   # float64 -> half directly, ties to even
     elif h_round is not None:
         raise ValueError(h_round)
     return h @ to_f64(w_out)

@@ -22,7 +22,7 @@ lib = C.CDLL(LIB_PATH)
 MOE_OK, MOE_ERR_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE, MOE_ERR_CAPACITY, MOE_ERR_HIP = 0, -1, -2, -3, -4, -5
 MOE_F32, MOE_BF16 = 0, 1
 MOE_RELU, MOE_SWIGLU = 0, 1
-MOE_PLAN_BALANCED, MOE_PLAN_HARMOENY, MOE_PLAN_STATIC, MOE_PLAN_EVEN_SPLIT = 0, 1, 2, 3
+MOE_PLAN_BALANCED, MOE_PLAN_HARMOENY, MOE_PLAN_STATIC, MOE_PLAN_EVEN_SPLIT, MOE_PLAN_ROUND_ROBIN = 0, 1, 2, 3, 4
 MOE_MAX_EXPERTS, MOE_MAX_TOPK, MOE_MAX_BINS = 256, 8, 16
 MOE_PLAN_HDR_CTR = 4 + 2 * (MOE_MAX_BINS + 1)
 MOE_PLAN_HDR_INTS = MOE_PLAN_HDR_CTR + MOE_MAX_BINS + 1

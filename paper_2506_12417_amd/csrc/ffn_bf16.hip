@@ -462,8 +462,9 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             u32x2 v = {__float_as_uint(lo), __float_as_uint(hi)};
             __builtin_amdgcn_raw_buffer_store_b64(v, ro, voff, soff, 0);
         } else {
-            const f32x2 f = {lo, hi};
-            const f16x2 b = __builtin_convertvector(f, f16x2);            // nearest-even; beyond +-65504: infinity
+            // hidden activations saturate at the largest half value instead of becoming infinite
+            const f32x2 f = {__builtin_amdgcn_fmed3f(lo, -65504.f, 65504.f), __builtin_amdgcn_fmed3f(hi, -65504.f, 65504.f)};
+            const f16x2 b = __builtin_convertvector(f, f16x2);            // nearest-even
             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, b), ro, voff, soff, 0);
         }
     };
@@ -688,10 +689,32 @@ struct ScatterArgs {             // MOE_EPI_SCATTER: output row and gate value o
     int a_div = 1;
 };
 
+// The persistent launch and its XCD mapping assume the whole MI355X: 256 compute units, dealt
+// to 8 XCDs in turn.  Asked of the runtime once per device.
+int check_device() {
+    static int cus[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return moe_fail(MOE_ERR_HIP, "moe_grouped_ffn: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= 64) return moe_fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn: device %d", dev);
+    if (!cus[dev]) {
+        int n = 0;
+        e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return moe_fail(MOE_ERR_HIP, "moe_grouped_ffn: hipDeviceGetAttribute: %s", hipGetErrorString(e));
+        cus[dev] = n;
+    }
+    if (cus[dev] != MOE_GEMM_GRID)
+        return moe_fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn: the bf16 kernels are built for a GPU of %d compute units, "
+                        "device %d has %d", MOE_GEMM_GRID, dev, cus[dev]);
+    return MOE_OK;
+}
+
 template <int EPI, class C, bool GATHER = false>
 int launch(const void* a, int K, int N, const void* const* w, const moe_tile* tiles, int32_t* hdr, void* out,
            int ld_out, const ScatterArgs& sc, hipStream_t st) {
     static_assert(C::SMEM <= 160 * 1024, "LDS ring too large");
+    const int dev_ok = check_device();
+    if (dev_ok != MOE_OK) return dev_ok;
     auto kern = gemm_bf16_kernel<EPI, C::BM, C::BN, C::BK, C::RING, C::WM, C::WN, C::CS, GATHER>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)C::SMEM);

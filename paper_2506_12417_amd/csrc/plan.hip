@@ -149,9 +149,9 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
                 atomicAdd(&load[g], n);
             }
         }
-    } else {             // contiguous blocks of experts per bin
+    } else {             // contiguous blocks of experts per bin, or experts dealt to the bins in turn
         if (tid < E) {
-            const int g = (int)(((long long)tid * G) / E);
+            const int g = policy == MOE_PLAN_ROUND_ROBIN ? tid % G : (int)(((long long)tid * G) / E);
             S[tid * G + g] = cnt[tid];
             atomicAdd(&load[g], cnt[tid]);
         }
@@ -456,7 +456,7 @@ static int plan_impl(const char* who, const int32_t* counts, const int32_t* offs
     MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "%s: E=%d > %d", who, E, MOE_MAX_EXPERTS);
     MOE_REQUIRE(n_bins >= 1 && n_bins <= MOE_MAX_BINS, MOE_ERR_ARG, "%s: n_bins=%d outside [1,%d]", who, n_bins, MOE_MAX_BINS);
     MOE_REQUIRE(tile_m >= 1 && q_tokens >= 1, MOE_ERR_ARG, "%s: tile_m=%d q_tokens=%d must be >= 1", who, tile_m, q_tokens);
-    MOE_REQUIRE(policy >= MOE_PLAN_BALANCED && policy <= MOE_PLAN_EVEN_SPLIT, MOE_ERR_ARG, "%s: policy %d", who, policy);
+    MOE_REQUIRE(policy >= MOE_PLAN_BALANCED && policy <= MOE_PLAN_ROUND_ROBIN, MOE_ERR_ARG, "%s: policy %d", who, policy);
     MOE_REQUIRE(counts && offsets && tiles && plan_hdr, MOE_ERR_ARG, "%s: null pointer", who);
     MOE_REQUIRE(tile_capacity >= moe_plan_capacity(A, E, tile_m, n_bins), MOE_ERR_CAPACITY,
                 "%s: tile_capacity %d < %d", who, tile_capacity, moe_plan_capacity(A, E, tile_m, n_bins));

@@ -182,11 +182,15 @@ class MoELayer:
         B.moe_unpermute_combine(self.y_perm, self.inv_perm, self.gate_w if use_gate else None,
                                 self.s_y if self.shared_F else None, self.T, self.d, self.k, self.y, stream)
 
-    def forward(self, x: torch.Tensor, stream=None, marks=None, routed: bool = False) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, stream=None, marks=None, routed: bool = False, stages=None) -> torch.Tensor:
         """Enqueues the whole layer on the current (or given) stream; returns the output buffer.
         marks: optional list of 3 torch.cuda.Event recorded before / between / after the two
         grouped GEMMs (for per-kernel timing).  routed: expert_idx and gate_w are already set
-        (a router that samples ids, section 5.1's synthetic skew): step 1 is skipped."""
+        (a router that samples ids, section 5.1's synthetic skew): step 1 is skipped.
+        stages: optional list that receives (name, event) after every stage of the path, starting
+        with ("start", event) (per-stage timing; the events are recorded on the current stream)."""
+        if stages is not None:
+            return self._forward_staged(x, stages, routed)
         if not routed:
             self.route(x, None, stream)
         if self.fuse_gather:
@@ -239,6 +243,52 @@ class MoELayer:
         if self.shared_F:
             self.shared_ffn(x, stream)
         self.combine(True, stream)
+        return self.y
+
+
+    def _forward_staged(self, x: torch.Tensor, stages: list, routed: bool) -> torch.Tensor:
+        """forward() with an event after every stage: the same calls in the same order."""
+        def mark(name):
+            ev = torch.cuda.Event(enable_timing=True)
+            ev.record()
+            stages.append((name, ev))
+
+        g = self.experts
+        mark("start")
+        if not routed:
+            self.route(x, None, None)
+            mark("route")
+        self.permute(None if self.fuse_gather else x, None)
+        mark("permute")
+        self.plan(None)
+        mark("plan")
+        if self.fuse_gather:
+            args = (x, self.T, self.d, self.F, self.E, self.k, self.act, self.dt, g.in_ptrs, g.out_ptrs, self.tiles,
+                    self.plan_hdr, self.tile_m, self.h, self.perm, self.gate_w, self.y if self.k == 1 else self.y_perm, None)
+            B.moe_grouped_ffn_fused_phase(1, *args)
+            mark("g1")
+            B.moe_grouped_ffn_fused_phase(2, *args)
+            mark("g2")
+            if self.k == 1:
+                return self.y
+        elif self.fold_combine:
+            args = (self.x_perm, self.T, self.d, self.F, self.E, self.act, self.dt, g.in_ptrs, g.out_ptrs, self.tiles,
+                    self.plan_hdr, self.tile_m, self.h, self.perm, self.gate_w, self.y, None)
+            B.moe_grouped_ffn_top1_phase(1, *args)
+            mark("g1")
+            B.moe_grouped_ffn_top1_phase(2, *args)
+            mark("g2")
+            return self.y
+        else:
+            self.ffn_phase(1, None)
+            mark("g1")
+            self.ffn_phase(2, None)
+            mark("g2")
+        if self.shared_F:
+            self.shared_ffn(x, None)
+            mark("shared")
+        self.combine(True, None)
+        mark("combine")
         return self.y
 
 

@@ -127,7 +127,7 @@ def test_plan_argument_errors():
     assert call(G=0) == B.MOE_ERR_ARG and call(G=B.MOE_MAX_BINS + 1) == B.MOE_ERR_ARG
     assert call(tile_m=0) == B.MOE_ERR_ARG
     assert call(q=0) == B.MOE_ERR_ARG                      # Alg. 2 needs a threshold of at least one token
-    assert call(policy=4) == B.MOE_ERR_ARG and call(policy=-1) == B.MOE_ERR_ARG
+    assert call(policy=5) == B.MOE_ERR_ARG and call(policy=-1) == B.MOE_ERR_ARG
     assert call(E=B.MOE_MAX_EXPERTS + 1) == B.MOE_ERR_UNSUPPORTED
     assert call(A=1 << 26) == B.MOE_ERR_UNSUPPORTED
     assert call(counts=None) == B.MOE_ERR_ARG and call(hdr=None) == B.MOE_ERR_ARG

@@ -180,7 +180,7 @@ def _plan_counts():
     return cases
 
 
-@pytest.mark.parametrize("policy", [0, 1, 2, 3])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4])
 def test_plan_tiles_all_policies(torch_gpu, policy):
     torch = torch_gpu
     from paper_2506_12417_amd import binding as B
@@ -197,8 +197,10 @@ def test_plan_tiles_all_policies(torch_gpu, policy):
                 S = O.schedule_harmoeny(counts, G, q)
             elif policy == B.MOE_PLAN_STATIC:
                 S = O.schedule_static(counts, G)
-            else:
+            elif policy == B.MOE_PLAN_EVEN_SPLIT:
                 S = O.schedule_even_split(counts, G)
+            else:
+                S = O.schedule_round_robin(counts, G)
             tiles_o, bin_start_o = O.tiles_from_schedule(S, offsets, tile_m)
             cap = B.moe_plan_capacity(A, E, tile_m, G)
             assert len(tiles_o) <= cap
@@ -392,6 +394,44 @@ def test_layer_stage_by_stage(torch_gpu, name, over):
     _note("layer %s %s" % (name, over))
     inp = W.make_inputs(wl)
     _stage_check(torch_gpu, wl, inp)
+
+
+@pytest.mark.parametrize("act", ["relu", "swiglu"])
+def test_hidden_activations_saturate_at_the_half_range(torch_gpu, act):
+    """The bf16 path keeps the hidden activations in IEEE half.  A hidden activation beyond +-65504
+    is stored as +-65504 (it does not become infinite): a few rows of x are scaled by 2^17, so
+    their pre-activations reach about 1e5.  Those rows must come out finite and equal to the
+    oracle's diagnostic mode (hidden activations rounded to half with saturation) within 1e-3 of
+    the row's own RMS; every other row keeps the layer's tolerance against the exact oracle."""
+    torch = torch_gpu
+    from paper_2506_12417_amd.layer import to_device
+    wl = W.WORKLOADS["c2"].scaled(T=700, d=256, F=512, E=6, k=1, act=act)
+    _note("saturation %s" % act)
+    inp = W.make_inputs(wl)
+    big = np.array([3, 150, 699])
+    x32 = W.bf16_bits_to_f32(inp["x"])
+    x32[big] *= 2.0 ** 17                                   # exact in bf16
+    x_bits = W.f32_to_bf16_bits(x32)
+    assert np.array_equal(W.bf16_bits_to_f32(x_bits), x32)
+    layer = make_layer(wl, inp)
+    r = np.random.default_rng(3)
+    idx = r.integers(0, wl.E, size=(wl.T, 1)).astype(np.int32)
+    layer.expert_idx.copy_(torch.from_numpy(idx))
+    layer.gate_w.fill_(1.0)
+    y = to_numpy(layer.forward(to_device(x_bits, layer.device), routed=True))
+    torch.cuda.synchronize()
+    assert np.isfinite(y).all()
+    ew, ones = expert_dict(wl, inp), np.ones((wl.T, 1))
+    y_sat = O.moe_layer(x_bits, idx, ones, ew, act, tokens=big, h_round="f16")
+    # the planted rows do saturate: without the clamp the same rounding gives infinities
+    h_big = O.to_f64(x_bits[big[0]]) @ O.to_f64(ew["W1" if act == "relu" else "Wu"][idx[big[0], 0]])
+    assert np.abs(h_big).max() > 65504
+    for i, t in enumerate(big):
+        row_rms = float(np.sqrt(np.mean(y_sat[i] ** 2)))
+        assert np.abs(y[t] - y_sat[i]).max() <= 1e-3 * row_rms, (act, t)
+    rest = np.setdiff1d(np.arange(wl.T), big)
+    y_o = O.moe_layer(x_bits, idx, ones, ew, act, tokens=rest)
+    assert max_err_over_rms(y[rest], y_o) <= TOL["bf16"]
 
 
 @pytest.mark.parametrize("T", [300000, 400000])
@@ -760,7 +800,7 @@ def test_plan_policies_give_the_same_layer_output(torch_gpu, name, over):
     x = layer_x(layer, inp)
     ref = layer.forward(x).clone()
     torch.cuda.synchronize()
-    for pol in (B.MOE_PLAN_BALANCED, B.MOE_PLAN_STATIC, B.MOE_PLAN_EVEN_SPLIT):
+    for pol in (B.MOE_PLAN_BALANCED, B.MOE_PLAN_STATIC, B.MOE_PLAN_EVEN_SPLIT, B.MOE_PLAN_ROUND_ROBIN):
         layer.policy = pol
         y = layer.forward(x)
         torch.cuda.synchronize()

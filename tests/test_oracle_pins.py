@@ -325,6 +325,19 @@ def test_combine_identity_and_weights():
     assert O.combine(yp, inv, gw, sh).tolist() == [[50.0 + 0.25 + 0.125], [2000.0 + 10.0]]
 
 
+def test_half_hidden_diagnostic_mode_saturates():
+    # hand numbers: h = relu([1] . [[70000, 3, -5]]) = [70000, 3, 0]; as half with saturation
+    # [65504, 3, 0]; times a column of ones -> 65507.  2049 is not a half value (spacing 2 there):
+    # it rounds to even, 2048.
+    w = {"W1": np.array([[70000.0, 3.0, -5.0]]), "W2": np.ones((3, 1))}
+    assert O.expert_ffn(np.array([[1.0]]), w, "relu")[0, 0] == 70003.0
+    assert O.expert_ffn(np.array([[1.0]]), w, "relu", h_round="f16")[0, 0] == 65507.0
+    w = {"W1": np.array([[2049.0, -70000.0]]), "W2": np.array([[1.0], [1.0]])}
+    assert O.expert_ffn(np.array([[1.0]]), w, "relu", h_round="f16")[0, 0] == 2048.0
+    wg = {"Wg": np.array([[50.0]]), "Wu": np.array([[-90000.0]]), "Wd": np.array([[1.0]])}     # silu(50) = 50 to 1e-20
+    assert O.expert_ffn(np.array([[1.0]]), wg, "swiglu", h_round="f16")[0, 0] == -65504.0
+
+
 # ------------------------------------------------------------------------------------ Alg. 2
 def test_rebalance_paper_example():
     g = _golden("alg2_example.txt")
