@@ -293,6 +293,9 @@ def main():
     ap.add_argument("--no-ablation", action="store_true", help="skip the plan-policy and alpha-skew legs")
     ap.add_argument("--no-mfma-leg", action="store_true",
                     help="skip the arithmetic-bound workloads (c4, c3) that the default run times after c2")
+    ap.add_argument("--ffn-kernels", default="auto", choices=["auto", "ring", "stream"],
+                    help="which 16-bit GEMM kernels run 128-row tiles (moe_ffn_kernel_mode): the default (the "
+                         "LDS-ring kernels), the LDS-ring kernels, or the register-streaming kernels")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 256 MiB a few times (reference for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -308,6 +311,7 @@ def main():
     from paper_2506_12417_amd import binding as B
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    B.moe_ffn_kernel_mode({"auto": 0, "ring": 1, "stream": 2}[args.ffn_kernels])
     if args.workload == "c5":
         return bench_prerouted(args)
     leg = Leg(args.workload)
@@ -356,7 +360,7 @@ def main():
         "config": {"workload": "%s: T=%d d=%d F=%d E=%d top-%d %s%s, skew=%s" % (
             wl.name, wl.T, wl.d, wl.F, wl.E, wl.k, wl.act, (" + shared F=%d" % wl.shared_F) if wl.shared_F else "",
             wl.skew), "seed": wl.seed(), "n_bins": layer.n_bins, "q_tokens": layer.q_tokens,
-            "hidden_activations": "f16" if wl.dtype == "bf16" else "f32",
+            "hidden_activations": "f16" if wl.dtype == "bf16" else "f32", "ffn_kernels": args.ffn_kernels,
             "active_experts": active, "max_expert_rows": int(counts.max()), "min_expert_rows": int(counts.min())},
         "ffn_tflops": round(ffn_tflops, 1), "ffn_mfma_frac": round(ffn_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "layer_tflops": round(flops / (ms * 1e-3) / 1e12, 1),

@@ -283,6 +283,17 @@ MOE_API int moe_ffn_tile_m(moe_dtype dt);
  * their tiles are mostly empty at 256 rows).  Plan and FFN must be given the same value. */
 MOE_API int moe_ffn_pick_tile_m(moe_dtype dt, int A, int E);
 
+/* The 128-row bf16 configuration has two families of kernels that compute the same bits: one
+ * stages both operands through an LDS ring, the other streams the weights straight into
+ * registers (meant for experts with few rows, where a product costs the fetch of its weights:
+ * section 4.4's regime below q; it covers the ReLU first product and the second product, the
+ * scatter form from F >= 512 on).  The LDS ring is the default: it is the faster one on every
+ * workload measured so far.  moe_ffn_kernel_mode sets the choice for the process -- 0 default,
+ * 1 the LDS ring, 2 the streaming kernels wherever they cover the call, -1 leaves it -- and
+ * returns the previous setting (a negative moe_status on a bad argument).  For measurements and
+ * tests. */
+MOE_API int moe_ffn_kernel_mode(int mode);
+
 MOE_API int moe_grouped_ffn(const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,
                     const void* const* w_in, const void* const* w_out,
                     const moe_tile* tiles, int32_t* plan_hdr, int tile_m,

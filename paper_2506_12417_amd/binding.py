@@ -31,7 +31,7 @@ MOE_PERMUTE_STATIC_BYTES = 1 << 20
 
 EXPORTS = [
     "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_permute_static", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_rebalance", "moe_pack_weights", "moe_pack_w_out",
-    "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_grouped_ffn_top1", "moe_grouped_ffn_top1_phase", "moe_grouped_ffn_fused", "moe_grouped_ffn_fused_phase", "moe_unpermute_combine", "moe_prefetch_create",
+    "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_ffn_kernel_mode", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_grouped_ffn_top1", "moe_grouped_ffn_top1_phase", "moe_grouped_ffn_fused", "moe_grouped_ffn_fused_phase", "moe_unpermute_combine", "moe_prefetch_create",
     "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_reset", "moe_prefetch_destroy",
     "moe_token_threshold", "moe_workspace_bytes", "moe_copy_bytes", "moe_last_error", "moe_version",
 ]
@@ -50,6 +50,7 @@ lib.moe_pack_weights.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp]
 lib.moe_pack_w_out.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp]
 lib.moe_ffn_tile_m.argtypes = [_i]
 lib.moe_ffn_pick_tile_m.argtypes = [_i, _i, _i]
+lib.moe_ffn_kernel_mode.argtypes = [_i]
 lib.moe_grouped_ffn.argtypes = [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp]
 lib.moe_grouped_ffn_phase.argtypes = [_i, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp]
 lib.moe_grouped_ffn_top1.argtypes = [_vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]
@@ -153,6 +154,13 @@ def moe_route_topk_packed(x, w_gate_t, w_norm2, bias, T, d, E, k, renorm, dt, ex
 def moe_permute(x, expert_idx, T, d, E, k, dt, counts, offsets, perm, inv_perm, x_perm, ws, ws_bytes, stream=None):
     _check(lib.moe_permute(_p(x), _p(expert_idx), T, d, E, k, dt, _p(counts), _p(offsets), _p(perm), _p(inv_perm),
                            _p(x_perm), _p(ws), ws_bytes, _stream(stream)))
+
+
+def moe_ffn_kernel_mode(mode: int) -> int:
+    r = int(lib.moe_ffn_kernel_mode(mode))
+    if r < 0:
+        _check(r)
+    return r
 
 
 def moe_permute_static(x, expert_idx, T, d, E, k, dt, counts, offsets, perm, inv_perm, x_perm, stream=None):

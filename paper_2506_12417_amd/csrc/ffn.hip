@@ -140,6 +140,17 @@ struct Gather {
     bool on = false;
 };
 
+// which 16-bit kernels run the 128-row configuration: 0 the default (the LDS-ring kernels), 1 the
+// LDS-ring kernels, 2 the register-streaming kernels wherever they cover the call
+static int g_kernel_mode = 0;
+
+extern "C" int moe_ffn_kernel_mode(int mode) {
+    MOE_REQUIRE(mode >= -1 && mode <= 2, MOE_ERR_ARG, "moe_ffn_kernel_mode: mode %d", mode);
+    const int before = g_kernel_mode;
+    if (mode >= 0) g_kernel_mode = mode;
+    return before;
+}
+
 static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,
                             const void* const* w_in, const void* const* w_out, const moe_tile* tiles,
                             int32_t* plan_hdr, int tile_m, void* h_scratch, float* y_perm, void* stream,
@@ -169,17 +180,34 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
         // device only; this is its expected value.
         const long long tiles_est = (A + tile_m - 1) / tile_m + E / 2;
         auto narrow = [&](int N) { return tile_m == 128 && tiles_est * ((N + 255) / 256) < 2 * MOE_GEMM_GRID; };
+        // The kernels that stream the weights into registers (ffn_stream.hip) run on request only
+        // (moe_ffn_kernel_mode 2): on the workloads measured so far the LDS-ring kernels are faster.
+        // They take items of 128 weight rows, two work-groups per CU, unless there are four wide
+        // items per CU.
+        const bool few_rows = tile_m == 128 && g_kernel_mode == 2;
+        auto stream = [&](int epi, int K) { return few_rows && moe_gemm_stream_supports(epi, K); };
+        auto stream_narrow = [&](int N) { return tiles_est * ((N + 255) / 256) < 4 * MOE_GEMM_GRID; };
         if (phases & 1) {
-            if (gather.on)
-                rc = moe_launch_gemm_bf16_gather(act == MOE_SWIGLU ? MOE_EPI_SWIGLU : MOE_EPI_RELU, x_perm, gather.x_rows, d, n1,
+            const int epi = act == MOE_SWIGLU ? MOE_EPI_SWIGLU : MOE_EPI_RELU;
+            if (gather.on && stream(epi, d))
+                rc = moe_launch_gemm_stream_gather(stream_narrow(n1), x_perm, gather.x_rows, d, n1, w_in, tiles, plan_hdr,
+                                                   h_scratch, F, st, gather.perm, gather.k);
+            else if (gather.on)
+                rc = moe_launch_gemm_bf16_gather(epi, x_perm, gather.x_rows, d, n1,
                                                  w_in, tiles, plan_hdr, h_scratch, F, st, gather.perm, gather.k);
+            else if (stream(epi, d))
+                rc = moe_launch_gemm_stream(epi, stream_narrow(n1), x_perm, d, n1, w_in, tiles, plan_hdr, h_scratch, F, st);
             else
-                rc = moe_launch_gemm_bf16(act == MOE_SWIGLU ? MOE_EPI_SWIGLU : MOE_EPI_RELU, tile_m, narrow(n1), x_perm, d, n1,
+                rc = moe_launch_gemm_bf16(epi, tile_m, narrow(n1), x_perm, d, n1,
                                           w_in, tiles, plan_hdr, h_scratch, F, st);
             if (rc != MOE_OK) return rc;
         }
         if (phases & 2) {
-            if (top1.on)
+            const int epi = top1.on ? MOE_EPI_SCATTER : MOE_EPI_STORE;
+            if (stream(epi, F))
+                rc = moe_launch_gemm_stream(epi, stream_narrow(d), h_scratch, F, d, w_out, tiles, plan_hdr, (void*)y_perm, d, st,
+                                            top1.perm, top1.gate_w, top1.on ? A : 0);
+            else if (top1.on)
                 rc = moe_launch_gemm_bf16(MOE_EPI_SCATTER, tile_m, narrow(d), h_scratch, F, d, w_out, tiles, plan_hdr,
                                           (void*)y_perm, d, st, top1.perm, top1.gate_w, A);
             else

@@ -21,3 +21,19 @@ int moe_launch_gemm_bf16(int epi, int tile_m, int narrow, const void* a, int K, 
 int moe_launch_gemm_bf16_gather(int epi, const void* x, int x_rows, int K, int N, const void* const* w,
                                 const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st,
                                 const int32_t* row_src, int src_div);
+
+// The same products by the kernels of ffn_stream.hip (128-row tiles; weights streamed global ->
+// registers: for experts that hold few rows each, where a product's time is the fetch of its
+// weights).  Same results, bit for bit.  narrow: items of 128 instead of 256 weight rows, two
+// work-groups per CU.  moe_gemm_stream_supports: whether those kernels cover (epilogue, K).
+bool moe_gemm_stream_supports(int epi, int K);
+int moe_launch_gemm_stream(int epi, int narrow, const void* a, int K, int N, const void* const* w, const moe_tile* tiles,
+                           int32_t* hdr, void* out, int ld_out, hipStream_t st, const int32_t* row_token = nullptr,
+                           const float* row_gate = nullptr, int out_rows = 0);
+int moe_launch_gemm_stream_gather(int narrow, const void* x, int x_rows, int K, int N, const void* const* w,
+                                  const moe_tile* tiles, int32_t* hdr, void* out, int ld_out, hipStream_t st,
+                                  const int32_t* row_src, int src_div);
+
+// MOE_OK if the current device is the GPU the persistent launches are laid out for (256 compute
+// units in 8 XCDs), else MOE_ERR_UNSUPPORTED.
+int moe_check_gemm_device();

@@ -247,3 +247,33 @@ def test_ticket_register_check():
         text = open(asm).read()
         assert "global_atomic_add v%d," % r in text
         assert b.check_ticket_register(text) == []
+
+
+def test_build_checks_the_registers_of_the_streamed_weight_loads():
+    """build.check_stream_registers: in the kernels that load weights with hand-written
+    buffer_load_dwordx4, a register that holds (or awaits) such a load's data may be read by the
+    matrix instruction's B operand only, on every path through the kernel."""
+    from paper_2506_12417_amd import build as b
+    head = "_ZN1x18gemm_stream_kernelILi0EEEvv: ; @k\n"
+    tail = "\ts_endpgm\n.Lfunc_end0:\n"
+    load = "\tbuffer_load_dwordx4 v[20:23], v1, s[4:7], s9 offen offset:64\n"
+    mfma = "\tv_mfma_f32_16x16x32_bf16 v[40:43], v[8:11], v[20:23], v[40:43]\n"
+    loop = (head + "\tv_mov_b32_e32 v20, 0\n\tv_add_u32_e32 v2, v20, v20\n"      # before any load: free to use
+            + load + ".LBB0_1:\n\ts_waitcnt vmcnt(0)\n" + mfma
+            + "\tv_lshlrev_b32_e32 v21, 2, v0\n\tds_read_b32 v22, v21\n"          # consumed, overwritten, reused
+            + load + "\ts_cbranch_scc1 .LBB0_1\n" + tail)
+    assert b.check_stream_registers(loop) == []
+    # a copy right after the load, a spill, the A operand of the matrix instruction, a read at the
+    # top of the loop (reached from the load at its bottom), an accumulator in a loaded register
+    for line in ("v_mov_b32_e32 v3, v21", "scratch_store_dword off, v23, off",
+                 "v_mfma_f32_16x16x32_bf16 v[40:43], v[20:23], v[8:11], v[40:43]", "v_fmac_f32_e32 v20, v1, v2"):
+        text = loop.replace(load + ".LBB0_1:", load + "\t" + line + "\n.LBB0_1:", 1)
+        assert [c for _, c in b.check_stream_registers(text)] == [line], line
+    text = loop.replace(".LBB0_1:\n", ".LBB0_1:\n\tv_add_u32_e32 v5, v22, v22\n", 1)
+    assert [c for _, c in b.check_stream_registers(text)] == ["v_add_u32_e32 v5, v22, v22"]
+    assert b.check_stream_registers("_Z1av:\n\ts_endpgm\n.Lfunc_end0:\n")          # no such kernel at all: reported
+    asm = os.path.join(os.path.dirname(b.LIB), "_build", "ffn_stream.s")
+    if os.path.exists(asm):          # the assembly of the library that is loaded here
+        text = open(asm).read()
+        assert text.count("buffer_load_dwordx4") > 32
+        assert b.check_stream_registers(text) == [] and b.check_ticket_register(text) == []

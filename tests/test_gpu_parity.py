@@ -434,6 +434,57 @@ def test_hidden_activations_saturate_at_the_half_range(torch_gpu, act):
     assert max_err_over_rms(y[rest], y_o) <= TOL["bf16"]
 
 
+STREAM_CASES = [
+    # T, d, F, E, k, skew: the register-streaming kernels against the LDS-ring kernels
+    (1500, 256, 512, 16, 1, "zipf"),        # few K-steps per item in the first product: fixed stride, rows fetched on the spot
+    (3000, 768, 3072, 40, 1, "zipf"),       # c2's shapes: on-demand hand-out, gather and scatter folded in
+    (2000, 512, 1024, 24, 2, "zipf"),       # top-2: plain second product, combine kernel
+    (700, 64, 512, 5, 1, "hot"),            # one K-step per item in the first product
+    (900, 192, 640, 300 // 20, 1, "uniform"),   # d and F not multiples of the item width
+    (1, 128, 512, 4, 1, "uniform"),         # a single row
+]
+
+
+@pytest.mark.parametrize("T,d,F,E,k,skew", STREAM_CASES)
+def test_streaming_kernels_give_the_bits_of_the_lds_ring_kernels(torch_gpu, T, d, F, E, k, skew):
+    """moe_ffn_kernel_mode: the 128-row bf16 configuration run by the kernels that stream the
+    weights into registers (mode 2) and by the LDS-ring kernels (mode 1) -- through the plain, the
+    top-1 and the fused entry points -- must give identical hidden activations and outputs, and
+    the layer must agree with the oracle."""
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    wl = W.WORKLOADS["c2"].scaled(T=T, d=d, F=F, E=E, k=k, skew=skew)
+    _note("stream vs ring T=%d d=%d F=%d E=%d k=%d %s" % (T, d, F, E, k, skew))
+    inp = W.make_inputs(wl)
+    layer = make_layer(wl, inp, tile_m=128)
+    x = layer_x(layer, inp)
+    before = B.moe_ffn_kernel_mode(-1)
+    try:
+        out = {}
+        for mode in (1, 2):
+            B.moe_ffn_kernel_mode(mode)
+            assert B.moe_ffn_kernel_mode(-1) == mode
+            layer.h.fill_(float("nan"))
+            layer.y.fill_(float("nan"))
+            layer.y_perm.fill_(float("nan"))
+            y = layer.forward(x).clone()                     # the fused entry points where the layer uses them
+            h_fused = layer.h.clone()
+            layer.h.fill_(float("nan"))
+            layer.y_perm.fill_(float("nan"))
+            layer.permute(x)
+            layer.ffn()                                       # the plain entry point
+            torch.cuda.synchronize()
+            out[mode] = (y, h_fused, layer.h.clone(), layer.y_perm.clone())
+        for a, b_, name in zip(out[1], out[2], ("y", "H (fused call)", "H", "y_perm")):
+            assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a.view(torch.int16),
+                               b_.view(torch.int32) if b_.dtype == torch.float32 else b_.view(torch.int16)), name
+    finally:
+        B.moe_ffn_kernel_mode(before)
+    idx_o, w_o, _ = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
+    y_o = O.moe_layer(inp["x"], idx_o, w_o, expert_dict(wl, inp), wl.act)
+    assert max_err_over_rms(to_numpy(out[2][0]), y_o) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("T", [300000, 400000])
 def test_layer_with_very_many_tiles_in_a_bin(torch_gpu, T):
     """All rows on ONE bin in 128-row tiles.  400 000 rows: more than 3 100 tiles, beyond the per-bin
