@@ -110,24 +110,64 @@ def bench_prerouted(args):
         out_slots[n_slots] = (ms, wall, same)
         if n_slots == 16:
             # the bare copies: all 16 host experts into their slots, nothing else on the GPU
-            eng, nb = sh.engine, sh.bytes_each
-            hw = [sh.host_w[e - wl.n_local].data_ptr() for e in heavy_first]
+            c, nb = sh.cache, sh.bytes_each
+            keys = [c.key(sh.layer_id, e) for e in heavy_first]
+            hw = [sh.host_ptr(e) for e in heavy_first]
             t_copy = []
             for _ in range(5):
-                B.moe_prefetch_reset(eng)
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
-                B.moe_prefetch_experts(eng, heavy_first, hw, nb)
-                for e in heavy_first:
-                    B.moe_prefetch_wait(eng, e)
+                c.fetch(keys, hw)
+                c.wait(keys)
                 torch.cuda.synchronize()
                 t_copy.append((time.perf_counter() - t0) * 1e3)
-                for e in heavy_first:
-                    B.moe_prefetch_release(eng, e)
+                for k in keys:
+                    c.release(k)
             ms_copy = min(t_copy)
             copy_bytes = len(heavy_first) * nb
         sh.close()
         del sh
+    # Two layers on one cache (16 slots): with look-ahead a layer's last groups run while the next
+    # layer's first experts are already being fetched into the slots it has released, so the host
+    # link does not idle across the layer boundary (section 1 of the paper: the system looks ahead).
+    from paper_2506_12417_amd.layer import ExpertCache
+    inp2 = W.make_inputs(wl, seed=wl.seed() + 1)
+    x2 = to_device(inp2["x"], "cuda:0")
+    ids2_d = torch.from_numpy(inp2["ids"]).to("cuda:0")
+    cnt2 = np.bincount(inp2["ids"], minlength=wl.E)
+    order2 = sorted(range(wl.n_local, wl.E), key=lambda e: (-cnt2[e], e))
+    shares, cache = [], None
+    for l, w_in in enumerate((inp, inp2)):
+        sh = PreRoutedShare(wl.T, wl.d, wl.F, wl.E, wl.n_local, 16, act=wl.act, dtype=wl.dtype, cache=cache, layer_id=l)
+        cache = sh.cache
+        for e in range(wl.E):
+            sh.load_expert(e, {"W1": w_in["W1"][e], "W2": w_in["W2"][e]})
+        shares.append(sh)
+    feed = [(x, ids_d, heavy_first), (x2, ids2_d, order2)]
+
+    def two_layers(ahead, passes):
+        for _ in range(passes):
+            for l in (0, 1):
+                xl, il, ol = feed[l]
+                la = (shares[1 - l], feed[1 - l][2][:ahead]) if ahead else None
+                shares[l].forward(xl, il, fetch_order=ol, lookahead=la)
+
+    look = {}
+    for ahead in (0, 4):
+        two_layers(ahead, max(2, args.warmup // 2))
+        torch.cuda.synchronize()
+        s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s_ev.record()
+        two_layers(ahead, max(3, args.steps // 2))
+        e_ev.record()
+        torch.cuda.synchronize()
+        look[ahead] = s_ev.elapsed_time(e_ev) / (2 * max(3, args.steps // 2))
+        for k in list(cache.where):                      # what the last look-ahead left in the cache
+            cache.release(k)
+    same_la = bool(torch.equal(shares[0].y, y_res))
+    for sh in shares:
+        sh.close()
+    cache.close()
     ms16, wall16, same16 = out_slots[16]
     ms4, wall4, same4 = out_slots[4]
     overlap = (ms_res + ms_copy - ms16) / min(ms_res, ms_copy)
@@ -144,7 +184,10 @@ def bench_prerouted(args):
                       "all_resident_ms": round(ms_res, 4), "with_16_slots_ms": round(ms16, 4), "with_4_slots_ms": round(ms4, 4),
                       "host_wall_ms_16_slots": round(wall16, 4), "host_wall_ms_4_slots": round(wall4, 4),
                       "exposed_ms_16_slots": round(ms16 - ms_res, 4), "overlap_efficiency_16_slots": round(overlap, 3),
-                      "bit_identical_to_all_resident": same16 and same4},
+                      "bit_identical_to_all_resident": same16 and same4 and same_la,
+                      "two_layers_one_cache": {"slots": 16, "ms_per_layer_no_lookahead": round(look[0], 4),
+                                               "ms_per_layer_lookahead_4": round(look[4], 4),
+                                               "copy_only_ms_per_layer": round(ms_copy, 4)}},
         "roofline": {"kernel": "hipMemcpyAsync H2D (expert fetch)", "bound": "host-link", "achieved": round(copy_bytes / (ms16 * 1e-3) / 1e9, 1),
                      "peak": 64.0, "unit": "GB/s", "frac": round(copy_bytes / (ms16 * 1e-3) / 1e9 / 64.0, 4), "traffic": copy_bytes},
     }

@@ -413,6 +413,20 @@ MOE_API int moe_prefetch_release(moe_prefetch* h, int expert_id, void* stream);
 MOE_API int moe_prefetch_reset(moe_prefetch* h);
 MOE_API int moe_prefetch_destroy(moe_prefetch* h);
 
+/* The addresses that moe_prefetch_experts chose, entered into the device pointer tables that
+ * moe_grouped_ffn reads (the library alone decides which slot an expert goes to; the caller
+ * passes the answers on before the expert's FFN).  For i < n:
+ *
+ *   w_in[expert_ids[i]] = ptrs[i]        w_out[expert_ids[i]] = ptrs[i] + out_offset   (w_out may be NULL)
+ *
+ * written by a small kernel on `stream`, ordered like every other call (a host-to-device copy
+ * of the table would queue behind the expert copies on the DMA engine).
+ *   w_in, w_out : device arrays of E device pointers      expert_ids, ptrs : HOST arrays of n
+ *   out_offset  : bytes from an expert's first matrix to its second inside a slot
+ */
+MOE_API int moe_set_expert_pointers(const void** w_in, const void** w_out, int E, const int32_t* expert_ids /*host*/,
+                                    int n, const void* const* ptrs /*host*/, size_t out_offset, void* stream);
+
 /* Token threshold q of section 4.4, Eq. 4: the row count above which running an expert takes
  * longer than fetching its weights, q = phi * d_type / (2 * beta), rounded up.
  *   phi: arithmetic rate in FLOP/s   d_type: bytes per weight   beta: fetch rate in bytes/s */

@@ -32,7 +32,7 @@ MOE_PERMUTE_STATIC_BYTES = 1 << 20
 EXPORTS = [
     "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_permute_static", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_rebalance", "moe_pack_weights", "moe_pack_w_out",
     "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_ffn_kernel_mode", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_grouped_ffn_top1", "moe_grouped_ffn_top1_phase", "moe_grouped_ffn_fused", "moe_grouped_ffn_fused_phase", "moe_unpermute_combine", "moe_prefetch_create",
-    "moe_prefetch_experts", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_reset", "moe_prefetch_destroy",
+    "moe_prefetch_experts", "moe_set_expert_pointers", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_reset", "moe_prefetch_destroy",
     "moe_token_threshold", "moe_workspace_bytes", "moe_copy_bytes", "moe_last_error", "moe_version",
 ]
 
@@ -60,6 +60,7 @@ lib.moe_grouped_ffn_fused_phase.argtypes = [_i, _vp, _i, _i, _i, _i, _i, _i, _i,
 lib.moe_unpermute_combine.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp]
 lib.moe_prefetch_create.argtypes = [C.POINTER(_vp), _i, _sz, _vp]
 lib.moe_prefetch_experts.argtypes = [_vp, C.POINTER(C.c_int32), _i, C.POINTER(_vp), _sz, C.POINTER(_vp)]
+lib.moe_set_expert_pointers.argtypes = [_vp, _vp, _i, C.POINTER(C.c_int32), _i, C.POINTER(_vp), _sz, _vp]
 lib.moe_prefetch_wait.argtypes = [_vp, _i, _vp]
 lib.moe_prefetch_release.argtypes = [_vp, _i, _vp]
 lib.moe_prefetch_reset.argtypes = [_vp]
@@ -255,6 +256,13 @@ def moe_prefetch_experts(h: int, expert_ids: Sequence[int], host_w: Sequence[int
     out = (_vp * max(n, 1))()
     _check(lib.moe_prefetch_experts(h, ids, n, hw, bytes_each, out))
     return [out[i] for i in range(n)]
+
+
+def moe_set_expert_pointers(w_in, w_out, E: int, expert_ids: Sequence[int], ptrs: Sequence[int], out_offset: int, stream=None):
+    n = len(expert_ids)
+    ids = (C.c_int32 * max(n, 1))(*expert_ids)
+    pp = (_vp * max(n, 1))(*ptrs)
+    _check(lib.moe_set_expert_pointers(_p(w_in), _p(w_out), E, ids, n, pp, out_offset, _stream(stream)))
 
 
 def moe_prefetch_wait(h: int, expert_id: int, stream=None):

@@ -137,3 +137,45 @@ extern "C" int moe_prefetch_destroy(moe_prefetch* h) {
     delete h;
     return MOE_OK;
 }
+
+// ------------------------------------------------------------------------------------------
+// moe_set_expert_pointers: the slots that moe_prefetch_experts chose, written into the device
+// pointer tables that moe_grouped_ffn reads -- by a tiny kernel on the compute stream, its values
+// passed as kernel arguments.  (A host-to-device copy of the table would queue behind the expert
+// copies on the same DMA engine and hold the compute stream for the length of a whole expert.)
+namespace {
+constexpr int SETP_MAX = 16;
+struct SetPointersArgs {
+    int32_t id[SETP_MAX];
+    const void* ptr[SETP_MAX];
+};
+__global__ void set_pointers_kernel(const void** w_in, const void** w_out, SetPointersArgs a, size_t out_offset, int n) {
+    const int i = threadIdx.x;
+    if (i < n) {
+        w_in[a.id[i]] = a.ptr[i];
+        if (w_out) w_out[a.id[i]] = (const char*)a.ptr[i] + out_offset;
+    }
+}
+}  // namespace
+
+extern "C" int moe_set_expert_pointers(const void** w_in, const void** w_out, int E, const int32_t* expert_ids, int n,
+                                       const void* const* ptrs, size_t out_offset, void* stream) {
+    MOE_REQUIRE(n >= 0 && E >= 1, MOE_ERR_ARG, "moe_set_expert_pointers: n=%d E=%d", n, E);
+    if (n == 0) return MOE_OK;
+    MOE_REQUIRE(w_in && expert_ids && ptrs, MOE_ERR_ARG, "moe_set_expert_pointers: null pointer");
+    for (int i = 0; i < n; ++i) {
+        MOE_REQUIRE(expert_ids[i] >= 0 && expert_ids[i] < E, MOE_ERR_ARG, "moe_set_expert_pointers: expert id %d outside [0, %d)", expert_ids[i], E);
+        MOE_REQUIRE(ptrs[i], MOE_ERR_ARG, "moe_set_expert_pointers: null pointer for expert %d", expert_ids[i]);
+    }
+    for (int at = 0; at < n; at += SETP_MAX) {
+        SetPointersArgs a;
+        const int m = n - at < SETP_MAX ? n - at : SETP_MAX;
+        for (int i = 0; i < SETP_MAX; ++i) {
+            a.id[i] = i < m ? expert_ids[at + i] : 0;
+            a.ptr[i] = i < m ? ptrs[at + i] : nullptr;
+        }
+        hipLaunchKernelGGL(set_pointers_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, w_in, w_out, a, out_offset, m);
+        MOE_CHECK_LAUNCH("moe_set_expert_pointers");
+    }
+    return MOE_OK;
+}

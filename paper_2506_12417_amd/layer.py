@@ -292,6 +292,59 @@ class MoELayer:
         return self.y
 
 
+class ExpertCache:
+    """The device slots that hold host-resident experts while they are needed, and the engine that
+    fills them (section 4.3: asynchronous fetching, a finished expert's slot is overwritten).  One
+    cache can serve several MoE layers of a model: an expert is named by (layer, expert id), so a
+    layer can fetch the first experts of the NEXT layer into the slots it has released (section 1:
+    the system looks ahead so that the right experts are in GPU memory when they are needed).
+    The library alone decides which slot an expert goes to; this class only remembers the answer."""
+
+    def __init__(self, n_slots: int, bytes_each: int, device="cuda:0"):
+        assert n_slots >= 1
+        self.n_slots, self.bytes_each = n_slots, bytes_each
+        self.device = torch.device(device)
+        self.slots = torch.empty((n_slots, bytes_each), dtype=torch.uint8, device=self.device)
+        self.engine = B.moe_prefetch_create(n_slots, bytes_each, self.slots)
+        self.where = {}          # key -> (slot address, sequence number) of experts fetched and not released
+        self.seq = 0
+        self.bytes_fetched = 0
+
+    @staticmethod
+    def key(layer: int, e: int) -> int:
+        return layer * 4096 + e              # the engine takes any non-negative id
+
+    def free_slots(self) -> int:
+        return self.n_slots - len(self.where)
+
+    def fetch(self, keys, host_ptrs):
+        """Enqueues the copies (in this order) on the engine's stream."""
+        if not keys:
+            return
+        got = B.moe_prefetch_experts(self.engine, keys, host_ptrs, self.bytes_each)
+        for k, p in zip(keys, got):
+            self.seq += 1
+            self.where[k] = (p, self.seq)
+        self.bytes_fetched += len(keys) * self.bytes_each
+
+    def wait(self, keys, stream=None):
+        """Makes the stream wait until all of these experts' copies have landed: copies complete in
+        the order they were enqueued, so one wait for the one enqueued last covers the others
+        (a chain of event waits on the compute stream costs far more than one)."""
+        last = max(keys, key=lambda k: self.where[k][1])
+        B.moe_prefetch_wait(self.engine, last, stream)
+
+    def release(self, key, stream=None):
+        B.moe_prefetch_release(self.engine, key, stream)
+        del self.where[key]
+
+    def close(self):
+        if self.engine:
+            torch.cuda.synchronize(self.device)
+            B.moe_prefetch_destroy(self.engine)
+            self.engine = 0
+
+
 class PreRoutedShare:
     """One GPU's share of an expert-parallel MoE layer after the scatter (Alg. 1 steps 4-5): T rows
     that arrive already routed (one expert id each), E experts of which the first n_local are
@@ -302,13 +355,16 @@ class PreRoutedShare:
 
     Experts run in groups: the resident ones first, then the fetched ones `group` at a time, in
     fetch order; each group is one moe_plan_tiles_subset + moe_grouped_ffn (or its fused form) over
-    the same rows."""
+    the same rows.
+
+    cache / layer_id: several layers of a model can share one ExpertCache; forward(lookahead=...)
+    then fetches the next layer's first experts into the slots this layer has released."""
 
     def __init__(self, T: int, d: int, F: int, E: int, n_local: int, n_slots: int, act: str = "relu",
                  dtype: str = "bf16", n_bins: int = XCDS, q_tokens: Optional[int] = None, group: Optional[int] = None,
-                 device="cuda:0"):
+                 device="cuda:0", cache: Optional[ExpertCache] = None, layer_id: int = 0):
         assert 0 <= n_local <= E and n_slots >= 1
-        self.T, self.d, self.F, self.E, self.n_local, self.n_slots = T, d, F, E, n_local, n_slots
+        self.T, self.d, self.F, self.E, self.n_local = T, d, F, E, n_local
         self.n_foreign = E - n_local
         self.act = B.MOE_SWIGLU if act == "swiglu" else B.MOE_RELU
         self.dt = B.MOE_BF16 if dtype == "bf16" else B.MOE_F32
@@ -317,8 +373,6 @@ class PreRoutedShare:
         self.n_bins = n_bins
         self.q_tokens = q_tokens if q_tokens is not None else default_q_tokens(self.dt)
         self.tile_m = B.moe_ffn_pick_tile_m(self.dt, T, E)
-        # a group of fetched experts runs while the next group's copies are in flight
-        self.group = group if group is not None else max(1, min(4, n_slots // 2))
         # one row per expert (k = 1): where the library offers it, the first product gathers its rows
         # from x and the second one writes every row to its place in y (moe_grouped_ffn_fused), so
         # that no gather precedes the groups and no combine follows the last one
@@ -329,13 +383,22 @@ class PreRoutedShare:
         self.rows_in = 2 * F if self.act == B.MOE_SWIGLU else F
         self.in_bytes, self.out_bytes = self.rows_in * d * es, d * F * es
         self.bytes_each = self.in_bytes + self.out_bytes
+        self.owns_cache = cache is None
+        self.cache = cache if cache is not None else ExpertCache(n_slots, self.bytes_each, dev)
+        assert self.cache.bytes_each >= self.bytes_each
+        self.layer_id = layer_id
+        self.n_slots = self.cache.n_slots
+        # a group of fetched experts runs while the next group's copies are in flight
+        self.group = group if group is not None else max(1, min(4, self.n_slots // 2))
         self.local = ExpertGroup(max(n_local, 1), d, F, self.act, self.dt, dev)
         self.host_w = torch.empty((max(self.n_foreign, 1), self.bytes_each), dtype=torch.uint8, pin_memory=True)
-        self.slots = torch.empty((n_slots, self.bytes_each), dtype=torch.uint8, device=dev)
-        self.engine = B.moe_prefetch_create(n_slots, self.bytes_each, self.slots)
         self._stage = ExpertGroup(1, d, F, self.act, self.dt, dev)       # packing area for host-resident experts
-        self.ptr_host = torch.empty((2, E), dtype=torch.int64, pin_memory=True)
-        self.ptr_dev = torch.empty((2, E), dtype=torch.int64, device=dev)
+        # where every expert's two matrices are: the resident block, or the slot the library chose
+        ip, op = self._local_ptrs()
+        tab = torch.zeros((2, E), dtype=torch.int64)
+        tab[0, :n_local] = torch.tensor(ip, dtype=torch.int64)
+        tab[1, :n_local] = torch.tensor(op, dtype=torch.int64)
+        self.ptr_dev = tab.to(dev)
         self.expert_idx = torch.empty((T, 1), dtype=i32, device=dev)
         self.counts = torch.empty(E, dtype=i32, device=dev)
         self.offsets = torch.empty(E + 1, dtype=i32, device=dev)
@@ -353,11 +416,15 @@ class PreRoutedShare:
         self.bytes_fetched = 0
         self._done = None
 
+    @property
+    def slots(self):
+        return self.cache.slots
+
     def close(self):
-        if self.engine:
+        if self.owns_cache:
+            self.cache.close()
+        else:
             torch.cuda.synchronize(self.device)
-            B.moe_prefetch_destroy(self.engine)
-            self.engine = 0
 
     def load_expert(self, e: int, w: Dict[str, np.ndarray]):
         """w: one expert's matrices in the paper's orientation.  Resident experts are packed in
@@ -378,11 +445,18 @@ class PreRoutedShare:
         op = [g.w_out.data_ptr() + e * self.d * self.F * es for e in range(self.n_local)]
         return ip, op
 
-    def forward(self, x: torch.Tensor, ids: torch.Tensor, fetch_order=None, stream=None) -> torch.Tensor:
+    def host_ptr(self, e: int) -> int:
+        return self.host_w[e - self.n_local].data_ptr()
+
+    def forward(self, x: torch.Tensor, ids: torch.Tensor, fetch_order=None, stream=None, lookahead=None) -> torch.Tensor:
         """ids: [T] int32 on the device.  fetch_order: the host-resident experts' ids in the order
         they are to be fetched and run (default: by id); the host may know the rows per expert
-        from the metadata exchange of Alg. 1 step 2 and put heavy experts first."""
-        T, E = self.T, self.E
+        from the metadata exchange of Alg. 1 step 2 and put heavy experts first.
+        lookahead: (next_share, expert ids) -- another layer on the same cache and the
+        host-resident experts it will want first: once all of this layer's own fetches are
+        enqueued, those are fetched into the slots this layer releases, so the host link does not
+        idle between the two layers."""
+        T, E, c, L = self.T, self.E, self.cache, self.layer_id
         # The host drives this flow group by group and does not run more than one pass ahead of the
         # GPU: copies that wait on "slot free" events of a pass still being enqueued were measured to
         # stall in the runtime (3.1 ms per pass with this wait, 3.4-4.3 ms without it).
@@ -390,35 +464,34 @@ class PreRoutedShare:
             self._done.synchronize()
         order = list(range(self.n_local, E)) if fetch_order is None else [int(e) for e in fetch_order]
         assert sorted(order) == list(range(self.n_local, E))
-        # where every expert's weights will be: resident block, or slot (position in the order) mod n_slots
-        # (uploaded only when the order changes)
-        if getattr(self, "_order", None) != order:
-            ip, op = self._local_ptrs()
-            tab = np.zeros((2, E), dtype=np.int64)
-            tab[0, :self.n_local], tab[1, :self.n_local] = ip, op
-            base = self.slots.data_ptr()
-            for j, e in enumerate(order):
-                tab[0, e] = base + (j % self.n_slots) * self.bytes_each
-                tab[1, e] = tab[0, e] + self.in_bytes
-            self.ptr_host.copy_(torch.from_numpy(tab))
-            self.ptr_dev.copy_(self.ptr_host, non_blocking=True)
-            self._order = list(order)
-            self._slot_of = {e: int(tab[0, e]) for e in order}
-            self._host_ptr = {e: self.host_w[e - self.n_local].data_ptr() for e in order}
-        B.moe_prefetch_reset(self.engine)
+        # experts that an earlier layer's look-ahead has already fetched run first: they hold slots
+        order = [e for e in order if c.key(L, e) in c.where] + [e for e in order if c.key(L, e) not in c.where]
+        pending = [(self, e) for e in order if c.key(L, e) not in c.where]
+        if lookahead is not None:
+            nxt_share, nxt_ids = lookahead
+            assert nxt_share.cache is c and nxt_share.layer_id != L
+            pending += [(nxt_share, int(e)) for e in nxt_ids if c.key(nxt_share.layer_id, int(e)) not in c.where]
+
+        def fetch_more(n):
+            take = pending[:max(0, min(n, c.free_slots()))]
+            del pending[:len(take)]
+            c.fetch([c.key(sh.layer_id, e) for sh, e in take], [sh.host_ptr(e) for sh, e in take])
+            for sh, e in take:
+                sh.bytes_fetched += sh.bytes_each
+
+        def upload(group_ids):
+            # the slots the library chose for this group's experts -> the device pointer table,
+            # enqueued ahead of the group's kernels
+            fetched = [e for e in group_ids if e >= self.n_local]
+            B.moe_set_expert_pointers(self.ptr_dev[0], self.ptr_dev[1], E, fetched,
+                                      [c.where[c.key(L, e)][0] for e in fetched], self.in_bytes, stream)
+
         self.expert_idx.view(-1).copy_(ids)
         B.moe_permute(None if self.fused else x, self.expert_idx, T, self.d, E, 1, self.dt, self.counts, self.offsets,
                       self.perm, self.inv_perm, None if self.fused else self.x_perm, self.ws, self.ws_bytes, stream)
 
-        def fetch(chunk):
-            if not chunk:
-                return
-            got = B.moe_prefetch_experts(self.engine, chunk, [self._host_ptr[e] for e in chunk], self.bytes_each)
-            for e, p in zip(chunk, got):
-                assert p == self._slot_of[e], "slot of expert %d is not where the pointer table says" % e
-            self.bytes_fetched += len(chunk) * self.bytes_each
-
         def run(group_ids):
+            upload(group_ids)
             B.moe_plan_tiles_subset(self.counts, self.offsets, E, T, self.tile_m, self.n_bins, self.q_tokens,
                                     B.MOE_PLAN_HARMOENY, group_ids, self.tiles, self.tile_capacity, self.plan_hdr,
                                     None, stream)
@@ -429,8 +502,7 @@ class PreRoutedShare:
                 B.moe_grouped_ffn(self.x_perm, T, self.d, self.F, E, self.act, self.dt, self.ptr_dev[0],
                                   self.ptr_dev[1], self.tiles, self.plan_hdr, self.tile_m, self.h, self.y_perm, stream)
 
-        next_fetch = min(self.n_slots, len(order))
-        fetch(order[:next_fetch])                       # fills every slot; copies run while the resident experts compute
+        fetch_more(c.n_slots)                           # fills every free slot; copies run while the resident experts compute
         if self.n_local:
             run(list(range(self.n_local)))
         done = 0
@@ -439,17 +511,18 @@ class PreRoutedShare:
             # hides it -- is then one expert's work, not a whole group's
             left = len(order) - done
             take = self.group if left > self.group or self.group == 1 else max(1, left - 1)
-            grp = order[done:done + take]
-            # copies complete in the order they were enqueued: waiting for the group's last one covers the others
-            # (a chain of event waits on the compute stream costs far more than one)
-            B.moe_prefetch_wait(self.engine, grp[-1], stream)
+            grp = []
+            for e in order[done:done + take]:              # (as many as have a slot: fetches follow `order`)
+                if c.key(L, e) not in c.where:
+                    break
+                grp.append(e)
+            assert grp, "no slot holds the next expert and none is free"
+            c.wait([c.key(L, e) for e in grp], stream)
             run(grp)
             for e in grp:
-                B.moe_prefetch_release(self.engine, e, stream)
+                c.release(c.key(L, e), stream)
             done += len(grp)
-            nxt = order[next_fetch:next_fetch + len(grp)]  # into the slots just released
-            fetch(nxt)
-            next_fetch += len(nxt)
+            fetch_more(len(grp))                        # into the slots just released
         if not self.fused:
             B.moe_unpermute_combine(self.y_perm, self.inv_perm, None, None, T, self.d, 1, self.y, stream)
         if self._done is None:

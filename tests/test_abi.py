@@ -200,6 +200,11 @@ def test_prefetch_argument_errors_before_any_device_work():
     assert B.lib.moe_prefetch_create(C.byref(h), 2, 0, FAKE) == B.MOE_ERR_ARG
     assert B.lib.moe_prefetch_create(C.byref(h), 2, 16, None) == B.MOE_ERR_ARG
     assert B.lib.moe_prefetch_create(None, 2, 16, FAKE) == B.MOE_ERR_ARG
+    ids, ptrs = (C.c_int32 * 2)(1, 9), (C.c_void_p * 2)(FAKE, FAKE)
+    assert B.lib.moe_set_expert_pointers(FAKE, FAKE, 8, ids, 2, ptrs, 64, None) == B.MOE_ERR_ARG        # id 9 outside [0, 8)
+    assert B.lib.moe_set_expert_pointers(None, FAKE, 16, ids, 2, ptrs, 64, None) == B.MOE_ERR_ARG
+    assert B.lib.moe_set_expert_pointers(FAKE, FAKE, 16, ids, 2, (C.c_void_p * 2)(FAKE, None), 64, None) == B.MOE_ERR_ARG
+    assert B.lib.moe_set_expert_pointers(FAKE, FAKE, 16, ids, 0, ptrs, 64, None) == B.MOE_OK            # nothing to write
     assert B.lib.moe_prefetch_wait(None, 0, None) == B.MOE_ERR_ARG
     assert B.lib.moe_prefetch_release(None, 0, None) == B.MOE_ERR_ARG
     assert B.lib.moe_prefetch_reset(None) == B.MOE_ERR_ARG

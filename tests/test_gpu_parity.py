@@ -592,6 +592,68 @@ def test_prefetch_overwrite_matches_all_resident(torch_gpu, n_slots, group, d, F
     sh.close()
 
 
+@pytest.mark.parametrize("n_slots,ahead,d,F", [(7, 3, 128, 256), (3, 2, 128, 256), (2, 1, 256, 512), (5, 5, 256, 512)])
+def test_lookahead_prefetch_across_two_layers(torch_gpu, n_slots, ahead, d, F):
+    """Two MoE layers (different weights, different rows and expert ids) share one expert cache.
+    While a layer's last groups compute, the first host-resident experts of the NEXT layer are
+    fetched into the slots it has released (section 1: the system looks ahead), also from the
+    second layer to the first layer of the next batch.  Every layer's output must be the bits
+    of the same layer with all experts resident, pass after pass; slots are poisoned first."""
+    torch = torch_gpu
+    from paper_2506_12417_amd.layer import ExpertCache, PreRoutedShare, to_device
+    wl = W.WORKLOADS["c5"].scaled(T=2500, d=d, F=F, E=12, n_local=5)
+    _note("look-ahead n_slots=%d ahead=%d d=%d F=%d" % (n_slots, ahead, d, F))
+    layers_in = [W.make_inputs(wl), W.make_inputs(wl, seed=wl.seed() + 1)]
+    assert not np.array_equal(layers_in[0]["ids"], layers_in[1]["ids"])
+    xs = [to_device(inp["x"], "cuda:0") for inp in layers_in]
+    ids = [torch.from_numpy(inp["ids"]).to("cuda:0") for inp in layers_in]
+    y_res = []
+    for inp, x, i in zip(layers_in, xs, ids):
+        ref = _share(torch, wl, inp, n_local=wl.E, n_slots=1)
+        y_res.append(to_numpy(ref.forward(x, i)).copy())
+        torch.cuda.synchronize()
+        ref.close()
+    y_o = O.moe_layer(layers_in[1]["x"], layers_in[1]["ids"].reshape(-1, 1), np.ones((wl.T, 1)),
+                      {n: layers_in[1][n] for n in ("W1", "W2")}, wl.act)
+    assert max_err_over_rms(y_res[1], y_o) <= TOL["bf16"]
+    cache = None
+    shares = []
+    for l, inp in enumerate(layers_in):
+        sh = PreRoutedShare(wl.T, wl.d, wl.F, wl.E, wl.n_local, n_slots, act=wl.act, dtype=wl.dtype, cache=cache, layer_id=l)
+        cache = sh.cache
+        for e in range(wl.E):
+            sh.load_expert(e, {n: inp[n][e] for n in ("W1", "W2")})
+        shares.append(sh)
+    assert isinstance(cache, ExpertCache) and shares[1].cache is shares[0].cache
+    orders = []
+    for inp in layers_in:
+        cnt = np.bincount(inp["ids"], minlength=wl.E)
+        orders.append(sorted(range(wl.n_local, wl.E), key=lambda e: (-cnt[e], e)))
+    cache.slots.fill_(0x7f)
+    torch.cuda.synchronize()
+    passes = 3
+    for p in range(passes):
+        for l in (0, 1):
+            nxt = 1 - l
+            shares[l].y.fill_(float("nan"))
+            shares[l].y_perm.fill_(float("nan"))
+            # (the last layer of the last pass looks ahead as well: its fetches stay in the cache)
+            y = to_numpy(shares[l].forward(xs[l], ids[l], fetch_order=orders[l], lookahead=(shares[nxt], orders[nxt][:ahead])))
+            torch.cuda.synchronize()
+            assert np.array_equal(y, y_res[l]), "pass %d layer %d" % (p, l)
+            # what the look-ahead fetched for the next layer is in the cache now
+            got = sorted(k - cache.key(nxt, 0) for k in cache.where if k // 4096 == nxt)
+            assert got == sorted(orders[nxt][:min(ahead, n_slots)]), (p, l, got)
+    n_for = wl.E - wl.n_local
+    assert shares[1].bytes_fetched == passes * n_for * shares[1].bytes_each
+    assert shares[0].bytes_fetched == (passes * n_for + min(ahead, n_slots)) * shares[0].bytes_each
+    for k in list(cache.where):
+        cache.release(k)
+    shares[0].close()
+    shares[1].close()
+    cache.close()
+
+
 def test_plan_subset_is_the_plan_of_the_masked_counts(torch_gpu):
     torch = torch_gpu
     from paper_2506_12417_amd import binding as B
