@@ -278,11 +278,16 @@ class Leg:
                 gbs = b / (us[n] * 1e-6) / 1e9
                 out[n] = {"us": round(us[n], 2), "algorithmic_bytes": int(b), "GBs": round(gbs, 1),
                           "frac_of_8TBs": round(gbs / HBM_PEAK_GBS, 4)}
-        out["plan_us"] = round(us["plan"], 2)
+        if "permute_plan" in us:
+            # the sort and the plan in one launch (moe_permute_plan): no bytes to speak of, latency only
+            out["permute_plan_us"] = round(us["permute_plan"], 2)
+        else:
+            out["plan_us"] = round(us["plan"], 2)
         if self.wl.k == 1 and "combine" not in us:
             out["combine"] = "folded into the second grouped GEMM (top-1): no kernel of its own"
         if self.layer.fuse_gather:
-            out["permute_note"] = "sort only: the row gather is done by the first grouped GEMM's loads"
+            out["permute_note"] = ("the sort and the plan are one launch (moe_permute_plan); the row gather is done by the "
+                                   "first grouped GEMM's loads")
         return out
 
     def gemm_rates(self, g1_ms, g2_ms):

@@ -180,6 +180,19 @@ MOE_API int moe_plan_tiles(const int32_t* counts, const int32_t* offsets, int E,
                    moe_tile* tiles, int tile_capacity, int32_t* plan_hdr, int32_t* sched,
                    void* stream);
 
+/* moe_permute (the sort only: no row gather) and moe_plan_tiles in ONE launch: the stable rank
+ * and the schedule need nothing from each other -- both start from the expert ids -- so the
+ * plan's serial loops (a single work-group) run beside the ranking work-groups instead of after
+ * them, and the histogram launch goes too (every work-group counts the experts of the
+ * assignments it needs by itself).  Outputs are those of the two calls, bit for bit; no
+ * workspace is needed.  For T*k <= MOE_PERMUTE_PLAN_MAX (every work-group reads all ids);
+ * MOE_ERR_UNSUPPORTED beyond: use the two calls.  T >= 1. */
+#define MOE_PERMUTE_PLAN_MAX 32768
+MOE_API int moe_permute_plan(const int32_t* expert_idx, int T, int E, int k,
+                   int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                   int tile_m, int n_bins, int q_tokens, int policy,
+                   moe_tile* tiles, int tile_capacity, int32_t* plan_hdr, int32_t* sched, void* stream);
+
 /* The same schedule over SOME of the experts: expert_ids (HOST array of n_ids ids in [0,E), any
  * order, repeats allowed) names the experts that take part; the others count as empty.  This
  * is how the experts of Alg. 1 step 5 are run in groups as their weights become available

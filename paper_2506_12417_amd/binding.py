@@ -28,9 +28,10 @@ MOE_PLAN_HDR_CTR = 4 + 2 * (MOE_MAX_BINS + 1)
 MOE_PLAN_HDR_INTS = MOE_PLAN_HDR_CTR + MOE_MAX_BINS + 1
 MOE_OP_PERMUTE = 1
 MOE_PERMUTE_STATIC_BYTES = 1 << 20
+MOE_PERMUTE_PLAN_MAX = 32768
 
 EXPORTS = [
-    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_permute_static", "moe_plan_capacity", "moe_plan_tiles", "moe_plan_tiles_subset", "moe_rebalance", "moe_pack_weights", "moe_pack_w_out",
+    "moe_route_topk", "moe_pack_router", "moe_route_topk_packed", "moe_permute", "moe_permute_static", "moe_plan_capacity", "moe_plan_tiles", "moe_permute_plan", "moe_plan_tiles_subset", "moe_rebalance", "moe_pack_weights", "moe_pack_w_out",
     "moe_ffn_tile_m", "moe_ffn_pick_tile_m", "moe_ffn_kernel_mode", "moe_grouped_ffn", "moe_grouped_ffn_phase", "moe_grouped_ffn_top1", "moe_grouped_ffn_top1_phase", "moe_grouped_ffn_fused", "moe_grouped_ffn_fused_phase", "moe_unpermute_combine", "moe_prefetch_create",
     "moe_prefetch_experts", "moe_set_expert_pointers", "moe_prefetch_wait", "moe_prefetch_release", "moe_prefetch_reset", "moe_prefetch_destroy",
     "moe_token_threshold", "moe_workspace_bytes", "moe_copy_bytes", "moe_last_error", "moe_version",
@@ -44,6 +45,7 @@ lib.moe_permute.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _v
 lib.moe_permute_static.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.moe_plan_capacity.argtypes = [_i, _i, _i, _i]
 lib.moe_plan_tiles.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp]
+lib.moe_permute_plan.argtypes = [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp]
 lib.moe_plan_tiles_subset.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), _i, _vp, _i, _vp, _vp, _vp]
 lib.moe_rebalance.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp, _vp]
 lib.moe_pack_weights.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp]
@@ -173,6 +175,12 @@ def moe_plan_tiles(counts, offsets, E, A, tile_m, n_bins, q_tokens, policy, tile
                    sched=None, stream=None):
     _check(lib.moe_plan_tiles(_p(counts), _p(offsets), E, A, tile_m, n_bins, q_tokens, policy, _p(tiles),
                               tile_capacity, _p(plan_hdr), _p(sched), _stream(stream)))
+
+
+def moe_permute_plan(expert_idx, T, E, k, counts, offsets, perm, inv_perm, tile_m, n_bins, q_tokens, policy, tiles,
+                     tile_capacity, plan_hdr, sched=None, stream=None):
+    _check(lib.moe_permute_plan(_p(expert_idx), T, E, k, _p(counts), _p(offsets), _p(perm), _p(inv_perm), tile_m, n_bins,
+                                q_tokens, policy, _p(tiles), tile_capacity, _p(plan_hdr), _p(sched), _stream(stream)))
 
 
 def moe_plan_tiles_subset(counts, offsets, E, A, tile_m, n_bins, q_tokens, policy, expert_ids, tiles, tile_capacity,

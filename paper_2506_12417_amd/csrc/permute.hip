@@ -9,13 +9,14 @@
 //      per-64-chunk counts are prefix-summed in LDS -> perm, inv_perm
 //   4. row gather x_perm[r] = x[perm[r] / k], 16 bytes per lane, fully coalesced
 #include "common.h"
+#include "permute_rank.h"
 #include <mutex>
 
 namespace {
 
-constexpr int PB = 1024;   // assignments per work-group in steps 1 and 3
-constexpr int NTH = 256;
-constexpr int CHUNKS = PB / 64;
+using moe_rank::CHUNKS;
+using moe_rank::NTH;
+using moe_rank::PB;   // assignments per work-group in steps 1 and 3
 
 __global__ __launch_bounds__(NTH) void hist_kernel(const int32_t* __restrict__ idx, int A, int E,
                                                    int32_t* __restrict__ block_hist) {
@@ -64,100 +65,12 @@ __global__ __launch_bounds__(NTH) void scan_kernel(int32_t* __restrict__ block_h
     }
 }
 
-// SCAN: block_hist holds the raw per-block histograms and this kernel does step 2 itself (every
-// work-group sums the histograms of the blocks before it and of all blocks, and scans the totals;
-// the first one also writes counts and offsets): one launch less when the blocks are few.
-template <bool SCAN>
+template <int MODE>
 __global__ __launch_bounds__(NTH) void rank_kernel(const int32_t* __restrict__ idx, int A, int E, int nbits, int nb,
                                                    const int32_t* __restrict__ block_hist,
                                                    int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
                                                    int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
-    extern __shared__ int chunk_hist[];   // [CHUNKS][E]
-    __shared__ int start_of[MOE_MAX_EXPERTS];      // first position of this work-group's assignments of expert e
-    __shared__ int scan_buf[2][MOE_MAX_EXPERTS];
-    for (int i = threadIdx.x; i < CHUNKS * E; i += NTH) chunk_hist[i] = 0;
-    // this thread's assignments: fetched first, all at once, so that their latency passes under the scan
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int base = blockIdx.x * PB;
-    int my_e[CHUNKS / 4], my_rank[CHUNKS / 4];
-#pragma unroll
-    for (int ci = 0; ci < CHUNKS / 4; ++ci) {
-        const int a = base + (ci * 4 + wave) * 64 + lane;
-        my_e[ci] = a < A ? idx[a] : -1;
-    }
-    if (SCAN) {
-        static_assert(NTH >= MOE_MAX_EXPERTS, "one thread per expert");
-        const int e = threadIdx.x;
-        int before = 0, total = 0;
-        if (e < E)
-            for (int b0 = 0; b0 < nb; b0 += 8) {           // eight loads in flight at a time
-                int v[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = b0 + j < nb ? block_hist[(size_t)(b0 + j) * E + e] : 0;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    before += b0 + j < (int)blockIdx.x ? v[j] : 0;
-                    total += v[j];
-                }
-            }
-        // inclusive scan of the totals over the experts (Hillis-Steele, MOE_MAX_EXPERTS entries)
-        scan_buf[0][e] = e < E ? total : 0;
-        __syncthreads();
-        int cur = 0;
-        for (int step = 1; step < MOE_MAX_EXPERTS; step <<= 1) {
-            const int v = scan_buf[cur][e] + (e >= step ? scan_buf[cur][e - step] : 0);
-            scan_buf[cur ^ 1][e] = v;
-            cur ^= 1;
-            __syncthreads();
-        }
-        const int incl = scan_buf[cur][e];
-        if (e < E) {
-            start_of[e] = incl - total + before;
-            if (blockIdx.x == 0) {
-                counts[e] = total;
-                offsets[e] = incl - total;
-                if (e == E - 1) offsets[E] = incl;
-            }
-        }
-    } else {
-        for (int e = threadIdx.x; e < E; e += NTH) start_of[e] = offsets[e] + block_hist[(size_t)blockIdx.x * E + e];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int ci = 0; ci < CHUNKS / 4; ++ci) {
-        const int c = ci * 4 + wave;
-        int e = my_e[ci];
-        if ((unsigned)e >= (unsigned)E) e = -1;
-        unsigned long long peers = __ballot(e >= 0);
-        for (int b = 0; b < nbits; ++b) {
-            unsigned long long m = __ballot((e >> b) & 1);
-            peers &= ((e >> b) & 1) ? m : ~m;
-        }
-        const unsigned long long below = peers & ((1ull << lane) - 1ull);
-        my_e[ci] = e;
-        my_rank[ci] = __popcll(below);
-        if (e >= 0 && below == 0) chunk_hist[c * E + e] = __popcll(peers);   // lowest peer lane
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < E; e += NTH) {
-        int run = start_of[e];
-        for (int c = 0; c < CHUNKS; ++c) {
-            int v = chunk_hist[c * E + e];
-            chunk_hist[c * E + e] = run;
-            run += v;
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int ci = 0; ci < CHUNKS / 4; ++ci) {
-        const int c = ci * 4 + wave;
-        const int a = base + c * 64 + lane;
-        if (my_e[ci] >= 0) {
-            int pos = chunk_hist[c * E + my_e[ci]] + my_rank[ci];
-            perm[pos] = a;
-            inv_perm[a] = pos;
-        }
-    }
+    moe_rank::rank_body<MODE>(idx, A, E, nbits, nb, block_hist, counts, offsets, perm, inv_perm);
 }
 
 // x_perm row r <- x row perm[r] / k, in 16-byte pieces (vpr pieces per row)
@@ -233,10 +146,10 @@ static int permute_launch(const void* x, const int32_t* expert_idx, int T, int d
     }
     if (A == 0) return MOE_OK;
     if (fused_scan)
-        hipLaunchKernelGGL(rank_kernel<true>, dim3(nb), dim3(NTH), sizeof(int) * CHUNKS * E, st, expert_idx, A, E, nbits, nb,
+        hipLaunchKernelGGL(rank_kernel<1>, dim3(nb), dim3(NTH), sizeof(int) * CHUNKS * E, st, expert_idx, A, E, nbits, nb,
                            block_hist, counts, offsets, perm, inv_perm);
     else
-        hipLaunchKernelGGL(rank_kernel<false>, dim3(nb), dim3(NTH), sizeof(int) * CHUNKS * E, st, expert_idx, A, E, nbits, nb,
+        hipLaunchKernelGGL(rank_kernel<0>, dim3(nb), dim3(NTH), sizeof(int) * CHUNKS * E, st, expert_idx, A, E, nbits, nb,
                            block_hist, counts, offsets, perm, inv_perm);
     MOE_CHECK_LAUNCH("moe_permute/rank");
     if (x) {

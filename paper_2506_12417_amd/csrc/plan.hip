@@ -6,6 +6,7 @@
 // bin, heaviest block first.  The paper's scheduler runs as host-driven tensor ops and costs
 // 20-30 % of its layer time (section 5.3.1); here it is a few microseconds on the device.
 #include "common.h"
+#include "permute_rank.h"
 #include <climits>
 #include <type_traits>
 
@@ -39,11 +40,30 @@ struct ExpertMask {
     uint32_t w[MOE_MAX_EXPERTS / 32];
 };
 
+// arguments of the launch that also ranks (moe_permute_plan)
+struct RankArgs {
+    const int32_t* idx;          // expert of every assignment
+    int nbits, nb;               // bits of an expert id, blocks of moe_rank::PB assignments
+    int32_t *counts, *offsets, *perm, *inv_perm;
+};
+
+// MERGED: one launch does the stable rank of moe_permute (work-groups 0 .. nb-1, moe_rank::rank_body
+// in the mode that counts by itself) AND the plan (work-group nb, which also counts the experts
+// of all assignments itself instead of reading counts and offsets): the two need nothing from
+// each other, so the plan's serial loops pass under the ranking instead of after it.
+template <bool MERGED>
 __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ counts,
                                                    const int32_t* __restrict__ offsets, int E, int A, int tile_m,
                                                    int G, int q, int policy, ExpertMask mask,
                                                    moe_tile* __restrict__ tiles, int capacity,
-                                                   int32_t* __restrict__ hdr, int32_t* __restrict__ sched) {
+                                                   int32_t* __restrict__ hdr, int32_t* __restrict__ sched, RankArgs ra) {
+    static_assert(NTH == moe_rank::NTH, "one block size for both roles");
+    if (MERGED) {
+        if ((int)blockIdx.x < ra.nb) {
+            moe_rank::rank_body<2>(ra.idx, A, E, ra.nbits, ra.nb, nullptr, ra.counts, ra.offsets, ra.perm, ra.inv_perm);
+            return;
+        }
+    }
     __shared__ int cnt[MOE_MAX_EXPERTS], order[MOE_MAX_EXPERTS], row0[MOE_MAX_EXPERTS];
     __shared__ __attribute__((aligned(16))) int cost[MOE_MAX_EXPERTS + 4];
     // (not volatile: volatile accesses are compiled to flat instructions that are waited for one by
@@ -61,7 +81,33 @@ __global__ __launch_bounds__(NTH) void plan_kernel(const int32_t* __restrict__ c
 
     for (int i = tid; i < E * G; i += NTH) S[i] = 0;
     if (tid < G) { load[tid] = 0; bin_blocks[tid] = 0; bin_cursor[tid] = 0; bin_tiles[tid] = 0; }
-    if (tid < E) {
+    if (MERGED) {
+        // this work-group's own count of every expert (cnt) and its first row (row0: exclusive prefix)
+        cnt[tid] = 0;
+        __syncthreads();
+        moe_rank::count_experts(ra.idx, A, E, 0, nullptr, cnt);
+        __syncthreads();
+        const int total = tid < E ? cnt[tid] : 0;
+        // inclusive scan over the experts (Hillis-Steele; order[] and cost[] are not in use yet)
+        int* buf[2] = {order, cost};
+        buf[0][tid] = total;
+        __syncthreads();
+        int cur = 0;
+        for (int step = 1; step < MOE_MAX_EXPERTS; step <<= 1) {
+            const int v = buf[cur][tid] + (tid >= step ? buf[cur][tid - step] : 0);
+            buf[cur ^ 1][tid] = v;
+            cur ^= 1;
+            __syncthreads();
+        }
+        const int first = buf[cur][tid] - total;
+        __syncthreads();
+        if (tid < E) {
+            const int c = ((mask.w[tid >> 5] >> (tid & 31)) & 1u) ? total : 0;
+            cnt[tid] = c;
+            row0[tid] = first;
+            cost[tid] = weight_of(c, tile_m, by_cost);
+        }
+    } else if (tid < E) {
         int c = ((mask.w[tid >> 5] >> (tid & 31)) & 1u) ? counts[tid] : 0;    // experts left out count as empty
         cnt[tid] = c;
         row0[tid] = offsets[tid];                  // (fetched now: a global load at the end would be waited for in full)
@@ -460,8 +506,43 @@ static int plan_impl(const char* who, const int32_t* counts, const int32_t* offs
     MOE_REQUIRE(counts && offsets && tiles && plan_hdr, MOE_ERR_ARG, "%s: null pointer", who);
     MOE_REQUIRE(tile_capacity >= moe_plan_capacity(A, E, tile_m, n_bins), MOE_ERR_CAPACITY,
                 "%s: tile_capacity %d < %d", who, tile_capacity, moe_plan_capacity(A, E, tile_m, n_bins));
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(NTH), 0, (hipStream_t)stream, counts, offsets, E, A, tile_m, n_bins,
-                       q_tokens, policy, mask, tiles, tile_capacity, plan_hdr, sched);
+    hipLaunchKernelGGL(plan_kernel<false>, dim3(1), dim3(NTH), 0, (hipStream_t)stream, counts, offsets, E, A, tile_m, n_bins,
+                       q_tokens, policy, mask, tiles, tile_capacity, plan_hdr, sched, RankArgs());
+    MOE_CHECK_LAUNCH(who);
+    return MOE_OK;
+}
+
+extern "C" int moe_permute_plan(const int32_t* expert_idx, int T, int E, int k, int32_t* counts, int32_t* offsets,
+                                int32_t* perm, int32_t* inv_perm, int tile_m, int n_bins, int q_tokens, int policy,
+                                moe_tile* tiles, int tile_capacity, int32_t* plan_hdr, int32_t* sched, void* stream) {
+    const char* who = "moe_permute_plan";
+    MOE_REQUIRE(T >= 1 && E >= 1 && k >= 1, MOE_ERR_ARG, "%s: T=%d E=%d k=%d", who, T, E, k);
+    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "%s: E=%d > %d", who, E, MOE_MAX_EXPERTS);
+    MOE_REQUIRE((long long)T * k <= MOE_PERMUTE_PLAN_MAX, MOE_ERR_UNSUPPORTED,
+                "%s: T*k = %lld assignments, at most %d (use moe_permute and moe_plan_tiles)", who, (long long)T * k, MOE_PERMUTE_PLAN_MAX);
+    const int A = T * k;
+    MOE_REQUIRE((long long)A + (long long)E * q_tokens < (1ll << 26), MOE_ERR_UNSUPPORTED,
+                "%s: A + E*q_tokens = %lld is not below 2^26", who, (long long)A + (long long)E * q_tokens);
+    MOE_REQUIRE(n_bins >= 1 && n_bins <= MOE_MAX_BINS, MOE_ERR_ARG, "%s: n_bins=%d outside [1,%d]", who, n_bins, MOE_MAX_BINS);
+    MOE_REQUIRE(tile_m >= 1 && q_tokens >= 1, MOE_ERR_ARG, "%s: tile_m=%d q_tokens=%d must be >= 1", who, tile_m, q_tokens);
+    MOE_REQUIRE(policy >= MOE_PLAN_BALANCED && policy <= MOE_PLAN_ROUND_ROBIN, MOE_ERR_ARG, "%s: policy %d", who, policy);
+    MOE_REQUIRE(expert_idx && counts && offsets && perm && inv_perm && tiles && plan_hdr, MOE_ERR_ARG, "%s: null pointer", who);
+    MOE_REQUIRE(tile_capacity >= moe_plan_capacity(A, E, tile_m, n_bins), MOE_ERR_CAPACITY,
+                "%s: tile_capacity %d < %d", who, tile_capacity, moe_plan_capacity(A, E, tile_m, n_bins));
+    ExpertMask all;
+    for (int i = 0; i < MOE_MAX_EXPERTS / 32; ++i) all.w[i] = 0xffffffffu;
+    RankArgs ra;
+    ra.idx = expert_idx;
+    ra.nb = (A + moe_rank::PB - 1) / moe_rank::PB;
+    ra.nbits = 0;
+    while ((1 << ra.nbits) < E) ++ra.nbits;
+    ra.counts = counts;
+    ra.offsets = offsets;
+    ra.perm = perm;
+    ra.inv_perm = inv_perm;
+    hipLaunchKernelGGL(plan_kernel<true>, dim3(ra.nb + 1), dim3(NTH), sizeof(int) * moe_rank::CHUNKS * E, (hipStream_t)stream,
+                       (const int32_t*)nullptr, (const int32_t*)nullptr, E, A, tile_m, n_bins, q_tokens, policy, all, tiles,
+                       tile_capacity, plan_hdr, sched, ra);
     MOE_CHECK_LAUNCH(who);
     return MOE_OK;
 }

@@ -159,6 +159,16 @@ class MoELayer:
         B.moe_permute(x, self.expert_idx, self.T, self.d, self.E, self.k, self.dt, self.counts, self.offsets,
                       self.perm, self.inv_perm, None if x is None else self.x_perm, self.ws, self.ws_bytes, stream)
 
+    def permute_plan(self, stream=None):
+        """The sort (no row gather) and the plan: one launch where the library offers it."""
+        if 1 <= self.A <= B.MOE_PERMUTE_PLAN_MAX:
+            B.moe_permute_plan(self.expert_idx, self.T, self.E, self.k, self.counts, self.offsets, self.perm, self.inv_perm,
+                               self.tile_m, self.n_bins, self.q_tokens, self.policy, self.tiles, self.tile_capacity,
+                               self.plan_hdr, self.sched, stream)
+        else:
+            self.permute(None, stream)
+            self.plan(stream)
+
     def plan(self, stream=None):
         B.moe_plan_tiles(self.counts, self.offsets, self.E, self.A, self.tile_m, self.n_bins, self.q_tokens,
                          self.policy, self.tiles, self.tile_capacity, self.plan_hdr, self.sched, stream)
@@ -196,8 +206,7 @@ class MoELayer:
         if self.fuse_gather:
             # the first product gathers its rows from x itself (no x_perm); for top-1 the second one
             # also writes y directly
-            self.permute(None, stream)
-            self.plan(stream)
+            self.permute_plan(stream)
             g = self.experts
             args = (x, self.T, self.d, self.F, self.E, self.k, self.act, self.dt, g.in_ptrs, g.out_ptrs, self.tiles,
                     self.plan_hdr, self.tile_m, self.h, self.perm, self.gate_w, self.y if self.k == 1 else self.y_perm,
@@ -258,10 +267,14 @@ class MoELayer:
         if not routed:
             self.route(x, None, None)
             mark("route")
-        self.permute(None if self.fuse_gather else x, None)
-        mark("permute")
-        self.plan(None)
-        mark("plan")
+        if self.fuse_gather:
+            self.permute_plan(None)
+            mark("permute_plan")
+        else:
+            self.permute(x, None)
+            mark("permute")
+            self.plan(None)
+            mark("plan")
         if self.fuse_gather:
             args = (x, self.T, self.d, self.F, self.E, self.k, self.act, self.dt, g.in_ptrs, g.out_ptrs, self.tiles,
                     self.plan_hdr, self.tile_m, self.h, self.perm, self.gate_w, self.y if self.k == 1 else self.y_perm, None)

@@ -92,6 +92,18 @@ def test_permute_static_argument_errors():
     assert "moe_permute" in B.moe_last_error()
 
 
+def test_permute_plan_argument_errors():
+    def call(idx=FAKE, T=64, E=8, k=2, counts=FAKE, perm=FAKE, tile_m=128, G=8, q=10, policy=1, tiles=FAKE, cap=10000, hdr=FAKE):
+        return status(B.moe_permute_plan, idx, T, E, k, counts, FAKE, perm, FAKE, tile_m, G, q, policy, tiles, cap, hdr, None, 0)
+
+    assert call(T=0) == B.MOE_ERR_ARG
+    assert call(E=B.MOE_MAX_EXPERTS + 1) == B.MOE_ERR_UNSUPPORTED
+    assert call(T=B.MOE_PERMUTE_PLAN_MAX // 2 + 1) == B.MOE_ERR_UNSUPPORTED      # times k = 2
+    assert call(G=0) == B.MOE_ERR_ARG and call(q=0) == B.MOE_ERR_ARG and call(policy=9) == B.MOE_ERR_ARG
+    assert call(idx=None) == B.MOE_ERR_ARG and call(perm=None) == B.MOE_ERR_ARG and call(hdr=None) == B.MOE_ERR_ARG
+    assert call(cap=3) == B.MOE_ERR_CAPACITY
+
+
 def test_workspace_and_capacity_closed_forms():
     # one histogram of E int32 counters per block of 1024 assignments
     for T, k, E in ((1, 1, 1), (1024, 1, 8), (1025, 1, 8), (16384, 4, 60), (0, 2, 5)):

@@ -139,6 +139,45 @@ def test_permute(torch_gpu, T, k, E, d):
     assert np.array_equal(to_numpy(layer.x_perm), O.gather_rows(x, ref["perm"], k))
 
 
+@pytest.mark.parametrize("T,k,E", [(1, 1, 1), (256, 2, 8), (1000, 1, 128), (5000, 4, 60), (3, 2, 256), (4097, 1, 7),
+                                   (16384, 1, 128), (16384, 2, 200), (8192, 4, 60)])
+def test_permute_plan_in_one_launch(torch_gpu, T, k, E):
+    """moe_permute_plan: the sort and the schedule from one launch must be the oracle's counting sort
+    and -- bit for bit -- the plan that moe_plan_tiles makes from its counts (all five policies)."""
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    dev = torch.device("cuda:0")
+    _note("permute_plan T=%d k=%d E=%d" % (T, k, E))
+    r = np.random.default_rng(T * 11 + k)
+    p = 1.0 / np.arange(1, E + 1) ** 1.1
+    idx = r.choice(E, size=(T, k), p=p / p.sum()).astype(np.int32)
+    ref = O.permute(idx, E)
+    A, G, q, tile_m = T * k, 8, 50, 128
+    cap = B.moe_plan_capacity(A, E, tile_m, G)
+    idx_d = torch.from_numpy(idx).to(dev)
+    for policy in range(5):
+        out = {n: torch.full((m,), -3, dtype=torch.int32, device=dev) for n, m in (("counts", E), ("offsets", E + 1), ("perm", A), ("inv_perm", A))}
+        tiles = torch.full((cap, 4), -1, dtype=torch.int32, device=dev)
+        hdr = torch.full((B.MOE_PLAN_HDR_INTS,), -1, dtype=torch.int32, device=dev)
+        sched = torch.full((E, G), -1, dtype=torch.int32, device=dev)
+        B.moe_permute_plan(idx_d, T, E, k, out["counts"], out["offsets"], out["perm"], out["inv_perm"], tile_m, G, q, policy,
+                           tiles, cap, hdr, sched)
+        torch.cuda.synchronize()
+        for n in out:
+            assert np.array_equal(to_numpy(out[n]), ref[n]), (n, policy)
+        tiles2 = torch.full((cap, 4), -1, dtype=torch.int32, device=dev)
+        hdr2 = torch.full((B.MOE_PLAN_HDR_INTS,), -1, dtype=torch.int32, device=dev)
+        sched2 = torch.full((E, G), -1, dtype=torch.int32, device=dev)
+        B.moe_plan_tiles(out["counts"], out["offsets"], E, A, tile_m, G, q, policy, tiles2, cap, hdr2, sched2)
+        torch.cuda.synchronize()
+        assert torch.equal(tiles, tiles2) and torch.equal(hdr, hdr2) and torch.equal(sched, sched2), policy
+    O.validate_tiles(to_numpy(tiles)[:int(to_numpy(hdr)[0])], to_numpy(hdr)[4:4 + G + 1], ref["counts"], ref["offsets"], tile_m, G)
+    with pytest.raises(B.MoeError) as e:
+        B.moe_permute_plan(idx_d, B.MOE_PERMUTE_PLAN_MAX + 1, E, 1, out["counts"], out["offsets"], out["perm"], out["inv_perm"],
+                           tile_m, G, q, 1, tiles, 1 << 20, hdr, None)
+    assert e.value.status == B.MOE_ERR_UNSUPPORTED
+
+
 def test_permute_fp32_rows_and_empty_input(torch_gpu):
     torch = torch_gpu
     from paper_2506_12417_amd import binding as B
