@@ -85,6 +85,9 @@ struct Cfg {
 
 // (The body is a __device__ function: it uses buffer-descriptor types that exist only on the
 // device side, and the host pass must still be able to instantiate the kernel's stub.)
+// (Every lambda of the body is force-inlined: one that the compiler leaves as a call takes its
+// captures through memory, and with them go the LDS address space of the ring and the
+// wave-uniformity of the item bookkeeping -- flat loads and vector loads with full waits.)
 template <int EPI, int BM, int BN, int BK, int RING, int WM, int WN, int CS, bool GATHER>
 __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_mat, int K, int N,
                                                const void* const* __restrict__ w_ptrs,
@@ -138,7 +141,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // them out on demand measured no gain there, and it has no register to spare)
     const bool dyn = RING >= 3 && KT >= 4;
     int* ids = (int*)(ring + C::SMEM - C::ROWINFO_BYTES - 16);
-    auto leave = [&]() {                                    // (every work-group of a dynamic launch passes here once)
+    auto leave = [&]() __attribute__((always_inline)) {                                    // (every work-group of a dynamic launch passes here once)
         if (dyn && tid == 0) {
             const int before = __hip_atomic_fetch_add(done_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (before == (int)gridDim.x - 1) {
@@ -176,12 +179,12 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     if (dyn && tid == 0) ids[1] = stride + __hip_atomic_fetch_add(next_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     // id of the seq-th item of this work-group (seq >= 1)
-    auto item_of = [&](int seq, int prev) { return dyn ? sgpr(ids[seq & 3]) : prev + stride; };
+    auto item_of = [&](int seq, int prev) __attribute__((always_inline)) { return dyn ? sgpr(ids[seq & 3]) : prev + stride; };
     // Wavefront 0 asks for the id of item `seq`; the answer is passed on by publish() once the
     // wait of a later K-step has covered it (loads and this request complete in issue order).
     int f_seq = -1, f_ready = 0;
     // item -> (tile of the bin, column block)
-    auto locate = [&](int it, int& tile_idx, int& cb) {
+    auto locate = [&](int it, int& tile_idx, int& cb) __attribute__((always_inline)) {
         if (by_block) {
             const uint32_t u = (uint32_t)sgpr((int)blk[it / n_col_blocks]);
             const int f = (int)(u & 0xffffu), sz = (int)(u >> 16);
@@ -211,7 +214,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // the item's id, one item ahead (see publish()).  When the loader turns to the item, every
     // lane reads the rows of its NA passes and keeps their byte offsets.
     unsigned voff_a[GATHER ? C::NA : 1];
-    auto fetch_rows = [&](int par, int id) {               // (wavefront 0)
+    auto fetch_rows = [&](int par, int id) __attribute__((always_inline)) {               // (wavefront 0)
         int cb, ti;
         locate(id, ti, cb);
         const moe_tile t = tiles[bin_start + ti];
@@ -222,7 +225,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rt, (lds_void_t*)(rinfo + par * 2 * BM + i * 64), 4,
                                                      (unsigned)(i * 64 + lane) * 4u, 0, 0, 0);
     };
-    auto rows_to_offsets = [&](int par, int rc) {
+    auto rows_to_offsets = [&](int par, int rc) __attribute__((always_inline)) {
         const unsigned piece = (unsigned)(((tid % C::PPR) ^ C::swz(ld_row)) << 4);
 #pragma unroll
         for (int q = 0; q < C::NA; ++q) {
@@ -233,7 +236,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             voff_a[q] = row < rc ? src * (unsigned)K * 2u + piece : 0xFFFFFFF0u;
         }
     };
-    auto load_item = [&](int it) {
+    auto load_item = [&](int it) __attribute__((always_inline)) {
         int cb, ti;
         locate(it, ti, cb);
         const moe_tile t = tiles[bin_start + ti];
@@ -250,7 +253,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         l_rb = make_rsrc(wmat + (size_t)n0 * K, (unsigned)nr * (unsigned)K * 2u);
     };
     // load q of a stage (the A passes first, then the B passes), and the bookkeeping once all are out
-    auto issue_load = [&](int q) {
+    auto issue_load = [&](int q) __attribute__((always_inline)) {
         unsigned char* st = ring + l_buf * C::STAGE_BYTES + wave * 1024;
         const unsigned k_off = (unsigned)l_kt * (BK * 2);
         if (q < C::NA)
@@ -260,7 +263,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             __builtin_amdgcn_raw_ptr_buffer_load_lds(l_rb, (lds_void_t*)(st + C::A_BYTES + (q - C::NA) * (C::NW * 1024)), 16,
                                                      ld_voff0 + (unsigned)(q - C::NA) * ld_pass, k_off, 0, 0);
     };
-    auto issue_done = [&]() {
+    auto issue_done = [&]() __attribute__((always_inline)) {
         ++issued;
         l_buf = l_buf + 1 == RING ? 0 : l_buf + 1;
         if (++l_kt == KT) {
@@ -282,7 +285,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             }
         }
     };
-    auto issue = [&]() {
+    auto issue = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < C::LPS; ++q) issue_load(q);
         issue_done();
@@ -304,7 +307,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     const int b_delta = sgpr(C::A_BYTES + (wn * C::WTN - wm * 32) * C::ROW_BYTES);
     bf16x8 af[S32][MI][2], bf[S32][NI][2];
     f32x4 acc[MI][NI][2][2];
-    auto zero_acc = [&]() {
+    auto zero_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -319,7 +322,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // the issuing wavefront until the texture path accepts it (some tens of cycles each when four
     // wavefronts issue at once), the LDS reads do not: the loads are spread between the reads so
     // that the two kinds of waiting overlap instead of adding up.
-    auto mem_phase = [&](int buf, int h) {
+    auto mem_phase = [&](int buf, int h) __attribute__((always_inline)) {
         constexpr int PER = 2 * (NI + MI), NR = S32 * PER, NL = C::LPS, STEP = NR / NL;
         static_assert(STEP >= 1, "more loads than reads in a chunk");
         // (the empty asm keeps the compiler from forming all slice addresses once, outside the loop,
@@ -344,7 +347,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         }
         if (h == 0) issue_done();
     };
-    auto mfma_chunk = [&](auto full, int mi_on) {
+    auto mfma_chunk = [&](auto full, int mi_on) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < S32; ++s)
 #pragma unroll
@@ -368,14 +371,14 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     };
     // Stage g+1 has landed once only the stages issued after it are outstanding.  (Loads
     // complete in issue order; stores that are still in flight only make the wait longer.)
-    auto wait_stage_after = [&](int g) {
+    auto wait_stage_after = [&](int g) __attribute__((always_inline)) {
         const int younger = issued - g - 2;
         if (RING >= 4 && younger >= 2) MOE_WAIT_VMCNT(2 * C::LPS);
         else if (RING >= 3 && younger >= 1) MOE_WAIT_VMCNT(C::LPS);
         else MOE_WAIT_VMCNT(0);
     };
     // (wavefront 0, after its wait of a K-step)
-    auto publish = [&]() {
+    auto publish = [&]() __attribute__((always_inline)) {
         if (dyn && wave == 0 && f_seq >= 0 && g >= f_ready) {
             const int id = stride + read_ticket();
             if (lane == 0) ids[f_seq & 3] = id;
@@ -387,7 +390,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         }
     };
     // (nothing may move across a phase boundary: neither memory operations nor matrix-core work)
-    auto phase_barrier = [&]() {
+    auto phase_barrier = [&]() __attribute__((always_inline)) {
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();
@@ -404,7 +407,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     constexpr int ES = HALF_IN ? 4 : 2;
     const unsigned ld_bytes = (unsigned)ld_out * ES;
     const unsigned st_voff = (unsigned)(wm * 32 + 4 * lq) * ld_bytes + (unsigned)(2 * l16) * ES;
-    auto store_pair = [&](__amdgpu_buffer_rsrc_t ro, float lo, float hi, unsigned voff, unsigned soff) {
+    auto store_pair = [&](__amdgpu_buffer_rsrc_t ro, float lo, float hi, unsigned voff, unsigned soff) __attribute__((always_inline)) {
         if (HALF_IN) {
             u32x2 v = {__float_as_uint(lo), __float_as_uint(hi)};
             __builtin_amdgcn_raw_buffer_store_b64(v, ro, voff, soff, 0);
@@ -415,7 +418,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, b), ro, voff, soff, 0);
         }
     };
-    auto epilogue = [&](__amdgpu_buffer_rsrc_t ro, int mi_on, int n0) {
+    auto epilogue = [&](__amdgpu_buffer_rsrc_t ro, int mi_on, int n0) __attribute__((always_inline)) {
         // (the empty asm keeps the compiler from computing all row offsets once, up front, and
         // holding -- or spilling -- them across the whole kernel)
         unsigned st_base = st_voff;
@@ -457,7 +460,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // global -> LDS loads during the item's first K-steps: first the tokens of the tile's rows,
     // then, indexed by them, the gate values.
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(out, (unsigned)out_rows * ld_bytes);
-    auto fetch_tokens = [&](int par, int row_begin, int rc) {
+    auto fetch_tokens = [&](int par, int row_begin, int rc) __attribute__((always_inline)) {
         if (wave < BM / 64) {
             const __amdgpu_buffer_rsrc_t rt = make_rsrc(row_token + row_begin, (unsigned)(rc > 0 ? rc : 0) * 4u);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rt, (lds_void_t*)(rinfo + par * 2 * BM + wave * 64), 4,
@@ -465,14 +468,14 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             if (!row_gate) ((float*)rinfo)[par * 2 * BM + BM + wave * 64 + lane] = 1.f;
         }
     };
-    auto fetch_gates = [&](int par) {
+    auto fetch_gates = [&](int par) __attribute__((always_inline)) {
         if (row_gate && wave < BM / 64) {
             const unsigned tok = (unsigned)rinfo[par * 2 * BM + wave * 64 + lane];
             const __amdgpu_buffer_rsrc_t rg = make_rsrc(row_gate, (unsigned)out_rows * 4u);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rg, (lds_void_t*)(rinfo + par * 2 * BM + BM + wave * 64), 4, tok * 4u, 0, 0, 0);
         }
     };
-    auto epilogue_scatter = [&](int par, int rc, int mi_on, int n0) {
+    auto epilogue_scatter = [&](int par, int rc, int mi_on, int n0) __attribute__((always_inline)) {
         const int lane_row = wm * 32 + 4 * lq;
         const unsigned col_off = (unsigned)(2 * l16) * 4u;
 #pragma unroll
@@ -497,7 +500,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
     // the finished item: p_* describe it
     int p_mi_on = 0, p_n0 = 0, p_rc = 0, p_par = 0;
     __amdgpu_buffer_rsrc_t p_ro = make_rsrc(out, 0u);       // the previous item, stored in the next one's first phase
-    auto finish_prev = [&]() {
+    auto finish_prev = [&]() __attribute__((always_inline)) {
         if constexpr (SCAT) epilogue_scatter(p_par, p_rc, p_mi_on, p_n0);
         else epilogue(p_ro, p_mi_on, p_n0);
     };
@@ -539,7 +542,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
             make_rsrc((const unsigned char*)out + (size_t)tile.row_begin * ld_bytes, (unsigned)(rc > 0 ? rc : 0) * ld_bytes);
 
         // One K-step of this wavefront: per chunk a memory phase and a multiply phase.
-        auto k_step = [&](auto full, bool first_of_item, bool last_of_all) {
+        auto k_step = [&](auto full, bool first_of_item, bool last_of_all) __attribute__((always_inline)) {
 #pragma unroll
             for (int h = 0; h < PH; ++h) {
                 // ---- memory phase: stage g's buffer is complete; the buffer of stage g-1 has been
@@ -583,7 +586,7 @@ __device__ __forceinline__ void gemm_bf16_body(const uint16_t* __restrict__ a_ma
         // The id of the next item is known by this item's last K-step: the loader needed it
         // RING-1 K-steps ago.  (With one K-step per item there is no handing out: fixed stride.)
         int next = item + stride;
-        auto run_item = [&](auto full) {
+        auto run_item = [&](auto full) __attribute__((always_inline)) {
             if constexpr (SCAT) fetch_tokens(c_seq & 1, tile.row_begin, rc);
             k_step(full, true, KT == 1 && next >= n_items);
             for (int kt = 1; kt < KT; ++kt) {

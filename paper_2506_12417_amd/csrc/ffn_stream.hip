@@ -101,7 +101,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
     // gather, the item's source rows) to arrive in time; shorter contractions keep a fixed stride.
     const bool dyn = KT >= 2 * PF;
     int* ids = (int*)(ring + C::SMEM - C::ROWINFO_BYTES - 16);
-    auto leave = [&]() {
+    auto leave = [&]() __attribute__((always_inline)) {
         if (dyn && tid == 0) {
             const int before = __hip_atomic_fetch_add(done_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (before == (int)gridDim.x - 1) {
@@ -132,8 +132,8 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
     }
     if (dyn && tid == 0) ids[1] = stride + __hip_atomic_fetch_add(next_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    auto item_of = [&](int seq, int prev) { return dyn ? sgpr(ids[seq & 3]) : prev + stride; };
-    auto locate = [&](int it, int& tile_idx, int& cb) {
+    auto item_of = [&](int seq, int prev) __attribute__((always_inline)) { return dyn ? sgpr(ids[seq & 3]) : prev + stride; };
+    auto locate = [&](int it, int& tile_idx, int& cb) __attribute__((always_inline)) {
         if (by_block) {
             const uint32_t u = (uint32_t)sgpr((int)blk[it / n_col_blocks]);
             const int f = (int)(u & 0xffffu), sz = (int)(u >> 16);
@@ -163,7 +163,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
     unsigned voff_a[GATHER ? NA : 1];
     u32x4 bq[PF][4];                                         // [slot][2 * (16-row block) + slice]
 
-    auto fetch_rows = [&](int par, int id) {                 // (wavefront 0) source rows of item id -> rinfo[par]
+    auto fetch_rows = [&](int par, int id) __attribute__((always_inline)) {                 // (wavefront 0) source rows of item id -> rinfo[par]
         int cb, ti;
         locate(id, ti, cb);
         const moe_tile t = tiles[bin_start + ti];
@@ -174,7 +174,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rt, (lds_void_t*)(rinfo + par * 2 * BM + i * 64), 4,
                                                      (unsigned)(i * 64 + lane) * 4u, 0, 0, 0);
     };
-    auto load_item = [&](int it) {
+    auto load_item = [&](int it) __attribute__((always_inline)) {
         int cb, ti;
         locate(it, ti, cb);
         const moe_tile t = tiles[bin_start + ti];
@@ -206,7 +206,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
         l_rb = make_rsrc(wmat + (size_t)(nr ? n0 : 0) * K, (unsigned)nr * (unsigned)K * 2u);
     };
     // the loads of the next K-step of the stream: rows into LDS stage l_stage, weights into slot p
-    auto issue = [&](auto slot) {
+    auto issue = [&](auto slot) __attribute__((always_inline)) {
         constexpr int p = decltype(slot)::value;
         unsigned char* st = ring + l_stage * C::A_BYTES + wave * 1024;
         const unsigned k_off = (unsigned)sgpr(l_kt * 128);
@@ -246,7 +246,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
     // (stage) + row * 128 + ((4 s + lq) ^ swizzle) * 16; slice 1 is slice 0 with bit 6 flipped
     const int a_rd0 = l16 * C::ROW_BYTES + ((lq ^ ((l16 >> 1) & 7)) << 4);
     f32x4 acc[MB][2];
-    auto zero_acc = [&]() {
+    auto zero_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int m = 0; m < MB; ++m)
 #pragma unroll
@@ -254,7 +254,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[m][b][r] = 0.f;
     };
-    auto compute = [&](auto slot, auto full, int stage, int mb_on) {
+    auto compute = [&](auto slot, auto full, int stage, int mb_on) __attribute__((always_inline)) {
         constexpr int p = decltype(slot)::value;
         // (the empty asm keeps the compiler from forming every fragment address once, outside the
         // loop, and holding them in registers: the 16-row blocks are immediate offsets of these two)
@@ -291,7 +291,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
     constexpr int ES = HALF_IN ? 4 : 2;
     const unsigned ld_bytes = (unsigned)ld_out * ES;
     const unsigned st_voff = (unsigned)(4 * lq) * ld_bytes + (unsigned)(2 * l16) * ES;
-    auto store_pair = [&](__amdgpu_buffer_rsrc_t ro, float lo, float hi, unsigned voff, unsigned soff) {
+    auto store_pair = [&](__amdgpu_buffer_rsrc_t ro, float lo, float hi, unsigned voff, unsigned soff) __attribute__((always_inline)) {
         if (HALF_IN) {
             u32x2 v = {__float_as_uint(lo), __float_as_uint(hi)};
             __builtin_amdgcn_raw_buffer_store_b64(v, ro, voff, soff, 0);
@@ -302,7 +302,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, b), ro, voff, soff, 0);
         }
     };
-    auto epilogue = [&](__amdgpu_buffer_rsrc_t ro, int mb_on, int col) {
+    auto epilogue = [&](__amdgpu_buffer_rsrc_t ro, int mb_on, int col) __attribute__((always_inline)) {
         if (col >= N) return;
         // (the empty asm keeps the compiler from computing all row offsets once, up front, and
         // holding -- or spilling -- them across the whole kernel)
@@ -324,7 +324,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
     // scatter epilogue (Alg. 1 step 6 folded in for top-1 routing): token and gate value of every
     // row of the tile wait in LDS, rinfo[parity of the item][0: tokens, 1: gates][row]
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(out, (unsigned)out_rows * ld_bytes);
-    auto fetch_tokens = [&](int par, int row_begin, int rc) {
+    auto fetch_tokens = [&](int par, int row_begin, int rc) __attribute__((always_inline)) {
         if (wave < BM / 64) {
             const __amdgpu_buffer_rsrc_t rt = make_rsrc(row_token + row_begin, (unsigned)(rc > 0 ? rc : 0) * 4u);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rt, (lds_void_t*)(rinfo + par * 2 * BM + wave * 64), 4,
@@ -332,14 +332,14 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
             if (!row_gate) ((float*)rinfo)[par * 2 * BM + BM + wave * 64 + lane] = 1.f;
         }
     };
-    auto fetch_gates = [&](int par) {
+    auto fetch_gates = [&](int par) __attribute__((always_inline)) {
         if (row_gate && wave < BM / 64) {
             const unsigned tok = (unsigned)rinfo[par * 2 * BM + wave * 64 + lane];
             const __amdgpu_buffer_rsrc_t rg = make_rsrc(row_gate, (unsigned)out_rows * 4u);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rg, (lds_void_t*)(rinfo + par * 2 * BM + BM + wave * 64), 4, tok * 4u, 0, 0, 0);
         }
     };
-    auto epilogue_scatter = [&](int par, int rc, int mb_on, int col) {
+    auto epilogue_scatter = [&](int par, int rc, int mb_on, int col) __attribute__((always_inline)) {
         if (col >= N) return;
         const unsigned col_off = (unsigned)(2 * l16) * 4u;
         // (one base address, the rows as immediate offsets: the empty asm keeps the compiler from
@@ -366,7 +366,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
 
     // (wavefront 0, after its wait of a K-step) the answer of the last ticket -> ids[], and with
     // the gather the source rows of that item -> rinfo[]
-    auto publish = [&](int g) {
+    auto publish = [&](int g) __attribute__((always_inline)) {
         if (dyn && wave == 0 && f_seq >= 0 && g >= f_ready) {
             const int id = stride + read_ticket();
             if (lane == 0) ids[f_seq & 3] = id;
@@ -375,7 +375,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
             MOE_WAIT_LGKMCNT(0);
         }
     };
-    auto step_barrier = [&]() {
+    auto step_barrier = [&]() __attribute__((always_inline)) {
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();
@@ -404,7 +404,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
     int rc = 0, col = 0, mb_on = 0, row_begin = 0;
     int st_steps = 0, st_blocks = 0;                          // stores of the last item still counted by the waits
     __amdgpu_buffer_rsrc_t ro = make_rsrc(out, 0u);
-    auto begin_item = [&]() {
+    auto begin_item = [&]() __attribute__((always_inline)) {
         int cb, ti;
         locate(item, ti, cb);
         const moe_tile tile = tiles[bin_start + ti];
@@ -416,7 +416,7 @@ __device__ __forceinline__ void gemm_stream_body(const uint16_t* __restrict__ a_
         ro = make_rsrc((const unsigned char*)out + (size_t)row_begin * ld_bytes, (unsigned)(rc > 0 ? rc : 0) * ld_bytes);
     };
     begin_item();
-    auto k_step = [&](auto slot) {
+    auto k_step = [&](auto slot) __attribute__((always_inline)) {
         constexpr int p = decltype(slot)::value;
         // this wavefront's loads of the K-step have landed: its rows' pieces in LDS, its weights in slot p.
         // Loads and stores complete in the order they were issued, so what may stay outstanding is
