@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe.so")
-SOURCES = ["common.hip", "route.hip", "route_mfma.hip", "permute.hip", "plan.hip", "ffn.hip", "ffn_bf16.hip", "ffn_stream.hip", "combine.hip", "pack.hip", "prefetch.hip"]
+SOURCES = ["common.hip", "route.hip", "route_mfma.hip", "permute.hip", "plan.hip", "ffn.hip", "ffn_bf16.hip", "ffn_stream.hip", "ffn_wide.hip", "combine.hip", "pack.hip", "prefetch.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -193,6 +193,29 @@ def check_stream_registers(asm_text: str):
     return bad
 
 
+def check_no_flat_access(asm_text: str):
+    """The GEMM kernels keep their whole state in registers and reach memory through buffer
+    descriptors and LDS instructions only.  A flat_load / flat_store in one of them means that
+    the compiler has left part of that state (a closure, a descriptor, an index table) in
+    scratch memory behind generic pointers: every such access waits for all loads in flight,
+    and the kernel runs several times slower with correct results -- a failure no parity test
+    sees.  Returns a list of (kernel, instruction) found in the device assembly."""
+    bad = []
+    kernel = None
+    for line in asm_text.split("\n"):
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            kernel = m.group(1)
+            continue
+        if line.startswith(".Lfunc_end"):
+            kernel = None
+            continue
+        code = line.split(";")[0].strip()
+        if kernel and "gemm_" in kernel and re.match(r"flat_(load|store|atomic)", code):
+            bad.append((kernel, code))
+    return bad
+
+
 def build(verbose: bool = True, jobs: int = 8) -> str:
     """Compiles every source (always; no staleness check) and links libmoe.so."""
     obj_dir = os.path.join(HERE, "_build")
@@ -201,7 +224,7 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
     objs = []
     # the device assembly of the GEMM kernels, for check_ticket_register (same flags, same code)
     asm_paths = []
-    for src in ("ffn_bf16.hip", "ffn_stream.hip"):
+    for src in ("ffn_bf16.hip", "ffn_stream.hip", "ffn_wide.hip"):
         asm_path = os.path.join(obj_dir, src.replace(".hip", ".s"))
         asm_paths.append(asm_path)
         asm_cmd = [HIPCC, *FLAGS, "-S", "--cuda-device-only", os.path.join(CSRC, src), "-o", asm_path]
@@ -233,6 +256,10 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
         if bad:
             raise RuntimeError("%s: v%d is not private to the ticket instructions:\n%s"
                                % (os.path.basename(asm_path), TICKET_REG, "\n".join("  %s: %s" % b for b in bad[:20])))
+        bad = check_no_flat_access(open(asm_path).read())
+        if bad:
+            raise RuntimeError("%s: kernel state behind generic pointers (flat accesses):\n%s"
+                               % (os.path.basename(asm_path), "\n".join("  %s: %s" % b for b in bad[:20])))
     bad = check_stream_registers(open(asm_paths[1]).read())
     if bad:
         raise RuntimeError("ffn_stream.hip: registers of the weight loads are touched by other code:\n%s"

@@ -187,6 +187,9 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
         const bool few_rows = tile_m == 128 && g_kernel_mode == 2;
         auto stream = [&](int epi, int K) { return few_rows && moe_gemm_stream_supports(epi, K); };
         auto stream_narrow = [&](int N) { return tiles_est * ((N + 255) / 256) < 4 * MOE_GEMM_GRID; };
+        // 256-row tiles (many rows per expert: the arithmetic-bound case) go to the four-wavefront
+        // kernels of ffn_wide.hip unless the LDS-ring kernels are asked for (moe_ffn_kernel_mode 1).
+        auto wide = [&](int epi, int K) { return tile_m == 256 && g_kernel_mode != 1 && moe_gemm_wide_supports(epi, K); };
         if (phases & 1) {
             const int epi = act == MOE_SWIGLU ? MOE_EPI_SWIGLU : MOE_EPI_RELU;
             if (gather.on && stream(epi, d))
@@ -197,6 +200,8 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
                                                  w_in, tiles, plan_hdr, h_scratch, F, st, gather.perm, gather.k);
             else if (stream(epi, d))
                 rc = moe_launch_gemm_stream(epi, stream_narrow(n1), x_perm, d, n1, w_in, tiles, plan_hdr, h_scratch, F, st);
+            else if (wide(epi, d))
+                rc = moe_launch_gemm_wide(epi, x_perm, d, n1, w_in, tiles, plan_hdr, h_scratch, F, st);
             else
                 rc = moe_launch_gemm_bf16(epi, tile_m, narrow(n1), x_perm, d, n1,
                                           w_in, tiles, plan_hdr, h_scratch, F, st);
@@ -207,6 +212,8 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
             if (stream(epi, F))
                 rc = moe_launch_gemm_stream(epi, stream_narrow(d), h_scratch, F, d, w_out, tiles, plan_hdr, (void*)y_perm, d, st,
                                             top1.perm, top1.gate_w, top1.on ? A : 0);
+            else if (wide(epi, F))
+                rc = moe_launch_gemm_wide(epi, h_scratch, F, d, w_out, tiles, plan_hdr, (void*)y_perm, d, st);
             else if (top1.on)
                 rc = moe_launch_gemm_bf16(MOE_EPI_SCATTER, tile_m, narrow(d), h_scratch, F, d, w_out, tiles, plan_hdr,
                                           (void*)y_perm, d, st, top1.perm, top1.gate_w, A);

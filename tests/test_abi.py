@@ -294,3 +294,21 @@ def test_build_checks_the_registers_of_the_streamed_weight_loads():
         text = open(asm).read()
         assert text.count("buffer_load_dwordx4") > 32
         assert b.check_stream_registers(text) == [] and b.check_ticket_register(text) == []
+
+
+def test_build_refuses_gemm_kernels_with_state_behind_generic_pointers():
+    """build.check_no_flat_access: a GEMM kernel whose device assembly holds a flat access keeps
+    part of its state in scratch memory (slow, but correct: no parity test would notice)."""
+    from paper_2506_12417_amd import build as b
+    ok = "_ZN1x16gemm_wide_kernelILi0EEEvv:\n\tbuffer_load_dwordx4 v1, s[0:3], 0 offen lds\n\tds_read_b128 v[0:3], v4\n\ts_endpgm\n.Lfunc_end0:\n"
+    assert b.check_no_flat_access(ok) == []
+    for line in ("flat_load_dword v2, v[2:3]", "flat_store_dwordx2 v[2:3], v[4:5]", "flat_atomic_add v1, v[2:3], v4"):
+        text = ok.replace("\ts_endpgm", "\t" + line + "\n\ts_endpgm")
+        assert [c for _, c in b.check_no_flat_access(text)] == [line]
+    # other kernels may use flat accesses
+    assert b.check_no_flat_access("_Z11plan_kernelv:\n\tflat_load_dword v2, v[2:3]\n\ts_endpgm\n.Lfunc_end0:\n") == []
+    for name in ("ffn_bf16.s", "ffn_stream.s", "ffn_wide.s"):
+        asm = os.path.join(os.path.dirname(b.LIB), "_build", name)
+        if os.path.exists(asm):      # the assembly of the library that is loaded here
+            text = open(asm).read()
+            assert "gemm_" in text and b.check_no_flat_access(text) == []

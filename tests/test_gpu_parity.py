@@ -524,6 +524,50 @@ def test_streaming_kernels_give_the_bits_of_the_lds_ring_kernels(torch_gpu, T, d
     assert max_err_over_rms(to_numpy(out[2][0]), y_o) <= TOL["bf16"]
 
 
+WIDE_CASES = [
+    # T, d, F, E, k, act, skew: the four-wavefront kernels for 256-row tiles against the LDS-ring kernels
+    (3000, 256, 512, 4, 2, "swiglu", "hot"),          # full and ragged tiles, several column blocks
+    (5000, 768, 3072, 6, 1, "relu", "zipf"),          # c5's shapes
+    (2500, 512, 1408, 3, 2, "swiglu", "zipf"),        # F not a multiple of the column block: ragged last block in the first product
+    (1100, 320, 704, 5, 1, "relu", "uniform"),        # d not a multiple of the column block: ragged last block in the second product
+    (40, 256, 256, 2, 1, "swiglu", "uniform"),        # every tile a few rows: whole row blocks skipped
+    (1, 256, 256, 1, 1, "relu", "uniform"),           # a single row
+]
+
+
+@pytest.mark.parametrize("T,d,F,E,k,act,skew", WIDE_CASES)
+def test_four_wavefront_kernels_give_the_bits_of_the_lds_ring_kernels(torch_gpu, T, d, F, E, k, act, skew):
+    """256-row tiles: the kernels of four wavefronts (the default, mode 0) and the LDS-ring kernels
+    of eight (moe_ffn_kernel_mode 1) must give identical hidden activations and outputs, and the
+    layer must agree with the oracle."""
+    torch = torch_gpu
+    from paper_2506_12417_amd import binding as B
+    wl = W.WORKLOADS["c4"].scaled(T=T, d=d, F=F, E=E, k=k, act=act, skew=skew)
+    _note("wide vs ring T=%d d=%d F=%d E=%d k=%d %s %s" % (T, d, F, E, k, act, skew))
+    inp = W.make_inputs(wl)
+    layer = make_layer(wl, inp, tile_m=256)
+    x = layer_x(layer, inp)
+    before = B.moe_ffn_kernel_mode(-1)
+    try:
+        out = {}
+        for mode in (1, 0):
+            B.moe_ffn_kernel_mode(mode)
+            layer.h.fill_(float("nan"))
+            layer.y.fill_(float("nan"))
+            layer.y_perm.fill_(float("nan"))
+            y = layer.forward(x).clone()
+            torch.cuda.synchronize()
+            out[mode] = (y, layer.h.clone(), layer.y_perm.clone())
+        for a, b_, name in zip(out[1], out[0], ("y", "H", "y_perm")):
+            assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a.view(torch.int16),
+                               b_.view(torch.int32) if b_.dtype == torch.float32 else b_.view(torch.int16)), name
+    finally:
+        B.moe_ffn_kernel_mode(before)
+    idx_o, w_o, _ = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
+    y_o = O.moe_layer(inp["x"], idx_o, w_o, expert_dict(wl, inp), wl.act)
+    assert max_err_over_rms(to_numpy(out[0][0]), y_o) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("T", [300000, 400000])
 def test_layer_with_very_many_tiles_in_a_bin(torch_gpu, T):
     """All rows on ONE bin in 128-row tiles.  400 000 rows: more than 3 100 tiles, beyond the per-bin
