@@ -296,15 +296,20 @@ MOE_API int moe_ffn_tile_m(moe_dtype dt);
  * their tiles are mostly empty at 256 rows).  Plan and FFN must be given the same value. */
 MOE_API int moe_ffn_pick_tile_m(moe_dtype dt, int A, int E);
 
-/* The 128-row bf16 configuration has two families of kernels that compute the same bits: one
- * stages both operands through an LDS ring, the other streams the weights straight into
- * registers (meant for experts with few rows, where a product costs the fetch of its weights:
- * section 4.4's regime below q; it covers the ReLU first product and the second product, the
- * scatter form from F >= 512 on).  The LDS ring is the default: it is the faster one on every
- * workload measured so far.  moe_ffn_kernel_mode sets the choice for the process -- 0 default,
- * 1 the LDS ring, 2 the streaming kernels wherever they cover the call, -1 leaves it -- and
- * returns the previous setting (a negative moe_status on a bad argument).  For measurements and
- * tests. */
+/* Each bf16 tile height has two families of kernels that compute the same bits.
+ * 128 rows: one stages both operands through an LDS ring (eight wavefronts), the other streams
+ * the weights straight into registers (meant for experts with few rows, where a product costs
+ * the fetch of its weights: section 4.4's regime below q; it covers the ReLU first product and
+ * the second product, the scatter form from F >= 512 on).  The LDS ring is the default: it is
+ * the faster one on every workload measured so far.
+ * 256 rows: the LDS ring with eight wavefronts of 128 x 64 outputs each, and four wavefronts of
+ * 128 x 128 (a third less LDS traffic per multiply-add, which is what the arithmetic-bound case
+ * pays for; d and F multiples of 64, at least 256).  The four wavefronts are the default; only
+ * they offer the row gather of moe_grouped_ffn_fused at this height.
+ * moe_ffn_kernel_mode sets the choice for the process -- 0 default, 1 the LDS ring with eight
+ * wavefronts at both heights, 2 the streaming kernels wherever they cover the call, -1 leaves
+ * it -- and returns the previous setting (a negative moe_status on a bad argument).  For
+ * measurements and tests. */
 MOE_API int moe_ffn_kernel_mode(int mode);
 
 MOE_API int moe_grouped_ffn(const void* x_perm, int A, int d, int F, int E, moe_act act, moe_dtype dt,
@@ -363,8 +368,9 @@ MOE_API int moe_grouped_ffn_top1_phase(int phase, const void* x_perm, int T, int
  *            moe_grouped_ffn_top1 (gate_w [T] fp32 or NULL; F >= 512)
  *   k  > 1 : y_out = y_perm [T*k,d] fp32 as in moe_grouped_ffn (gate_w is not used); the caller
  *            combines with moe_unpermute_combine
- * other arguments as moe_grouped_ffn.  MOE_BF16 only, tile_m = 128, d >= 256, x smaller than
- * 4 GiB (MOE_ERR_UNSUPPORTED otherwise: use the separate calls).
+ * other arguments as moe_grouped_ffn.  MOE_BF16 only, d >= 256, x smaller than 4 GiB; with
+ * tile_m = 256 only while moe_ffn_kernel_mode is not 1 (MOE_ERR_UNSUPPORTED otherwise: use the
+ * separate calls).
  */
 MOE_API int moe_grouped_ffn_fused(const void* x, int T, int d, int F, int E, int k, moe_act act, moe_dtype dt,
                                   const void* const* w_in, const void* const* w_out,

@@ -195,6 +195,10 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
             if (gather.on && stream(epi, d))
                 rc = moe_launch_gemm_stream_gather(stream_narrow(n1), x_perm, gather.x_rows, d, n1, w_in, tiles, plan_hdr,
                                                    h_scratch, F, st, gather.perm, gather.k);
+            else if (gather.on && tile_m == 256)
+                // (fused_impl has checked that the four-wavefront kernels are in use and cover d)
+                rc = moe_launch_gemm_wide_gather(epi, x_perm, gather.x_rows, d, n1, w_in, tiles, plan_hdr, h_scratch, F, st,
+                                                 gather.perm, gather.k);
             else if (gather.on)
                 rc = moe_launch_gemm_bf16_gather(epi, x_perm, gather.x_rows, d, n1,
                                                  w_in, tiles, plan_hdr, h_scratch, F, st, gather.perm, gather.k);
@@ -213,7 +217,8 @@ static int grouped_ffn_impl(int phases, const void* x_perm, int A, int d, int F,
                 rc = moe_launch_gemm_stream(epi, stream_narrow(d), h_scratch, F, d, w_out, tiles, plan_hdr, (void*)y_perm, d, st,
                                             top1.perm, top1.gate_w, top1.on ? A : 0);
             else if (wide(epi, F))
-                rc = moe_launch_gemm_wide(epi, h_scratch, F, d, w_out, tiles, plan_hdr, (void*)y_perm, d, st);
+                rc = moe_launch_gemm_wide(epi, h_scratch, F, d, w_out, tiles, plan_hdr, (void*)y_perm, d, st, top1.perm,
+                                          top1.gate_w, top1.on ? A : 0);
             else if (top1.on)
                 rc = moe_launch_gemm_bf16(MOE_EPI_SCATTER, tile_m, narrow(d), h_scratch, F, d, w_out, tiles, plan_hdr,
                                           (void*)y_perm, d, st, top1.perm, top1.gate_w, A);
@@ -290,7 +295,10 @@ static int fused_impl(int phases, const void* x, int T, int d, int F, int E, int
     MOE_REQUIRE(dt == MOE_BF16, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: MOE_BF16 only (dtype %d)", (int)dt);
     MOE_REQUIRE(T >= 0 && k >= 1, MOE_ERR_ARG, "moe_grouped_ffn_fused: T=%d k=%d", T, k);
     MOE_REQUIRE((long long)T * k < (1ll << 30), MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: T*k too large");
-    MOE_REQUIRE(tile_m == 128, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: needs 128-row tiles (tile_m=%d)", tile_m);
+    MOE_REQUIRE(tile_m == 128 || tile_m == 256, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: bf16 tile_m=%d, must be 128 or 256", tile_m);
+    MOE_REQUIRE(tile_m == 128 || (g_kernel_mode != 1 && moe_gemm_wide_supports(MOE_EPI_RELU, d)), MOE_ERR_UNSUPPORTED,
+                "moe_grouped_ffn_fused: with 256-row tiles the row gather is done by the four-wavefront kernels only "
+                "(moe_ffn_kernel_mode %d, d=%d)", g_kernel_mode, d);
     MOE_REQUIRE(d >= 256, MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: needs d >= 256 (d=%d)", d);
     MOE_REQUIRE((long long)T * d * 2 < (1ll << 32), MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_fused: x must be smaller than 4 GiB (T=%d d=%d)", T, d);
     MOE_REQUIRE(T == 0 || perm, MOE_ERR_ARG, "moe_grouped_ffn_fused: null pointer");

@@ -36,10 +36,15 @@ int moe_launch_gemm_stream_gather(int narrow, const void* x, int x_rows, int K, 
 
 // The same products for 256-row tiles by the kernels of ffn_wide.hip (four wavefronts of 128 x 128
 // per work-group instead of eight of 128 x 64: less LDS traffic per multiply-add, which is what the
-// power-bound case pays for).  Same results, bit for bit.  epi: RELU, SWIGLU or STORE.
+// power-bound case pays for).  Same results, bit for bit; all four epilogues, and the first
+// product with the row gather folded in (arguments as for the launchers above).
 bool moe_gemm_wide_supports(int epi, int K);
 int moe_launch_gemm_wide(int epi, const void* a, int K, int N, const void* const* w, const moe_tile* tiles,
-                         const int32_t* hdr, void* out, int ld_out, hipStream_t st);
+                         const int32_t* hdr, void* out, int ld_out, hipStream_t st, const int32_t* row_token = nullptr,
+                         const float* row_gate = nullptr, int out_rows = 0);
+int moe_launch_gemm_wide_gather(int epi, const void* x, int x_rows, int K, int N, const void* const* w,
+                                const moe_tile* tiles, const int32_t* hdr, void* out, int ld_out, hipStream_t st,
+                                const int32_t* row_src, int src_div);
 
 // MOE_OK if the current device is the GPU the persistent launches are laid out for (256 compute
 // units in 8 XCDs), else MOE_ERR_UNSUPPORTED.

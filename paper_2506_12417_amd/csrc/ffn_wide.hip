@@ -72,6 +72,13 @@ struct Geo {
     const uint32_t* blk;       // LDS: first tile and tile count of the block each tile of the bin belongs to
     int K, N, KT, n_col_blocks, bin_start, n_tiles, n_items, stride;
     bool by_block;
+    // gather (first product): row r of the table's row space is row row_token[r] / a_div of a_mat,
+    // which has out_rows rows.  scatter (second product, top-1): row r goes to row row_token[r] of
+    // the output (out_rows rows), times row_gate[that row] (1 if null).
+    const int32_t* row_token;
+    const float* row_gate;
+    int out_rows, a_div;
+    int* rinfo;                // LDS: per-row tables of two items, [parity][tokens | gates][BM]
 };
 
 // item -> (tile of the bin, column block): block after block of the bin's table, column-block-major
@@ -94,9 +101,26 @@ __device__ __forceinline__ void locate(const Geo& g, int it, int& tile_idx, int&
 struct Loader {
     __amdgpu_buffer_rsrc_t ra, rb;   // the item's rows and its block of weight rows (exactly: the range check does the clipping)
     int item, kt, buf;
+    int seq;                         // gather: how many items the loader has turned to before this one
+    unsigned voff_a[WCfg::NA];       // gather: byte offsets of the source rows of this lane's NA passes
 };
 
-__device__ __forceinline__ void load_item(const Geo& g, Loader& L, int it) {
+// Gather: the source rows of an item's rows wait in LDS (rinfo[parity of the item's sequence
+// number]): every wavefront fetches 64 of them there with one global -> LDS load, one item
+// ahead.  Alg. 1's step 4 (the rows of x brought into expert order) is then done by the operand
+// loads themselves, whose per-lane addresses are free to choose.
+__device__ __forceinline__ void fetch_rows(const Geo& g, int par, int it, int wave, int lane) {
+    int cb, ti;
+    locate(g, it, ti, cb);
+    const moe_tile t = g.tiles[g.bin_start + ti];
+    const int rc = t.row_count < C::BM ? t.row_count : C::BM;
+    const __amdgpu_buffer_rsrc_t rt = make_rsrc(g.row_token + t.row_begin, (unsigned)(rc > 0 ? rc : 0) * 4u);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rt, (lds_void_t*)(g.rinfo + par * 2 * C::BM + wave * 64), 4,
+                                             (unsigned)(wave * 64 + lane) * 4u, 0, 0, 0);
+}
+
+template <bool GATHER>
+__device__ __forceinline__ void load_item(const Geo& g, Loader& L, int it, int wave, int lane, int ld_row, unsigned ld_piece) {
     int cb, ti;
     locate(g, it, ti, cb);
     const moe_tile t = g.tiles[g.bin_start + ti];
@@ -104,7 +128,23 @@ __device__ __forceinline__ void load_item(const Geo& g, Loader& L, int it) {
     const int n0 = cb * C::BN;
     const int nr = g.N - n0 < C::BN ? g.N - n0 : C::BN;
     const uint16_t* wmat = (const uint16_t*)g.w_ptrs[t.expert];
-    L.ra = make_rsrc(g.a_mat + (size_t)t.row_begin * g.K, (unsigned)(rc > 0 ? rc : 0) * (unsigned)g.K * 2u);
+    if constexpr (GATHER) {
+        L.ra = make_rsrc(g.a_mat, (unsigned)g.out_rows * (unsigned)g.K * 2u);
+        const int par = L.seq & 1;
+#pragma unroll
+        for (int q = 0; q < C::NA; ++q) {
+            const int row = q * C::ROWS_PER_PASS + ld_row;
+            unsigned src = (unsigned)g.rinfo[par * 2 * C::BM + row];
+            if (g.a_div != 1) src /= (unsigned)g.a_div;
+            // (a row past the tile's end gets an offset beyond the matrix: the range check reads zeros)
+            L.voff_a[q] = row < rc ? src * (unsigned)g.K * 2u + ld_piece : 0xFFFFFFF0u;
+        }
+        // the rows of the item after this one (its table was read one item ago)
+        if (it + g.stride < g.n_items) fetch_rows(g, par ^ 1, it + g.stride, wave, lane);
+        ++L.seq;
+    } else {
+        L.ra = make_rsrc(g.a_mat + (size_t)t.row_begin * g.K, (unsigned)(rc > 0 ? rc : 0) * (unsigned)g.K * 2u);
+    }
     L.rb = make_rsrc(wmat + (size_t)n0 * g.K, (unsigned)nr * (unsigned)g.K * 2u);
 }
 
@@ -112,26 +152,28 @@ __device__ __forceinline__ void load_item(const Geo& g, Loader& L, int it) {
 // tile: row id / PPR, position id % PPR, the piece fetched there is position ^ swz(row).  The row
 // part of an address sits in the per-lane offset (only that one is range-checked); pass i lies a
 // wave-uniform distance further down.
+template <bool GATHER>
 __device__ __forceinline__ void issue_load(const Loader& L, unsigned char* ring, int wave, unsigned ld_voff0,
                                            unsigned ld_pass, int q) {
     unsigned char* st = ring + L.buf * C::STAGE_BYTES + wave * 1024;
     const unsigned k_off = (unsigned)L.kt * (C::BK * 2);
     if (q < C::NA)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(L.ra, (lds_void_t*)(st + q * (C::NW * 1024)), 16,
-                                                 ld_voff0 + (unsigned)q * ld_pass, k_off, 0, 0);
+                                                 GATHER ? L.voff_a[q < C::NA ? q : 0] : ld_voff0 + (unsigned)q * ld_pass, k_off, 0, 0);
     else
         __builtin_amdgcn_raw_ptr_buffer_load_lds(L.rb, (lds_void_t*)(st + C::A_BYTES + (q - C::NA) * (C::NW * 1024)), 16,
                                                  ld_voff0 + (unsigned)(q - C::NA) * ld_pass, k_off, 0, 0);
 }
 
 // after the last load of a stage
-__device__ __forceinline__ void issue_done(const Geo& g, Loader& L) {
+template <bool GATHER>
+__device__ __forceinline__ void issue_done(const Geo& g, Loader& L, int wave, int lane, int ld_row, unsigned ld_piece) {
     L.buf = L.buf + 1 == C::RING ? 0 : L.buf + 1;
     if (++L.kt == g.KT) {
         L.kt = 0;
         if (L.item < g.n_items) L.item += g.stride;
         if (L.item < g.n_items) {
-            load_item(g, L, L.item);
+            load_item<GATHER>(g, L, L.item, wave, lane, ld_row, ld_piece);
         } else {
             // past the last item: empty descriptors (nothing is fetched), the schedule and the
             // count of outstanding loads stay those of the steady state
@@ -203,8 +245,8 @@ __device__ __forceinline__ void wait_landed(StoreCredit& sc) {
 
 // What a lane needs to find its fragments and its loads.
 struct Lane {
-    int wave, a_rd0, b_delta;
-    unsigned ld_voff0, ld_pass;
+    int wave, lane, a_rd0, b_delta, ld_row;
+    unsigned ld_voff0, ld_pass, ld_piece;
 };
 
 // One step: multiply set S (stage s), read stage s + 1 from buffer rd_buf into the other set,
@@ -212,7 +254,7 @@ struct Lane {
 // with the first twelve groups (their data is due at the next step's start), a load with every
 // other group: the path that takes the loads accepts one per wavefront every few tens of
 // cycles, so they are spread over the whole step.
-template <int S, bool FULL, bool HALF_IN>
+template <int S, bool FULL, bool HALF_IN, bool GATHER>
 __device__ __forceinline__ void step(const Geo& g, Loader& L, const Lane& ln, unsigned char* ring, Acc& acc,
                                      FragSet (&fr)[2], int& rd_buf, StoreCredit& sc, int mi_on) {
     const unsigned a_at = (unsigned)(rd_buf * C::STAGE_BYTES) + (unsigned)ln.a_rd0;
@@ -232,10 +274,10 @@ __device__ __forceinline__ void step(const Geo& g, Loader& L, const Lane& ln, un
         } else if (t < 12) {
             read_frag<S ^ 1>(fr, ring, t + 4, a_at, b_at);
         }
-        if (t & 1) issue_load(L, ring, ln.wave, ln.ld_voff0, ln.ld_pass, t >> 1);
+        if (t & 1) issue_load<GATHER>(L, ring, ln.wave, ln.ld_voff0, ln.ld_pass, t >> 1);
         __builtin_amdgcn_sched_barrier(0);
     }
-    issue_done(g, L);
+    issue_done<GATHER>(g, L, ln.wave, ln.lane, ln.ld_row, ln.ld_piece);
     rd_buf = rd_buf + 1 == C::RING ? 0 : rd_buf + 1;
     MOE_WAIT_LGKMCNT(0);
     wait_landed(sc);
@@ -298,13 +340,72 @@ __device__ __forceinline__ void epilogue(const Acc& acc, __amdgpu_buffer_rsrc_t 
     }
 }
 
-template <int EPI>
+// Scatter epilogue (top-1 routing: Alg. 1's step 6 folded into the second product).  The token and
+// the gate value of every row of a tile wait in LDS (rinfo[parity of the item][tokens | gates][row]);
+// they are fetched there by two small global -> LDS loads per wavefront during the item's first
+// steps: first the tokens of the tile's rows, then, indexed by them, the gate values.
+__device__ __forceinline__ void fetch_tokens(const Geo& g, int par, int row_begin, int rc, int wave, int lane) {
+    const __amdgpu_buffer_rsrc_t rt = make_rsrc(g.row_token + row_begin, (unsigned)(rc > 0 ? rc : 0) * 4u);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rt, (lds_void_t*)(g.rinfo + par * 2 * C::BM + wave * 64), 4,
+                                             (unsigned)(wave * 64 + lane) * 4u, 0, 0, 0);
+    if (!g.row_gate) ((float*)g.rinfo)[par * 2 * C::BM + C::BM + wave * 64 + lane] = 1.f;
+}
+__device__ __forceinline__ void fetch_gates(const Geo& g, int par, int wave, int lane) {
+    if (g.row_gate) {
+        const unsigned tok = (unsigned)g.rinfo[par * 2 * C::BM + wave * 64 + lane];
+        const __amdgpu_buffer_rsrc_t rg = make_rsrc(g.row_gate, (unsigned)g.out_rows * 4u);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rg, (lds_void_t*)(g.rinfo + par * 2 * C::BM + C::BM + wave * 64), 4, tok * 4u, 0, 0, 0);
+    }
+}
+__device__ __forceinline__ void epilogue_scatter(const Acc& acc, const Geo& g, __amdgpu_buffer_rsrc_t ry, int par, int rc,
+                                                 int lane_row, unsigned col_off, unsigned ld_bytes, int col0, int mi_on) {
+    // The tokens and gates of two row blocks are read before the first of their stores goes out:
+    // the compiler cannot tell these LDS reads from the targets of the global -> LDS loads and
+    // waits for every outstanding memory operation before each group of reads -- stores included.
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        unsigned voff[2][8];
+        float gate[2][8];
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int rr = lane_row + (half * 2 + m) * 64 + (j >> 2) * 16 + (j & 3);
+                const unsigned tok = (unsigned)g.rinfo[par * 2 * C::BM + rr];
+                gate[m][j] = ((const float*)g.rinfo)[par * 2 * C::BM + C::BM + rr];
+                // (a row past the tile's end gets an offset no output has: the range check drops it)
+                voff[m][j] = (rr < rc ? tok * ld_bytes : 0x80000000u) + col_off;
+            }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int mi = half * 2 + m;
+            if (mi >= mi_on) continue;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int a = j >> 2, r = j & 3;
+#pragma unroll
+                for (int ni = 0; ni < C::NI; ++ni) {
+                    const int col = col0 + ni * 32;
+                    if (col < g.N)
+                        store_pair<true>(ry, acc[mi][ni][a][0][r] * gate[m][j], acc[mi][ni][a][1][r] * gate[m][j], voff[m][j],
+                                         (unsigned)col * 4u);
+                }
+            }
+        }
+    }
+}
+
+template <int EPI, bool GATHER>
 __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint16_t* __restrict__ a_mat, int K, int N,
                                                         const void* const* __restrict__ w_ptrs,
                                                         const moe_tile* __restrict__ tiles,
                                                         const int32_t* __restrict__ hdr, void* __restrict__ out,
-                                                        int ld_out) {
-    constexpr bool HALF_IN = EPI == MOE_EPI_STORE;          // the second product: half operands, fp32 results
+                                                        int ld_out, const int32_t* __restrict__ row_token,
+                                                        const float* __restrict__ row_gate, int out_rows, int a_div) {
+    static_assert(!GATHER || EPI == MOE_EPI_RELU || EPI == MOE_EPI_SWIGLU, "gather: first product");
+    constexpr bool SCAT = EPI == MOE_EPI_SCATTER;
+    constexpr bool HALF_IN = EPI == MOE_EPI_STORE || SCAT;  // the second product: half operands, fp32 results
     constexpr int ES = HALF_IN ? 4 : 2;
     extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -319,6 +420,11 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint16_t* __restri
     g.a_mat = a_mat;
     g.w_ptrs = w_ptrs;
     g.tiles = tiles;
+    g.row_token = row_token;
+    g.row_gate = row_gate;
+    g.out_rows = out_rows;
+    g.a_div = a_div;
+    g.rinfo = (int*)(ring + C::SMEM - C::ROWINFO_BYTES);
     g.K = K;
     g.N = N;
     g.KT = K / C::BK;                                        // (even: K is a multiple of 64)
@@ -353,8 +459,11 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint16_t* __restri
 
     Lane ln;
     ln.wave = wave;
+    ln.lane = lane;
     const int ld_row = tid / C::PPR;
-    ln.ld_voff0 = (unsigned)ld_row * (unsigned)K * 2u + (unsigned)(((tid % C::PPR) ^ C::swz(ld_row)) << 4);
+    ln.ld_row = ld_row;
+    ln.ld_piece = (unsigned)(((tid % C::PPR) ^ C::swz(ld_row)) << 4);
+    ln.ld_voff0 = (unsigned)ld_row * (unsigned)K * 2u + ln.ld_piece;
     ln.ld_pass = (unsigned)sgpr(C::ROWS_PER_PASS * K * 2);
     // the B rows of lane l16 sit a wave-uniform distance behind its A rows
     ln.a_rd0 = (wm * 32 + l16) * C::ROW_BYTES + ((lq ^ C::swz(l16)) << 4);
@@ -369,11 +478,17 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint16_t* __restri
     L.item = first;
     L.kt = 0;
     L.buf = 0;
-    load_item(g, L, first);
+    L.seq = 0;
+    if constexpr (GATHER) {                                 // source rows of the first item: fetched and waited for
+        fetch_rows(g, 0, first, wave, lane);
+        MOE_WAIT_VMCNT(0);
+        __syncthreads();
+    }
+    load_item<GATHER>(g, L, first, wave, lane, ld_row, ln.ld_piece);
     for (int s = 0; s < C::RING; ++s) {
 #pragma unroll
-        for (int q = 0; q < C::LPS; ++q) issue_load(L, ring, wave, ln.ld_voff0, ln.ld_pass, q);
-        issue_done(g, L);
+        for (int q = 0; q < C::LPS; ++q) issue_load<GATHER>(L, ring, wave, ln.ld_voff0, ln.ld_pass, q);
+        issue_done<GATHER>(g, L, wave, lane, ld_row, ln.ld_piece);
     }
     MOE_WAIT_VMCNT((C::RING - 1) * C::LPS);
     wg_barrier();
@@ -388,7 +503,9 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint16_t* __restri
 
     const unsigned ld_bytes = (unsigned)ld_out * ES;
     const unsigned st_voff = (unsigned)(wm * 32 + 4 * lq) * ld_bytes + (unsigned)(2 * l16) * ES;
-    for (int item = first; item < g.n_items; item += g.stride) {
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(out, (unsigned)out_rows * ld_bytes);     // (scatter: the whole output)
+    int c_seq = 0;
+    for (int item = first; item < g.n_items; item += g.stride, ++c_seq) {
         int cb, ti;
         locate(g, item, ti, cb);
         const moe_tile tile = tiles[g.bin_start + ti];
@@ -397,20 +514,30 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint16_t* __restri
         // 32-row blocks of this wavefront that hold real rows (wave-uniform)
         int mi_on = ((rc + 31) / 32 - wm + 1) / 2;
         mi_on = mi_on < 0 ? 0 : (mi_on > C::MI ? C::MI : mi_on);
+        // (scatter: the token load is covered by the waits of the first two steps -- every step
+        // issues a stage of operand loads behind it -- and the barriers after them; the gate load
+        // likewise by the steps that follow it, long before the item ends: K / 32 >= 8 steps)
+        if constexpr (SCAT) fetch_tokens(g, c_seq & 1, tile.row_begin, rc, wave, lane);
         if (mi_on == C::MI) {
             for (int kt = 0; kt < g.KT; kt += 2) {
-                step<0, true, HALF_IN>(g, L, ln, ring, acc, fr, rd_buf, sc, mi_on);
-                step<1, true, HALF_IN>(g, L, ln, ring, acc, fr, rd_buf, sc, mi_on);
+                if constexpr (SCAT) { if (kt == 4) fetch_gates(g, c_seq & 1, wave, lane); }
+                step<0, true, HALF_IN, GATHER>(g, L, ln, ring, acc, fr, rd_buf, sc, mi_on);
+                step<1, true, HALF_IN, GATHER>(g, L, ln, ring, acc, fr, rd_buf, sc, mi_on);
             }
         } else {
             for (int kt = 0; kt < g.KT; kt += 2) {
-                step<0, false, HALF_IN>(g, L, ln, ring, acc, fr, rd_buf, sc, mi_on);
-                step<1, false, HALF_IN>(g, L, ln, ring, acc, fr, rd_buf, sc, mi_on);
+                if constexpr (SCAT) { if (kt == 4) fetch_gates(g, c_seq & 1, wave, lane); }
+                step<0, false, HALF_IN, GATHER>(g, L, ln, ring, acc, fr, rd_buf, sc, mi_on);
+                step<1, false, HALF_IN, GATHER>(g, L, ln, ring, acc, fr, rd_buf, sc, mi_on);
             }
         }
-        const __amdgpu_buffer_rsrc_t ro =
-            make_rsrc((const unsigned char*)out + (size_t)tile.row_begin * ld_bytes, (unsigned)(rc > 0 ? rc : 0) * ld_bytes);
-        epilogue<EPI>(acc, ro, st_voff, ld_bytes, N, col0, mi_on);
+        if constexpr (SCAT) {
+            epilogue_scatter(acc, g, ry, c_seq & 1, rc, wm * 32 + 4 * lq, (unsigned)(2 * l16) * 4u, ld_bytes, col0, mi_on);
+        } else {
+            const __amdgpu_buffer_rsrc_t ro =
+                make_rsrc((const unsigned char*)out + (size_t)tile.row_begin * ld_bytes, (unsigned)(rc > 0 ? rc : 0) * ld_bytes);
+            epilogue<EPI>(acc, ro, st_voff, ld_bytes, N, col0, mi_on);
+        }
         zero_acc(acc);
         // store instructions just issued (a lower bound is what the waits need)
         int cols = (N - col0 + 31) / 32;
@@ -421,17 +548,18 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(const uint16_t* __restri
     MOE_WAIT_VMCNT(0);                                      // (the trailing empty loads still target this LDS)
 }
 
-template <int EPI>
+template <int EPI, bool GATHER = false>
 int launch_wide(const void* a, int K, int N, const void* const* w, const moe_tile* tiles, const int32_t* hdr, void* out,
-                int ld_out, hipStream_t st) {
+                int ld_out, hipStream_t st, const int32_t* row_token = nullptr, const float* row_gate = nullptr,
+                int out_rows = 0, int a_div = 1) {
     const int dev_ok = moe_check_gemm_device();
     if (dev_ok != MOE_OK) return dev_ok;
-    auto kern = gemm_wide_kernel<EPI>;
+    auto kern = gemm_wide_kernel<EPI, GATHER>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)C::SMEM);
     if (e != hipSuccess) return moe_fail(MOE_ERR_HIP, "moe_grouped_ffn: shared memory attribute: %s", hipGetErrorString(e));
     hipLaunchKernelGGL(kern, dim3(MOE_GEMM_GRID), dim3(C::NTH), C::SMEM, st, (const uint16_t*)a, K, N, w, tiles, hdr, out,
-                       ld_out);
+                       ld_out, row_token, row_gate, out_rows, a_div);
     MOE_CHECK_LAUNCH("moe_grouped_ffn (bf16 GEMM, four wavefronts)");
     return MOE_OK;
 }
@@ -439,13 +567,24 @@ int launch_wide(const void* a, int K, int N, const void* const* w, const moe_til
 }  // namespace
 
 bool moe_gemm_wide_supports(int epi, int K) {
-    return (epi == MOE_EPI_RELU || epi == MOE_EPI_SWIGLU || epi == MOE_EPI_STORE) && K % 64 == 0 && K >= 256;
+    return epi >= MOE_EPI_RELU && epi <= MOE_EPI_SCATTER && K % 64 == 0 && K >= 256;
 }
 
 int moe_launch_gemm_wide(int epi, const void* a, int K, int N, const void* const* w, const moe_tile* tiles,
-                         const int32_t* hdr, void* out, int ld_out, hipStream_t st) {
+                         const int32_t* hdr, void* out, int ld_out, hipStream_t st, const int32_t* row_token,
+                         const float* row_gate, int out_rows) {
     if (epi == MOE_EPI_RELU) return launch_wide<MOE_EPI_RELU>(a, K, N, w, tiles, hdr, out, ld_out, st);
     if (epi == MOE_EPI_SWIGLU) return launch_wide<MOE_EPI_SWIGLU>(a, K, N, w, tiles, hdr, out, ld_out, st);
     if (epi == MOE_EPI_STORE) return launch_wide<MOE_EPI_STORE>(a, K, N, w, tiles, hdr, out, ld_out, st);
+    if (epi == MOE_EPI_SCATTER)
+        return launch_wide<MOE_EPI_SCATTER>(a, K, N, w, tiles, hdr, out, ld_out, st, row_token, row_gate, out_rows);
     return moe_fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn: epilogue %d in the four-wavefront kernel", epi);
+}
+
+int moe_launch_gemm_wide_gather(int epi, const void* x, int x_rows, int K, int N, const void* const* w,
+                                const moe_tile* tiles, const int32_t* hdr, void* out, int ld_out, hipStream_t st,
+                                const int32_t* row_src, int src_div) {
+    if (epi == MOE_EPI_SWIGLU)
+        return launch_wide<MOE_EPI_SWIGLU, true>(x, K, N, w, tiles, hdr, out, ld_out, st, row_src, nullptr, x_rows, src_div);
+    return launch_wide<MOE_EPI_RELU, true>(x, K, N, w, tiles, hdr, out, ld_out, st, row_src, nullptr, x_rows, src_div);
 }

@@ -102,11 +102,13 @@ class MoELayer:
         self.y_perm = torch.empty((A, d), dtype=f32, device=dev)
         self.y = torch.empty((T, d), dtype=f32, device=dev)
         self.shared_F = shared_F
-        # top-1 routing without a shared expert: step 6 is folded into the second GEMM (128-row tiles;
-        # the 256-row kernel has no registers left for it)
-        self.fold_combine = (k == 1 and self.dt == B.MOE_BF16 and not shared_F and self.tile_m == 128 and F >= 512)
+        # 256-row tiles: the library folds the gather and the scatter into the products of its
+        # four-wavefront kernels (its default); its eight-wavefront kernels have no gather at this height
+        tall_ok = self.tile_m == 128 or (B.moe_ffn_kernel_mode(-1) != 1 and d >= 256 and F >= 256)
+        # top-1 routing without a shared expert: step 6 is folded into the second GEMM
+        self.fold_combine = (k == 1 and self.dt == B.MOE_BF16 and not shared_F and tall_ok and F >= 512)
         # the row gather inside the first product (moe_grouped_ffn_fused): where the library offers it
-        can_fuse = (self.dt == B.MOE_BF16 and self.tile_m == 128 and d >= 256 and d % 64 == 0 and F % 64 == 0
+        can_fuse = (self.dt == B.MOE_BF16 and tall_ok and d >= 256 and d % 64 == 0 and F % 64 == 0
                     and T * d * 2 < 2 ** 32 and (k > 1 or self.fold_combine))
         self.fuse_gather = can_fuse if fuse_gather is None else (fuse_gather and can_fuse)
         if shared_F:
@@ -389,8 +391,8 @@ class PreRoutedShare:
         # one row per expert (k = 1): where the library offers it, the first product gathers its rows
         # from x and the second one writes every row to its place in y (moe_grouped_ffn_fused), so
         # that no gather precedes the groups and no combine follows the last one
-        self.fused = (self.dt == B.MOE_BF16 and self.tile_m == 128 and d >= 256 and d % 64 == 0 and F >= 512
-                      and F % 64 == 0 and T * d * 4 < 2 ** 31)
+        self.fused = (self.dt == B.MOE_BF16 and (self.tile_m == 128 or B.moe_ffn_kernel_mode(-1) != 1)
+                      and d >= 256 and d % 64 == 0 and F >= 512 and F % 64 == 0 and T * d * 4 < 2 ** 31)
         dev, i32, f32 = self.device, torch.int32, torch.float32
         es = 2 if dtype == "bf16" else 4
         self.rows_in = 2 * F if self.act == B.MOE_SWIGLU else F

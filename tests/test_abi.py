@@ -186,7 +186,12 @@ def test_pack_combine_copy_argument_errors():
                   128, FAKE, FAKE, None, FAKE, 0) == B.MOE_ERR_ARG
     fused = lambda dt=B.MOE_BF16, T=8, d=256, F=512, k=1, tile_m=128, perm=FAKE, y=FAKE: status(
         B.moe_grouped_ffn_fused, FAKE, T, d, F, 2, k, B.MOE_RELU, dt, FAKE, FAKE, FAKE, FAKE, tile_m, FAKE, perm, None, y, 0)
-    assert fused(dt=B.MOE_F32) == B.MOE_ERR_UNSUPPORTED and fused(tile_m=256) == B.MOE_ERR_UNSUPPORTED
+    assert fused(dt=B.MOE_F32) == B.MOE_ERR_UNSUPPORTED and fused(tile_m=64) == B.MOE_ERR_UNSUPPORTED
+    before = B.moe_ffn_kernel_mode(1)        # 256-row tiles: only the four-wavefront kernels gather
+    try:
+        assert fused(tile_m=256) == B.MOE_ERR_UNSUPPORTED
+    finally:
+        B.moe_ffn_kernel_mode(before)
     assert fused(d=192) == B.MOE_ERR_UNSUPPORTED and fused(F=448) == B.MOE_ERR_UNSUPPORTED       # top-1 needs F >= 512
     assert fused(T=2 ** 24, d=256) == B.MOE_ERR_UNSUPPORTED                                        # x of 8 GiB
     assert fused(k=0) == B.MOE_ERR_ARG and fused(perm=None) == B.MOE_ERR_ARG and fused(y=None) == B.MOE_ERR_ARG

@@ -537,30 +537,42 @@ WIDE_CASES = [
 
 @pytest.mark.parametrize("T,d,F,E,k,act,skew", WIDE_CASES)
 def test_four_wavefront_kernels_give_the_bits_of_the_lds_ring_kernels(torch_gpu, T, d, F, E, k, act, skew):
-    """256-row tiles: the kernels of four wavefronts (the default, mode 0) and the LDS-ring kernels
-    of eight (moe_ffn_kernel_mode 1) must give identical hidden activations and outputs, and the
-    layer must agree with the oracle."""
+    """256-row tiles: the kernels of four wavefronts (the default, mode 0: the layer then folds the
+    row gather into the first product and, for top-1, the combine into the second) and the LDS-ring
+    kernels of eight (moe_ffn_kernel_mode 1: separate gather and combine) must give identical
+    hidden activations and outputs, and the layer must agree with the oracle."""
     torch = torch_gpu
     from paper_2506_12417_amd import binding as B
     wl = W.WORKLOADS["c4"].scaled(T=T, d=d, F=F, E=E, k=k, act=act, skew=skew)
     _note("wide vs ring T=%d d=%d F=%d E=%d k=%d %s %s" % (T, d, F, E, k, act, skew))
     inp = W.make_inputs(wl)
-    layer = make_layer(wl, inp, tile_m=256)
-    x = layer_x(layer, inp)
     before = B.moe_ffn_kernel_mode(-1)
     try:
         out = {}
         for mode in (1, 0):
             B.moe_ffn_kernel_mode(mode)
+            layer = make_layer(wl, inp, tile_m=256)           # (the layer asks the library which fusions it offers)
+            assert layer.fuse_gather == (mode == 0 and d >= 256 and (k > 1 or F >= 512))
+            x = layer_x(layer, inp)
             layer.h.fill_(float("nan"))
             layer.y.fill_(float("nan"))
             layer.y_perm.fill_(float("nan"))
             y = layer.forward(x).clone()
             torch.cuda.synchronize()
-            out[mode] = (y, layer.h.clone(), layer.y_perm.clone())
-        for a, b_, name in zip(out[1], out[0], ("y", "H", "y_perm")):
-            assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a.view(torch.int16),
-                               b_.view(torch.int32) if b_.dtype == torch.float32 else b_.view(torch.int16)), name
+            out[mode] = (y, layer.h.clone()) + ((layer.y_perm.clone(),) if k > 1 else ())
+            if mode == 0:                                     # the plain entry point with the same kernels
+                layer.h.fill_(float("nan"))
+                layer.y_perm.fill_(float("nan"))
+                layer.permute(x)
+                layer.plan()
+                layer.ffn()
+                layer.combine(True)
+                torch.cuda.synchronize()
+                out[2] = (layer.y.clone(), layer.h.clone()) + ((layer.y_perm.clone(),) if k > 1 else ())
+        for other in (0, 2):
+            for a, b_, name in zip(out[1], out[other], ("y", "H", "y_perm")):
+                assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a.view(torch.int16),
+                                   b_.view(torch.int32) if b_.dtype == torch.float32 else b_.view(torch.int16)), (name, other)
     finally:
         B.moe_ffn_kernel_mode(before)
     idx_o, w_o, _ = O.route_topk(inp["x"], inp["W_g"], inp["b"], wl.k, wl.renorm)
