@@ -386,15 +386,21 @@ def main():
     # the binding roof of the first grouped GEMM: weights stream from HBM when the experts hold
     # few rows each (c2), the matrix cores bind when rows per expert are many (c3, c4)
     t_hbm, t_mfma = g1_bytes / (HBM_PEAK_GBS * 1e9), g1_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    # (256-row tiles run on the four-wavefront kernels unless the LDS ring is asked for)
+    g1_kernel = "gemm_wide_kernel<G1>" if layer.tile_m == 256 and args.ffn_kernels != "ring" else "gemm_bf16_kernel<G1>"
     if t_hbm >= t_mfma:
-        roofline = {"kernel": "gemm_bf16_kernel<G1>", "bound": "hbm", "achieved": round(g1_gbs, 1), "peak": HBM_PEAK_GBS,
+        roofline = {"kernel": g1_kernel, "bound": "hbm", "achieved": round(g1_gbs, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(g1_gbs / HBM_PEAK_GBS, 4), "traffic": None,
                     "mfma_frac": round(g1_tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
     else:
-        roofline = {"kernel": "gemm_bf16_kernel<G1>", "bound": "mfma", "achieved": round(g1_tflops, 1),
+        roofline = {"kernel": g1_kernel, "bound": "mfma", "achieved": round(g1_tflops, 1),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(g1_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                     "traffic": None, "hbm_frac": round(g1_gbs / HBM_PEAK_GBS, 4)}
     roofline["traffic"] = measured_traffic(args.workload)
+    # (hardware counters cannot be read from inside this run: the figure is the committed summary's)
+    roofline["traffic_source"] = (None if roofline["traffic"] is None else
+                                  "profiles/bench_%s_hbm_traffic.txt: rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier "
+                                  "run of this command, not measured in this run" % args.workload)
     roofline["algorithmic_bytes"] = int(g1_bytes)
     roofline["algorithmic_flops"] = int(g1_flops)
     roofline["avg_launch_ms"] = round(g1_ms, 4)
