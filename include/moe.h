@@ -210,16 +210,18 @@ MOE_API int moe_plan_tiles_subset(const int32_t* counts, const int32_t* offsets,
  *
  *   S[g_from, e, g_to] = tokens that GPU g_from sends to GPU g_to for expert e  (S_initial from
  *   Alg. 1 step 3: everything goes to the expert's home GPU).
- *   t_g = sum over g_from, e of S[., ., g];  t_avg = floor(sum S / G).  While some t_g > t_avg:
- *   g_max = argmax t_g; g_from = the source sending most to g_max; e_max = its largest expert
- *   block there, t_move its size; stop if t_move < q; g_min = argmin t_g; stop if g_min = g_max
- *   or t_g[g_min] + q > t_avg; move t_s = min(t_move, t_avg - t_g[g_min]) tokens of that block
- *   from g_max to g_min.  argmax / argmin take the lowest index among equals.
+ *   A GPU's load is everything addressed to it; the target is the floor of the mean load.  One
+ *   move takes tokens off the most loaded GPU: of the sources that send to it, the one sending
+ *   most (summed over experts), and of that source's blocks there the largest; they go to the
+ *   least loaded GPU, as many as bring it up to the target, at most the whole block.  No move is
+ *   made -- and the schedule is final -- once no GPU is above the target, once that largest block
+ *   is smaller than q, or once the least loaded GPU has room for fewer than q tokens (or is the
+ *   most loaded one itself).  Equal values: the lowest index, in every choice.
  *
  *   s_initial [G_src, E, G] int32 (device)     s_out [G_src, E, G] int32 (device; may alias s_initial)
- *   info [4 + MOE_MAX_BINS] int32 (device) or NULL: [0] moves made, [1] t_avg, [2] why the loop
+ *   info [4 + MOE_MAX_BINS] int32 (device) or NULL: [0] moves made, [1] the target, [2] why the loop
  *        ended (0 no GPU above the average, 1 block below q, 2 no room on the least loaded GPU,
- *        3 iteration cap), [4 ..] t_g afterwards
+ *        3 iteration cap), [4 ..] the GPUs' loads afterwards
  * Requires G_src, G <= MOE_MAX_BINS, E <= MOE_MAX_EXPERTS, q_tokens >= 1 and S at most 128 KiB.
  * Entries must be non-negative with a total below 2^26.
  */

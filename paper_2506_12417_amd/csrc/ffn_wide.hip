@@ -23,6 +23,9 @@
 // have between two and three steps to arrive.  A work-group's items form one stream of stages:
 // the loads cross item boundaries, and past the last item they go on with empty descriptors.
 // An item's results are converted and stored between its last step and the next item's first.
+// As in ffn_bf16.hip the first product can fetch its rows from x through the sort's permutation
+// (Alg. 1's step 4 done by the operand loads) and, for top-1 routing, the second can write every
+// row to its token's place times its gate value (step 6 done by the epilogue).
 //
 // The code is written as plain functions over explicit state (no lambdas that capture other
 // lambdas): a closure is an object in memory that holds pointers, a chain of them is only
