@@ -525,18 +525,20 @@ def test_streaming_kernels_give_the_bits_of_the_lds_ring_kernels(torch_gpu, T, d
 
 
 WIDE_CASES = [
-    # T, d, F, E, k, act, skew: the four-wavefront kernels for 256-row tiles against the LDS-ring kernels
-    (3000, 256, 512, 4, 2, "swiglu", "hot"),          # full and ragged tiles, several column blocks
-    (5000, 768, 3072, 6, 1, "relu", "zipf"),          # c5's shapes
-    (2500, 512, 1408, 3, 2, "swiglu", "zipf"),        # F not a multiple of the column block: ragged last block in the first product
-    (1100, 320, 704, 5, 1, "relu", "uniform"),        # d not a multiple of the column block: ragged last block in the second product
-    (40, 256, 256, 2, 1, "swiglu", "uniform"),        # every tile a few rows: whole row blocks skipped
-    (1, 256, 256, 1, 1, "relu", "uniform"),           # a single row
+    # T, d, F, E, k, act, skew, bins: the four-wavefront kernels for 256-row tiles against the LDS-ring kernels
+    (3000, 256, 512, 4, 2, "swiglu", "hot", 8),       # full and ragged tiles, several column blocks
+    (5000, 768, 3072, 6, 1, "relu", "zipf", 8),       # c5's shapes
+    (2500, 512, 1408, 3, 2, "swiglu", "zipf", 8),     # F not a multiple of the column block: ragged last block in the first product
+    (1100, 320, 704, 5, 1, "relu", "uniform", 8),     # d not a multiple of the column block: ragged last block in the second product
+    (40, 256, 256, 2, 1, "swiglu", "uniform", 8),     # every tile a few rows: whole row blocks skipped
+    (1, 256, 256, 1, 1, "relu", "uniform", 8),        # a single row
+    (70000, 256, 512, 3, 1, "relu", "hot", 1),        # one bin: all 256 work-groups on one list, more items than work-groups
+    (9000, 512, 512, 7, 2, "swiglu", "zipf", 3),      # three bins: work-groups dealt unevenly (86, 85, 85)
 ]
 
 
-@pytest.mark.parametrize("T,d,F,E,k,act,skew", WIDE_CASES)
-def test_four_wavefront_kernels_give_the_bits_of_the_lds_ring_kernels(torch_gpu, T, d, F, E, k, act, skew):
+@pytest.mark.parametrize("T,d,F,E,k,act,skew,bins", WIDE_CASES)
+def test_four_wavefront_kernels_give_the_bits_of_the_lds_ring_kernels(torch_gpu, T, d, F, E, k, act, skew, bins):
     """256-row tiles: the kernels of four wavefronts (the default, mode 0: the layer then folds the
     row gather into the first product and, for top-1, the combine into the second) and the LDS-ring
     kernels of eight (moe_ffn_kernel_mode 1: separate gather and combine) must give identical
@@ -544,14 +546,14 @@ def test_four_wavefront_kernels_give_the_bits_of_the_lds_ring_kernels(torch_gpu,
     torch = torch_gpu
     from paper_2506_12417_amd import binding as B
     wl = W.WORKLOADS["c4"].scaled(T=T, d=d, F=F, E=E, k=k, act=act, skew=skew)
-    _note("wide vs ring T=%d d=%d F=%d E=%d k=%d %s %s" % (T, d, F, E, k, act, skew))
+    _note("wide vs ring T=%d d=%d F=%d E=%d k=%d %s %s bins=%d" % (T, d, F, E, k, act, skew, bins))
     inp = W.make_inputs(wl)
     before = B.moe_ffn_kernel_mode(-1)
     try:
         out = {}
         for mode in (1, 0):
             B.moe_ffn_kernel_mode(mode)
-            layer = make_layer(wl, inp, tile_m=256)           # (the layer asks the library which fusions it offers)
+            layer = make_layer(wl, inp, tile_m=256, n_bins=bins)   # (the layer asks the library which fusions it offers)
             assert layer.fuse_gather == (mode == 0 and d >= 256 and (k > 1 or F >= 512))
             x = layer_x(layer, inp)
             layer.h.fill_(float("nan"))
